@@ -1,0 +1,476 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix (no GPU).
+
+Each test checks the oracle against something that is not the oracle: a closed form, an
+invariant of the method, a dense linear-algebra construction, an independent float64
+library routine (torch CPU), finite differences, or a scalar brute-force re-derivation.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import mgrit_oracle as O
+
+DENSE, CONV = O.DENSE, O.CONV
+TANH, RELU, IDENT = O.TANH, O.RELU, O.IDENT
+
+
+def _dense_problem(rng, N, q, B, bias=True, scale=1.0):
+    W = rng.standard_normal((N, q, q)) * scale / math.sqrt(q)
+    b = rng.standard_normal((N, q)) * 0.3 if bias else np.zeros((N, q))
+    u0 = rng.standard_normal((B, q))
+    return W, b, u0
+
+
+def _conv_problem(rng, N, C, B, H, Wd):
+    K = rng.standard_normal((N, C, 3, 3, C)) * math.sqrt(2.0 / (9 * C))
+    b = rng.standard_normal((N, C)) * 0.3
+    u0 = rng.standard_normal((B, H, Wd, C))
+    return K, b, u0
+
+
+# ---------------------------------------------------------------------------------------
+# Layer step against an independent float64 library routine (Sec. II, Eq. (1))
+# ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("kind", [TANH, RELU])
+def test_dense_step_matches_torch(kind):
+    rng = np.random.default_rng(1)
+    W, b, u0 = _dense_problem(rng, 1, 7, 5)
+    got = O.step(u0, W[0], b[0], 0.37, DENSE, kind)
+    z = torch.nn.functional.linear(torch.from_numpy(u0), torch.from_numpy(W[0]), torch.from_numpy(b[0]))
+    f = torch.tanh(z) if kind == TANH else torch.relu(z)
+    ref = torch.from_numpy(u0) + 0.37 * f
+    np.testing.assert_allclose(got, ref.numpy(), rtol=1e-13, atol=1e-13)
+
+
+@pytest.mark.parametrize("kind", [TANH, RELU])
+def test_conv_step_matches_torch_conv2d(kind):
+    rng = np.random.default_rng(2)
+    K, b, u0 = _conv_problem(rng, 1, 3, 2, 5, 6)      # non-square image, C_in = C_out = 3
+    got = O.step(u0, K[0], b[0], 0.21, CONV, kind)
+    x = torch.from_numpy(u0).permute(0, 3, 1, 2)        # NCHW
+    w = torch.from_numpy(K[0]).permute(0, 3, 1, 2)      # [Co, Ci, 3, 3]
+    z = torch.nn.functional.conv2d(x, w, torch.from_numpy(b[0]), padding=1)
+    f = torch.tanh(z) if kind == TANH else torch.relu(z)
+    ref = (x + 0.21 * f).permute(0, 2, 3, 1)
+    np.testing.assert_allclose(got, ref.numpy(), rtol=1e-13, atol=1e-13)
+
+
+def test_conv_affine_brute_force_asymmetric_kernel():
+    """Zero padding, cross-correlation orientation and the [Co,3,3,Ci] layout by explicit loops."""
+    rng = np.random.default_rng(3)
+    Co, Ci, H, Wd = 2, 3, 4, 3
+    K = rng.standard_normal((Co, 3, 3, Ci))
+    b = rng.standard_normal(Co)
+    u = rng.standard_normal((1, H, Wd, Ci))
+    z = O.affine(u, K, b, CONV)
+    for y in range(H):
+        for x in range(Wd):
+            for o in range(Co):
+                s = b[o]
+                for dy in range(3):
+                    for dx in range(3):
+                        yy, xx = y + dy - 1, x + dx - 1
+                        if 0 <= yy < H and 0 <= xx < Wd:
+                            s += float(K[o, dy, dx, :] @ u[0, yy, xx, :])
+                assert abs(z[0, y, x, o] - s) < 1e-12
+
+
+# ---------------------------------------------------------------------------------------
+# Linear F: closed-form propagator
+# ---------------------------------------------------------------------------------------
+def test_linear_diagonal_closed_form():
+    N, q, h = 20, 4, 0.05
+    lam = np.array([-1.0, 0.5, 2.0, -3.0])
+    W = np.tile(np.diag(lam), (N, 1, 1))
+    b = np.zeros((N, q))
+    u0 = np.array([[1.0, -2.0, 0.5, 3.0]])
+    U = O.serial_forward(W, b, u0, h, DENSE, IDENT)
+    for n in range(N + 1):
+        np.testing.assert_allclose(U[n], u0 * (1 + h * lam) ** n, rtol=1e-13)
+
+
+def test_linear_product_of_propagators():
+    rng = np.random.default_rng(4)
+    N, q, h = 6, 3, 0.2
+    W, b, u0 = _dense_problem(rng, N, q, 2, bias=False)
+    U = O.serial_forward(W, b, u0, h, DENSE, IDENT)
+    P = np.eye(q)
+    for n in range(N):
+        P = (np.eye(q) + h * W[n]) @ P
+    np.testing.assert_allclose(U[N], u0 @ P.T, rtol=1e-12, atol=1e-13)
+
+
+# ---------------------------------------------------------------------------------------
+# Two-level exactness (Sec. III-C, Alg. 1): with F-relaxation the first k coarse intervals
+# are exact after k cycles, for any initial guess; FCF advances two intervals per cycle.
+# ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("layer", [DENSE, CONV])
+@pytest.mark.parametrize("relax,per_cycle", [(O.RELAX_F, 1), (O.RELAX_FCF, 2)])
+def test_two_level_exact_after_enough_cycles(layer, relax, per_cycle):
+    rng = np.random.default_rng(5)
+    N, m = 12, 3
+    h = 1.0 / N
+    if layer == DENSE:
+        W, b, u0 = _dense_problem(rng, N, 5, 3, scale=2.0)
+    else:
+        W, b, u0 = _conv_problem(rng, N, 2, 2, 4, 3)
+    Us = O.serial_forward(W, b, u0, h, layer, TANH)
+    Uinit = rng.standard_normal(Us.shape)
+    for k in range(1, N // m + 1):
+        U, hist, it = O.fas_forward(W, b, u0, h, m, 2, 1, relax, k, layer, TANH, init=2, U_init=Uinit)
+        assert it == k and len(hist) == k
+        exact_upto = min(N, (per_cycle * k + 1) * m - 1)     # all points of the exact intervals
+        err = np.abs(U[:exact_upto + 1] - Us[:exact_upto + 1]).max()
+        assert err < 1e-12, (k, err)
+        if per_cycle * k * m < N:                            # and the rest is NOT yet exact
+            assert np.abs(U[-1] - Us[-1]).max() > 1e-8
+    assert np.abs(U - Us).max() < 1e-12
+
+
+def test_config1_shape_is_exact_after_four_cycles():
+    """N=16, m=4, two levels, F-relaxation, 4 cycles reproduces serial propagation."""
+    rng = np.random.default_rng(0)
+    W, b, u0 = _dense_problem(rng, 16, 8, 4)
+    Us = O.serial_forward(W, b, u0, 1 / 16, DENSE, TANH)
+    U, hist, _ = O.fas_forward(W, b, u0, 1 / 16, 4, 2, 1, O.RELAX_F, 4, DENSE, TANH)
+    assert np.abs(U - Us).max() < 1e-13
+    U3, _, _ = O.fas_forward(W, b, u0, 1 / 16, 4, 2, 1, O.RELAX_F, 3, DENSE, TANH)
+    assert np.abs(U3 - Us).max() > 1e-9
+
+
+# ---------------------------------------------------------------------------------------
+# Fixed point (Sec. III-A): at the exact solution the residual vanishes and nothing changes
+# ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("levels", [2, 3])
+@pytest.mark.parametrize("relax", [O.RELAX_F, O.RELAX_FCF])
+def test_fixed_point(levels, relax):
+    rng = np.random.default_rng(6)
+    N, m = 16, 2
+    W, b, u0 = _dense_problem(rng, N, 4, 2, scale=2.0)
+    Us = O.serial_forward(W, b, u0, 1 / N, DENSE, RELU)
+    U, hist, _ = O.fas_forward(W, b, u0, 1 / N, m, levels, 1, relax, 2, DENSE, RELU, init=2, U_init=Us)
+    assert max(hist) < 1e-13
+    assert np.abs(U - Us).max() < 1e-13
+
+
+# ---------------------------------------------------------------------------------------
+# Linear F: one two-level FAS cycle equals the textbook linear two-grid correction scheme
+# assembled as dense matrices (Sec. III-A, Eq. (9)-(11))
+# ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("relax", [O.RELAX_F, O.RELAX_FCF])
+def test_linear_two_level_equals_dense_two_grid(relax):
+    rng = np.random.default_rng(7)
+    N, m, q, h = 8, 2, 2, 0.3
+    W, b, u0 = _dense_problem(rng, N, q, 1, bias=False, scale=1.5)
+    n = (N + 1) * q
+    Phi = [np.eye(q) + h * W[k] for k in range(N)]
+    A = np.eye(n)
+    for k in range(N):
+        A[(k + 1) * q:(k + 2) * q, k * q:(k + 1) * q] = -Phi[k]
+    f = np.zeros(n)
+    f[:q] = u0[0]
+    Nc = N // m
+    AH = np.eye((Nc + 1) * q)
+    for i in range(Nc):
+        AH[(i + 1) * q:(i + 2) * q, i * q:(i + 1) * q] = -(np.eye(q) + m * h * W[i * m])
+    cidx = np.concatenate([np.arange(i * m * q, i * m * q + q) for i in range(Nc + 1)])
+
+    Uinit = rng.standard_normal((N + 1, 1, q))
+    x = Uinit.reshape(-1).copy()
+    x[:q] = u0[0]
+
+    def f_relax(x):                       # exact solve of the F-rows given the C-values
+        x = x.copy()
+        for i in range(Nc):
+            for k in range(1, m):
+                j = i * m + k
+                x[j * q:(j + 1) * q] = Phi[j - 1] @ x[(j - 1) * q:j * q]
+        return x
+
+    def c_relax(x):
+        x = x.copy()
+        for i in range(1, Nc + 1):
+            j = i * m
+            x[j * q:(j + 1) * q] = Phi[j - 1] @ x[(j - 1) * q:j * q]
+        return x
+
+    x = f_relax(x)
+    if relax == O.RELAX_FCF:
+        x = f_relax(c_relax(x))
+    r = f - A @ x
+    rnorm = np.linalg.norm(r[cidx])
+    assert np.abs(np.delete(r, cidx)).max() < 1e-13        # F-rows have zero residual
+    delta = np.linalg.solve(AH, r[cidx])                      # L_H dU_H = I r_h
+    x[cidx] += delta                                          # u += I_H^h dU_H (C-points)
+    x = f_relax(x)
+
+    U, hist, _ = O.fas_forward(W, b, u0, h, m, 2, 1, relax, 1, DENSE, IDENT, init=2, U_init=Uinit)
+    np.testing.assert_allclose(U.reshape(-1), x, rtol=1e-11, atol=1e-12)
+    assert abs(hist[0] - rnorm) < 1e-12 * max(1.0, rnorm)
+
+
+# ---------------------------------------------------------------------------------------
+# Brute force on a tiny nonlinear scalar instance: an independent pure-Python evaluation of the
+# system rows checks the coarse equation L_H(V) = L_H(Ubar) + R_H and the residual norm
+# ---------------------------------------------------------------------------------------
+def test_scalar_brute_force_coarse_equation_and_norm():
+    rng = np.random.default_rng(8)
+    N, m, h = 8, 2, 0.25
+    w = rng.standard_normal(N) * 1.5
+    bb = rng.standard_normal(N) * 0.5
+    y0 = 0.7
+    x = list(rng.standard_normal(N + 1))
+    x[0] = y0
+
+    def F(n, u):
+        return math.tanh(w[n] * u + bb[n])
+
+    # F-relaxation by hand
+    for i in range(N // m):
+        for k in range(1, m):
+            j = i * m + k
+            x[j] = x[j - 1] + h * F(j - 1, x[j - 1])
+    # rows of f_h - L_h(x)
+    R = [y0 - x[0]] + [-(x[n] - x[n - 1] - h * F(n - 1, x[n - 1])) for n in range(1, N + 1)]
+    Nc = N // m
+    ubar = [x[i * m] for i in range(Nc + 1)]
+    H = m * h
+    LH_ubar = [ubar[0]] + [ubar[i] - ubar[i - 1] - H * F((i - 1) * m, ubar[i - 1]) for i in range(1, Nc + 1)]
+    S = [LH_ubar[i] + R[i * m] for i in range(Nc + 1)]
+
+    W = w.reshape(N, 1, 1)
+    b = bb.reshape(N, 1)
+    u0 = np.array([[y0]])
+    Uinit = np.array(x).reshape(N + 1, 1, 1)
+    # the hand-relaxed x is a fixed point of the oracle's opening F-relaxation, so the cycle
+    # sees exactly this iterate
+    U, hist, _ = O.fas_forward(W, b, u0, h, m, 2, 1, O.RELAX_F, 1, DENSE, TANH, init=2, U_init=Uinit)
+    V = [float(U[i * m, 0, 0]) for i in range(Nc + 1)]
+    LH_V = [V[0]] + [V[i] - V[i - 1] - H * F((i - 1) * m, V[i - 1]) for i in range(1, Nc + 1)]
+    for i in range(Nc + 1):
+        assert abs(LH_V[i] - S[i]) < 1e-13, i
+    assert abs(hist[0] - math.sqrt(sum(R[i * m] ** 2 for i in range(Nc + 1)))) < 1e-13
+    # all-points residual norm of an arbitrary iterate
+    xr = list(rng.standard_normal(N + 1))
+    Rall = [y0 - xr[0]] + [-(xr[n] - xr[n - 1] - h * F(n - 1, xr[n - 1])) for n in range(1, N + 1)]
+    got = O.residual_norm(W, b, u0, np.array(xr).reshape(N + 1, 1, 1), h, DENSE, TANH)
+    assert abs(got - math.sqrt(sum(r * r for r in Rall))) < 1e-13
+    got_rms = O.residual_norm(W, b, u0, np.array(xr).reshape(N + 1, 1, 1), h, DENSE, TANH, norm_kind=1)
+    assert abs(got_rms - math.sqrt(sum(r * r for r in Rall) / (N + 1))) < 1e-13
+
+
+# ---------------------------------------------------------------------------------------
+# Multilevel: converges to serial propagation, the limit the iteration is defined by
+# ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("layer", [DENSE, CONV])
+def test_three_level_converges_to_serial(layer):
+    rng = np.random.default_rng(9)
+    N, m = 32, 2
+    if layer == DENSE:
+        W, b, u0 = _dense_problem(rng, N, 6, 3)
+    else:
+        W, b, u0 = _conv_problem(rng, N, 2, 1, 4, 4)
+    Us = O.serial_forward(W, b, u0, 1 / N, layer, TANH)
+    U, hist, it = O.fas_forward(W, b, u0, 1 / N, m, 3, 1, O.RELAX_FCF, 30, layer, TANH, tol=1e-13)
+    assert it < 30 and hist[-1] <= 1e-13
+    assert np.abs(U - Us).max() < 1e-11
+    assert all(hist[i + 1] < hist[i] for i in range(len(hist) - 1))
+
+
+def test_three_levels_with_coarsest_of_full_depth_equals_two_level():
+    """max_levels=3 but min_coarse stops coarsening after one level -> identical to two-level."""
+    rng = np.random.default_rng(10)
+    N, m = 16, 4
+    W, b, u0 = _dense_problem(rng, N, 4, 2)
+    a = O.fas_forward(W, b, u0, 1 / N, m, 3, 4, O.RELAX_FCF, 2, DENSE, TANH)
+    c = O.fas_forward(W, b, u0, 1 / N, m, 2, 1, O.RELAX_FCF, 2, DENSE, TANH)
+    assert np.array_equal(a[0], c[0]) and a[1] == c[1]
+
+
+def test_single_level_is_serial_propagation():
+    rng = np.random.default_rng(11)
+    W, b, u0 = _dense_problem(rng, 7, 3, 2)
+    U, hist, it = O.fas_forward(W, b, u0, 0.1, 2, 1, 1, O.RELAX_F, 5, DENSE, RELU)
+    assert np.array_equal(U, O.serial_forward(W, b, u0, 0.1, DENSE, RELU)) and it == 1
+
+
+# ---------------------------------------------------------------------------------------
+# Serial gradient against finite differences and automatic differentiation
+# ---------------------------------------------------------------------------------------
+def _loss_np(W, b, u0, h, layer, kind, Cw):
+    return float(np.sum(Cw * O.serial_forward(W, b, u0, h, layer, kind)[-1]))
+
+
+@pytest.mark.parametrize("layer", [DENSE, CONV])
+def test_serial_gradient_vs_finite_differences(layer):
+    rng = np.random.default_rng(12)
+    N, h = 5, 0.2
+    if layer == DENSE:
+        W, b, u0 = _dense_problem(rng, N, 4, 3, scale=1.5)
+    else:
+        W, b, u0 = _conv_problem(rng, N, 2, 2, 3, 4)
+    Cw = rng.standard_normal(u0.shape)                   # loss = <Cw, u^N>  ->  lam^N = Cw
+    U = O.serial_forward(W, b, u0, h, layer, TANH)
+    Lam, dW, db = O.serial_backward(W, b, U, Cw, h, layer, TANH)
+    eps = 1e-6
+    for _ in range(12):
+        idx = tuple(rng.integers(0, s) for s in W.shape)
+        Wp, Wm = W.copy(), W.copy()
+        Wp[idx] += eps
+        Wm[idx] -= eps
+        fd = (_loss_np(Wp, b, u0, h, layer, TANH, Cw) - _loss_np(Wm, b, u0, h, layer, TANH, Cw)) / (2 * eps)
+        assert abs(fd - dW[idx]) <= 1e-6 * max(1.0, abs(fd)), (idx, fd, dW[idx])
+    for _ in range(6):
+        idx = tuple(rng.integers(0, s) for s in b.shape)
+        bp, bm = b.copy(), b.copy()
+        bp[idx] += eps
+        bm[idx] -= eps
+        fd = (_loss_np(W, bp, u0, h, layer, TANH, Cw) - _loss_np(W, bm, u0, h, layer, TANH, Cw)) / (2 * eps)
+        assert abs(fd - db[idx]) <= 1e-6 * max(1.0, abs(fd))
+    for _ in range(6):                                   # lam^0 = dLoss/du^0
+        idx = tuple(rng.integers(0, s) for s in u0.shape)
+        up, um = u0.copy(), u0.copy()
+        up[idx] += eps
+        um[idx] -= eps
+        fd = (_loss_np(W, b, up, h, layer, TANH, Cw) - _loss_np(W, b, um, h, layer, TANH, Cw)) / (2 * eps)
+        assert abs(fd - Lam[0][idx]) <= 1e-6 * max(1.0, abs(fd))
+
+
+@pytest.mark.parametrize("layer,kind", [(DENSE, TANH), (DENSE, RELU), (CONV, TANH), (CONV, RELU)])
+def test_serial_gradient_vs_autograd(layer, kind):
+    rng = np.random.default_rng(13)
+    N, h = 4, 0.25
+    if layer == DENSE:
+        W, b, u0 = _dense_problem(rng, N, 5, 3)
+    else:
+        W, b, u0 = _conv_problem(rng, N, 3, 2, 4, 5)
+    Cw = rng.standard_normal(u0.shape)
+    U = O.serial_forward(W, b, u0, h, layer, kind)
+    Lam, dW, db = O.serial_backward(W, b, U, Cw, h, layer, kind)
+    Wt = torch.tensor(W, requires_grad=True)
+    bt = torch.tensor(b, requires_grad=True)
+    ut = torch.tensor(u0, requires_grad=True)
+    x = ut
+    f = torch.tanh if kind == TANH else torch.relu
+    for n in range(N):
+        if layer == DENSE:
+            z = torch.nn.functional.linear(x, Wt[n], bt[n])
+        else:
+            z = torch.nn.functional.conv2d(x.permute(0, 3, 1, 2), Wt[n].permute(0, 3, 1, 2), bt[n],
+                                           padding=1).permute(0, 2, 3, 1)
+        x = x + h * f(z)
+    (x * torch.tensor(Cw)).sum().backward()
+    np.testing.assert_allclose(dW, Wt.grad.numpy(), rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(db, bt.grad.numpy(), rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(Lam[0], ut.grad.numpy(), rtol=1e-11, atol=1e-13)
+
+
+# ---------------------------------------------------------------------------------------
+# Adjoint multigrid: mirror of the forward exactness; its limit is the serial gradient
+# ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("layer", [DENSE, CONV])
+@pytest.mark.parametrize("relax,per_cycle", [(O.RELAX_F, 1), (O.RELAX_FCF, 2)])
+def test_adjoint_two_level_exactness(layer, relax, per_cycle):
+    rng = np.random.default_rng(14)
+    N, m = 12, 3
+    h = 1.0 / N
+    if layer == DENSE:
+        W, b, u0 = _dense_problem(rng, N, 5, 3, scale=2.0)
+    else:
+        W, b, u0 = _conv_problem(rng, N, 2, 2, 4, 3)
+    U = O.serial_forward(W, b, u0, h, layer, TANH)
+    U += 0.05 * rng.standard_normal(U.shape)             # linearise about NON-converged states
+    lamN = rng.standard_normal(u0.shape)
+    Ls, dWs, dbs = O.serial_backward(W, b, U, lamN, h, layer, TANH)
+    Linit = rng.standard_normal(U.shape)
+    for k in range(1, N // m + 1):
+        Lam, dW, db, hist, it = O.fas_adjoint(W, b, U, lamN, h, m, 2, 1, relax, k, layer, TANH,
+                                              init=2, Lam_init=Linit)
+        lo = max(0, N - ((per_cycle * k + 1) * m - 1))    # exact from the top down to point lo
+        assert np.abs(Lam[lo:] - Ls[lo:]).max() < 1e-12, k
+        if per_cycle * k * m < N:
+            assert np.abs(Lam[0] - Ls[0]).max() > 1e-8
+    np.testing.assert_allclose(Lam, Ls, atol=1e-12)
+    np.testing.assert_allclose(dW, dWs, atol=1e-12)
+    np.testing.assert_allclose(db, dbs, atol=1e-12)
+
+
+def test_adjoint_three_level_converges_to_serial_gradient():
+    rng = np.random.default_rng(15)
+    N, m = 32, 2
+    W, b, u0 = _dense_problem(rng, N, 5, 3)
+    U = O.serial_forward(W, b, u0, 1 / N, DENSE, TANH)
+    lamN = rng.standard_normal(u0.shape)
+    Ls, dWs, dbs = O.serial_backward(W, b, U, lamN, 1 / N, DENSE, TANH)
+    Lam, dW, db, hist, it = O.fas_adjoint(W, b, U, lamN, 1 / N, m, 3, 1, O.RELAX_FCF, 30, DENSE, TANH,
+                                          tol=1e-13)
+    assert it < 30
+    np.testing.assert_allclose(Lam, Ls, atol=1e-11)
+    np.testing.assert_allclose(dW, dWs, atol=1e-11)
+
+
+def test_adjoint_coarse_step_is_transpose_of_coarse_forward_jacobian():
+    """<Psi_H(lam), v> == <lam, J v> with J the Jacobian of the coarse forward step (by differences)."""
+    rng = np.random.default_rng(16)
+    q, hs = 4, 0.6
+    W, b, u0 = _dense_problem(rng, 1, q, 1)
+    lam = rng.standard_normal((1, q))
+    v = rng.standard_normal((1, q))
+    eps = 1e-6
+    Jv = (O.step(u0 + eps * v, W[0], b[0], hs, DENSE, TANH) - O.step(u0 - eps * v, W[0], b[0], hs, DENSE, TANH)) / (2 * eps)
+    lhs = float(np.sum(O.adjoint_step(lam, u0, W[0], b[0], hs, DENSE, TANH) * v))
+    assert abs(lhs - float(np.sum(lam * Jv))) < 1e-8
+
+
+# ---------------------------------------------------------------------------------------
+# Level maps against enumeration (integer work)
+# ---------------------------------------------------------------------------------------
+def test_level_map_vs_enumeration():
+    for m in (2, 4, 8, 16):
+        for N in list(range(1, 70)) + [256, 512, 1024, 4096]:
+            for max_levels in (1, 2, 3, 5):
+                for min_coarse in (1, 8):
+                    # enumeration: level l holds every fine index divisible by m^l
+                    exp_sizes, ok = [N], True
+                    while len(exp_sizes) < max_levels and exp_sizes[-1] > min_coarse:
+                        if exp_sizes[-1] % m:
+                            ok = False
+                            break
+                        exp_sizes.append(exp_sizes[-1] // m)
+                    if not ok:
+                        with pytest.raises(ValueError):
+                            O.level_map(N, m, max_levels, min_coarse)
+                        continue
+                    sizes, fidx = O.level_map(N, m, max_levels, min_coarse)
+                    assert sizes == exp_sizes
+                    for l, idx in enumerate(fidx):
+                        brute = [n for n in range(N + 1) if n % (m ** l) == 0]
+                        assert list(idx) == brute
+
+
+def test_named_hierarchies():
+    assert O.level_sizes(16, 4, 2, 1) == [16, 4]
+    assert O.level_sizes(256, 4, 3, 1) == [256, 64, 16]
+    assert O.level_sizes(64, 4, 2, 1) == [64, 16]
+    assert O.level_sizes(512, 8, 3, 1) == [512, 64, 8]
+    assert O.level_sizes(1024, 16, 8, 8) == [1024, 64, 4]
+
+
+# ---------------------------------------------------------------------------------------
+# Depth-independent convergence (Sec. IV-A): recorded, with only a loose assertion
+# ---------------------------------------------------------------------------------------
+def test_convergence_history_similar_across_depths():
+    its = []
+    for N in (32, 64, 128):
+        rng = np.random.default_rng(17)
+        q = 8
+        # weights smooth in depth (one matrix for all layers): the setting of an ODE discretisation
+        A = rng.standard_normal((q, q)) / math.sqrt(q)
+        W = np.tile(A, (N, 1, 1))
+        b = np.zeros((N, q))
+        u0 = rng.standard_normal((2, q))
+        _, hist, it = O.fas_forward(W, b, u0, 1.0 / N, 4, 2, 1, O.RELAX_FCF, 20, DENSE, TANH, tol=1e-9)
+        its.append(it)
+    assert max(its) - min(its) <= 1, its
