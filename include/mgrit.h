@@ -1,0 +1,141 @@
+/*
+ * mgrit.h -- C ABI of the layer-parallel multigrid (MGRIT-FAS) solver for residual networks
+ *            u^{n+1} = u^n + h F(u^n; theta^n),  n = 0..N-1          (paper Sec. II, Eq. (1))
+ * on one AMD MI355X (gfx950).  Plain C: only pointers and sizes cross this boundary.
+ *
+ * Index convention.  N layer steps, N+1 states u^0..u^N ("points" 0..N), parameters
+ * theta^0..theta^{N-1}.  The coarsening factor (the paper's c, Sec. III-C) is called m here.
+ * Level l has N_l = N / m^l steps and step size h_l = m^l h; point j of level l is fine
+ * point j m^l and uses theta^{j m^l} (injection of states, residuals and parameters,
+ * Sec. III-C, Eq. (23)).
+ *
+ * Memory.  The caller owns every buffer.  Pointers marked "device" are HIP device pointers
+ * aligned to 256 bytes; pointers marked "host" are ordinary host pointers.  The library
+ * allocates no device memory and keeps no state between calls.  All device work is enqueued
+ * on `hip_stream` (a hipStream_t passed as void*; NULL = the default stream).  A call that
+ * writes a host output (resnorm_hist, iters_done, norm_out) synchronises that stream before
+ * it returns; otherwise it returns with its work in flight on the stream.
+ *
+ * Layouts (all row-major, last index fastest):
+ *   dense: state [B][q] float;  W [N][q_out][q_in];  b [N][q] float
+ *   conv : state [B][Himg][Wimg][C] float (NHWC);  W [N][C_out][3][3][C_in];  b [N][C] float
+ *          3x3, stride 1, one pixel of zero padding, cross-correlation:
+ *          z[b,y,x,o] = sum_{dy,dx,i} W[o][dy][dx][i] u[b,y+dy-1,x+dx-1,i] + b[o]
+ *   W is float when dtype = MGRIT_FP32 and bf16 (upper 16 bits of a float, 2 bytes) when
+ *   dtype = MGRIT_BF16.  With MGRIT_BF16 the matrix-core operands (weights and the state
+ *   operand of the affine map) are bf16 and everything else -- accumulation, bias,
+ *   activation, the skip add, states, residuals, corrections -- is float.
+ *   State arrays over points are [N+1][state].
+ *
+ * Return value of every int32_t function: MGRIT_OK or one of the negative codes below.
+ * Nothing is printed and nothing is thrown.
+ */
+#ifndef MGRIT_H
+#define MGRIT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  MGRIT_OK = 0,
+  MGRIT_ERR_POINTER = -1,     /* required pointer NULL or not 256-byte aligned              */
+  MGRIT_ERR_PROBLEM = -2,     /* invalid problem: N < 1, m < 2, bad enum, a level that must
+                                 be coarsened is not divisible by m, sizes <= 0, ...         */
+  MGRIT_ERR_WORKSPACE = -3,   /* workspace smaller than mgrit_*_workspace_bytes()            */
+  MGRIT_ERR_UNSUPPORTED = -4, /* valid request that this build does not implement            */
+  MGRIT_ERR_NONFINITE = -5,   /* a residual norm came out NaN or Inf                         */
+  MGRIT_ERR_HIP = -6          /* a HIP runtime call failed                                   */
+};
+
+enum { MGRIT_RELAX_F = 0, MGRIT_RELAX_FCF = 1 };           /* Sec. III-C, Fig. 3, Alg. 1 step 1 */
+enum { MGRIT_NORM_L2 = 0, MGRIT_NORM_RMS = 1 };            /* RMS = L2 / sqrt(#entries)         */
+enum { MGRIT_LAYER_DENSE = 0, MGRIT_LAYER_CONV3X3 = 1 };
+enum { MGRIT_ACT_TANH = 0, MGRIT_ACT_RELU = 1 };
+enum { MGRIT_FP32 = 0, MGRIT_BF16 = 1 };
+enum { MGRIT_INIT_ZERO = 0, MGRIT_INIT_COPY = 1, MGRIT_INIT_USER = 2 };
+enum { MGRIT_MAX_LEVELS = 16 };
+
+typedef struct mgrit_problem {
+  int32_t N;           /* layer steps, >= 1                                   (Sec. II, Eq. (1)) */
+  float   h;           /* fine step size                                      (Sec. II, Eq. (1)) */
+  int32_t m;           /* coarsening factor, >= 2                             (Sec. III-C)       */
+  int32_t max_levels;  /* 1 = serial propagation, 2 = two-level scheme of Alg. 1,
+                          > 2 = the scheme applied recursively (V-cycle)      (Sec. III-A)       */
+  int32_t min_coarse;  /* a level with N_l <= min_coarse is not coarsened further; values < 1
+                          act as 1                                                               */
+  int32_t relax;       /* MGRIT_RELAX_F or MGRIT_RELAX_FCF                    (Alg. 1 step 1)    */
+  int32_t cycle;       /* 0 = V-cycle (the only one defined)                                     */
+  int32_t max_iter;    /* number of cycles; with tol > 0 an upper bound       (Sec. IV-A)        */
+  float   tol;         /* > 0: stop after the first cycle whose residual norm is <= tol
+                          (Alg. 1 step 6); <= 0: run exactly max_iter cycles                     */
+  int32_t norm_kind;   /* MGRIT_NORM_L2 or MGRIT_NORM_RMS                                        */
+  int32_t layer;       /* MGRIT_LAYER_DENSE or MGRIT_LAYER_CONV3X3                                */
+  int32_t act;         /* MGRIT_ACT_TANH or MGRIT_ACT_RELU                                       */
+  int32_t dtype;       /* MGRIT_FP32 or MGRIT_BF16                                               */
+  int32_t B, q;        /* dense: batch and width                                                 */
+  int32_t C, Himg, Wimg; /* conv: channels, image height and width                               */
+  int32_t init;        /* initial guess of the fine C-points: MGRIT_INIT_ZERO, MGRIT_INIT_COPY
+                          (every C-point := the known end value u^0, resp. lambda^N) or
+                          MGRIT_INIT_USER (take them from the in/out array)                      */
+} mgrit_problem_t;
+
+/* Level hierarchy (Sec. III-C: every m-th layer of a level is also a member of the next
+ * coarser level).  Host only, integer only.  n_levels <- number of levels L; N_l[l] <- steps
+ * on level l (array of MGRIT_MAX_LEVELS entries); fine_index <- concatenation over levels of
+ * the fine point index of every point, sum_l (N_l + 1) entries.  N_l and fine_index may be
+ * NULL (then only the count is returned).  Errors: MGRIT_ERR_PROBLEM. */
+int32_t mgrit_level_map(const mgrit_problem_t* p, int32_t* n_levels, int32_t* N_l, int32_t* fine_index);
+
+/* Bytes of device workspace the forward solve / residual norm, and the adjoint solve, need
+ * for this problem; 0 if the problem is invalid.  Host only. */
+size_t mgrit_workspace_bytes(const mgrit_problem_t* p);
+size_t mgrit_adjoint_workspace_bytes(const mgrit_problem_t* p);
+
+/* Forward solve of L_h(U) = f_h = (u0, 0, .., 0) (Sec. III-C, Eq. (18)) by max_iter FAS cycles
+ * of Alg. 1: relaxation, residual at the C-points, injection, coarse FAS equation
+ * L_H(V) = L_H(U_H) + R_H (Eq. (24)) solved recursively / serially on the coarsest level,
+ * C-point correction, F-relaxation.  With max_levels = 1 this is serial propagation.
+ *   W, b      device, read only
+ *   u0        device [state], read only
+ *   U         device [(N+1)][state]; out; with init = MGRIT_INIT_USER also in (its C-points)
+ *   resnorm_hist  host [max_iter] or NULL; entry k <- norm of the C-point residual of the fine
+ *             level evaluated in cycle k after relaxation and before the correction
+ *   iters_done    host or NULL; <- cycles run
+ *   workspace device, workspace_bytes >= mgrit_workspace_bytes(p)
+ * Errors: all codes above; on MGRIT_ERR_NONFINITE U holds the diverged iterate. */
+int32_t mgrit_fas_forward(const mgrit_problem_t* p, const void* W, const float* b, const float* u0,
+                          float* U, double* resnorm_hist, int32_t* iters_done,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Adjoint (backward) solve by the same cycle on the reversed layer axis.  The paper states
+ * that the multigrid removes the serial backward propagation as well (Sec. III-C) and prints
+ * no equations; the system solved is the exact reverse-mode derivative of Eq. (1):
+ *   z^n = A_n U^n + b_n,  G^n = act'(z^n) * Lam^{n+1},  Lam^n = Lam^{n+1} + h A_n^T G^n,
+ * with terminal value Lam^N = lamN, linearised about the given states U (converged or not);
+ * the level-l step from point j+1 to point j uses U and theta of fine point j m^l and step h_l.
+ * Afterwards dW[n] = h G^n (U^n)^T (summed over the batch / batch and pixels) and
+ * db[n] = h sum G^n from the final Lam.
+ *   U     device [(N+1)][state], read only      lamN  device [state], read only
+ *   Lam   device [(N+1)][state]; out (in for init = MGRIT_INIT_USER)
+ *   dW    device float, same shape as W, overwritten, or NULL;  db like b, or NULL
+ *   workspace_bytes >= mgrit_adjoint_workspace_bytes(p)
+ * resnorm_hist / iters_done as above (residual of the adjoint system). */
+int32_t mgrit_fas_adjoint(const mgrit_problem_t* p, const void* W, const float* b, const float* U,
+                          const float* lamN, float* Lam, float* dW, float* db,
+                          double* resnorm_hist, int32_t* iters_done,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* || f_h - L_h(U) || over all N+1 points of the fine level (Sec. III-C, Eq. (19); Sec. IV-A).
+ *   norm_out  host, required.  Always synchronises the stream. */
+int32_t mgrit_residual_norm(const mgrit_problem_t* p, const void* W, const float* b, const float* u0,
+                            const float* U, double* norm_out,
+                            void* workspace, size_t workspace_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MGRIT_H */

@@ -1,0 +1,406 @@
+// Host side of the MGRIT-FAS library: argument checks, the level hierarchy, the workspace
+// layout and the launch schedule of the FAS V-cycle (forward and adjoint).  Every arithmetic
+// step of the method runs in the HIP kernels of mgrit_kernels.hip; this file only decides
+// which launch comes next.
+#include <math.h>
+#include <string.h>
+
+#include "../../include/mgrit.h"
+#include "mgrit_internal.h"
+
+using namespace mgrit;
+
+namespace {
+
+constexpr size_t ALIGN = 256;
+inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+inline bool aligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) % ALIGN) == 0; }
+
+struct Plan {
+  int L;
+  int Nl[MGRIT_MAX_LEVELS];
+  long long mpow[MGRIT_MAX_LEVELS];
+  float hl[MGRIT_MAX_LEVELS];
+  long long E, wsize;
+  int M, Nf, K, TH;
+  size_t esize;                        // bytes per weight element
+  size_t off_X[MGRIT_MAX_LEVELS], off_g[MGRIT_MAX_LEVELS], off_R[MGRIT_MAX_LEVELS];
+  size_t off_partial, n_partial, off_hist, off_Wt, off_D;
+  size_t bytes_fwd, bytes_adj;
+};
+
+// Level hierarchy (Sec. III-C): coarsen by m while fewer than max_levels levels exist and the
+// current level has more than min_coarse steps.
+int build_levels(const mgrit_problem_t* p, int* L, int* Nl) {
+  if (!p) return MGRIT_ERR_POINTER;
+  if (p->N < 1 || p->m < 2 || p->max_levels < 1 || p->max_levels > MGRIT_MAX_LEVELS) return MGRIT_ERR_PROBLEM;
+  const int minc = p->min_coarse < 1 ? 1 : p->min_coarse;
+  int n = 1;
+  Nl[0] = p->N;
+  while (n < p->max_levels && Nl[n - 1] > minc) {
+    if (Nl[n - 1] % p->m != 0) return MGRIT_ERR_PROBLEM;
+    Nl[n] = Nl[n - 1] / p->m;
+    ++n;
+  }
+  *L = n;
+  return MGRIT_OK;
+}
+
+int make_plan(const mgrit_problem_t* p, Plan* pl) {
+  memset(pl, 0, sizeof(*pl));
+  int rc = build_levels(p, &pl->L, pl->Nl);
+  if (rc != MGRIT_OK) return rc;
+  if (!(p->h > 0.0f) || !isfinite(p->h)) return MGRIT_ERR_PROBLEM;
+  if (p->relax != MGRIT_RELAX_F && p->relax != MGRIT_RELAX_FCF) return MGRIT_ERR_PROBLEM;
+  if (p->cycle != 0 || p->max_iter < 1) return MGRIT_ERR_PROBLEM;
+  if (p->norm_kind != MGRIT_NORM_L2 && p->norm_kind != MGRIT_NORM_RMS) return MGRIT_ERR_PROBLEM;
+  if (p->layer != MGRIT_LAYER_DENSE && p->layer != MGRIT_LAYER_CONV3X3) return MGRIT_ERR_PROBLEM;
+  if (p->act != MGRIT_ACT_TANH && p->act != MGRIT_ACT_RELU) return MGRIT_ERR_PROBLEM;
+  if (p->dtype != MGRIT_FP32 && p->dtype != MGRIT_BF16) return MGRIT_ERR_PROBLEM;
+  if (p->init < MGRIT_INIT_ZERO || p->init > MGRIT_INIT_USER) return MGRIT_ERR_PROBLEM;
+  if (p->layer == MGRIT_LAYER_DENSE) {
+    if (p->B < 1 || p->q < 1) return MGRIT_ERR_PROBLEM;
+    if (p->q % 8 != 0) return MGRIT_ERR_UNSUPPORTED;       // 16-byte operand pieces
+    pl->M = p->B; pl->Nf = p->q; pl->K = p->q; pl->TH = 0;
+  } else {
+    if (p->B < 1 || p->C < 1 || p->Himg < 1 || p->Wimg < 1) return MGRIT_ERR_PROBLEM;
+    if (p->C % 8 != 0 || p->C > 64 || p->Wimg > 256) return MGRIT_ERR_UNSUPPORTED;
+    if ((long long)p->B * p->Himg * p->Wimg > 0x7fffffffLL) return MGRIT_ERR_UNSUPPORTED;
+    pl->M = p->B * p->Himg * p->Wimg; pl->Nf = p->C; pl->K = 9 * p->C;
+    pl->TH = conv_tile_rows(p->Himg, p->Wimg, p->C, p->dtype);
+    if (pl->TH < 1) return MGRIT_ERR_UNSUPPORTED;
+  }
+  pl->E = (long long)pl->M * pl->Nf;
+  pl->wsize = (long long)pl->Nf * pl->K;
+  pl->esize = p->dtype == MGRIT_FP32 ? 4 : 2;
+  long long mp = 1;
+  for (int l = 0; l < pl->L; ++l) {
+    pl->mpow[l] = mp;
+    pl->hl[l] = p->h * (float)mp;
+    mp *= p->m;
+  }
+  // workspace: coarse-level states and right-hand sides, C-point residuals, norm partials,
+  // residual history; for the adjoint also the transposed weights and the act' cache
+  size_t off = 0;
+  for (int l = 1; l < pl->L; ++l) {
+    pl->off_X[l] = off; off = align_up(off + (size_t)(pl->Nl[l] + 1) * pl->E * 4);
+    pl->off_g[l] = off; off = align_up(off + (size_t)(pl->Nl[l] + 1) * pl->E * 4);
+  }
+  for (int l = 0; l + 1 < pl->L; ++l) {
+    pl->off_R[l] = off; off = align_up(off + (size_t)(pl->Nl[l + 1] + 1) * pl->E * 4);
+  }
+  StepArgs a;
+  memset(&a, 0, sizeof(a));
+  a.M = pl->M; a.Nf = pl->Nf; a.K = pl->K; a.Himg = p->Himg; a.Wimg = p->Wimg; a.TH = pl->TH;
+  size_t np = (size_t)step_grid_blocks(a, p->layer, p->dtype, p->N) * p->N + diff_sq_blocks(pl->E);
+  if (pl->L > 1) {
+    size_t np1 = (size_t)step_grid_blocks(a, p->layer, p->dtype, pl->Nl[1]) * pl->Nl[1];
+    if (np1 > np) np = np1;
+  }
+  pl->n_partial = np;
+  pl->off_partial = off; off = align_up(off + np * 4);
+  pl->off_hist = off; off = align_up(off + (size_t)(p->max_iter + 1) * 8);
+  pl->bytes_fwd = off;
+  pl->off_Wt = off; off = align_up(off + (size_t)p->N * pl->wsize * pl->esize);
+  pl->off_D = off; off = align_up(off + (size_t)p->N * pl->E * 4);
+  pl->bytes_adj = off;
+  return MGRIT_OK;
+}
+
+// The cycle is written once, in "sweep order": sweep point 0 carries the known value and the
+// sweep advances to sweep point N_l.  The forward solve sweeps up the layer axis; the adjoint
+// solve sweeps down it, so sweep point js of its fine level is natural point N - js.  Only the
+// caller's fine-level array is stored in natural order; all workspace arrays are in sweep order.
+struct Solver {
+  const mgrit_problem_t* p;
+  Plan pl;
+  hipStream_t s;
+  bool adjoint;
+  float* X[MGRIT_MAX_LEVELS];
+  float* g[MGRIT_MAX_LEVELS];
+  float* R[MGRIT_MAX_LEVELS];
+  const void* W;
+  const float* bias;
+  const float* Dm;
+  int act;
+  float* partial;
+  double* hist_dev;
+  hipError_t err = hipSuccess;
+
+  void chk(hipError_t e) { if (err == hipSuccess && e != hipSuccess) err = e; }
+  // map of a sweep-order index range of level l's state array to its storage order
+  PtMap pm(int l, long long base, long long stride) const {
+    if (l == 0 && adjoint) return PtMap{pl.Nl[0] - base, -stride};
+    return PtMap{base, stride};
+  }
+  // layer index used by the sweep step that lands on sweep point js of level l
+  PtMap layer_map(int l, long long js0, long long jstride) const {
+    if (adjoint) return PtMap{(pl.Nl[l] - js0) * pl.mpow[l], -jstride * pl.mpow[l]};
+    return PtMap{(js0 - 1) * pl.mpow[l], jstride * pl.mpow[l]};
+  }
+  StepArgs base_args(int l, long long js0, long long jstride) const {
+    StepArgs a;
+    memset(&a, 0, sizeof(a));
+    a.W = W; a.bias = bias; a.wm = layer_map(l, js0, jstride);
+    a.Dm = Dm; a.dm = a.wm;
+    a.sp = 1.0f; a.hs = pl.hl[l]; a.mode = MODE_PHI; a.act = act;
+    a.M = pl.M; a.Nf = pl.Nf; a.K = pl.K; a.Himg = p->Himg; a.Wimg = p->Wimg; a.TH = pl.TH;
+    a.E = pl.E; a.wsize = pl.wsize;
+    return a;
+  }
+  void launch(const StepArgs& a, int groups) {
+    if (err == hipSuccess) chk(launch_step(a, p->layer, p->dtype, groups, s));
+  }
+  // X[js] = Phi(X[js-1]) + g[js] for js = js0 + gi*jstride        (relaxation, coarsest solve)
+  void propagate(int l, long long js0, long long jstride, int groups) {
+    StepArgs a = base_args(l, js0, jstride);
+    a.X = X[l]; a.xm = pm(l, js0 - 1, jstride);
+    a.Out = X[l]; a.om = pm(l, js0, jstride);
+    if (g[l]) { a.E1 = g[l]; a.e1m = PtMap{js0, jstride}; a.c1 = 1.0f; }
+    launch(a, groups);
+  }
+  void f_relax(int l) {                                        // Sec. III-C, Fig. 3
+    for (int k = 1; k < p->m; ++k) propagate(l, k, p->m, pl.Nl[l + 1]);
+  }
+  void c_relax(int l) { propagate(l, p->m, p->m, pl.Nl[l + 1]); }
+
+  void cycle(int l, int iter, bool skip_opening_relax) {
+    const int m = p->m;
+    if (l == pl.L - 1) {                                        // coarsest level: serial solve
+      if (g[l]) chk(launch_copy_points(X[l], PtMap{0, 0}, g[l], PtMap{0, 0}, pl.E, 1, s));
+      for (int j = 1; j <= pl.Nl[l]; ++j) propagate(l, j, 1, 1);
+      return;
+    }
+    const int Nc = pl.Nl[l + 1];
+    if (!skip_opening_relax) f_relax(l);                        // Alg. 1 step 1
+    if (p->relax == MGRIT_RELAX_FCF) { c_relax(l); f_relax(l); }
+    {                                                           // residual at the C-points, Eq. (19)
+      StepArgs a = base_args(l, m, m);
+      a.X = X[l]; a.xm = pm(l, m - 1, m);
+      a.Out = R[l]; a.om = PtMap{1, 1};
+      a.E1 = X[l]; a.e1m = pm(l, m, m); a.c1 = -1.0f;
+      if (g[l]) { a.E2 = g[l]; a.e2m = PtMap{m, m}; a.c2 = 1.0f; }
+      if (l == 0) a.norm_partial = partial;
+      launch(a, Nc);
+      if (l == 0) {
+        const int nb = step_grid_blocks(a, p->layer, p->dtype, Nc) * Nc;
+        const double scale = p->norm_kind == MGRIT_NORM_RMS ? 1.0 / sqrt((double)(Nc + 1) * (double)pl.E) : 1.0;
+        chk(launch_norm_final(partial, nb, scale, hist_dev + iter, s));
+      }
+    }
+    // Alg. 1 step 2: injection of the C-points; the residual of point 0 is identically zero
+    chk(launch_copy_points(X[l + 1], PtMap{0, 1}, X[l], pm(l, 0, m), pl.E, Nc + 1, s));
+    chk(launch_copy_points(g[l + 1], PtMap{0, 0}, X[l], pm(l, 0, 0), pl.E, 1, s));
+    {                                                           // Alg. 1 step 3: S_H = L_H(U_H) + R_H
+      StepArgs a = base_args(l + 1, 1, 1);
+      a.X = X[l + 1]; a.xm = PtMap{0, 1};
+      a.Out = g[l + 1]; a.om = PtMap{1, 1};
+      a.sp = -1.0f;
+      a.E1 = X[l + 1]; a.e1m = PtMap{1, 1}; a.c1 = 1.0f;
+      a.E2 = R[l]; a.e2m = PtMap{1, 1}; a.c2 = 1.0f;
+      launch(a, Nc);
+    }
+    cycle(l + 1, iter, false);                                  // solve for V_H (in place of U_H)
+    // Alg. 1 steps 4, 5: C-points += V_H - U_H, where U_H is still held by the C-points themselves
+    chk(launch_correct(X[l], pm(l, m, m), X[l + 1], PtMap{1, 1}, pl.E, Nc, s));
+    f_relax(l);
+  }
+};
+
+int check_finite(const double* h, int n) {
+  for (int i = 0; i < n; ++i)
+    if (!isfinite(h[i])) return MGRIT_ERR_NONFINITE;
+  return MGRIT_OK;
+}
+
+// Runs the solve loop shared by the forward and the adjoint entry point.
+int run_solver(Solver& sv, const float* first, double* resnorm_hist, int32_t* iters_done) {
+  const mgrit_problem_t* p = sv.p;
+  const Plan& pl = sv.pl;
+  const int m = p->m;
+  // known value at sweep point 0 and initial guess of the C-points
+  if (pl.L > 1 && p->init == MGRIT_INIT_ZERO)
+    sv.chk(launch_zero_points(sv.X[0], sv.pm(0, m, m), pl.E, pl.Nl[1], sv.s));
+  if (pl.L > 1 && p->init == MGRIT_INIT_COPY)
+    sv.chk(launch_copy_points(sv.X[0], sv.pm(0, m, m), first, PtMap{0, 0}, pl.E, pl.Nl[1], sv.s));
+  sv.chk(launch_copy_points(sv.X[0], sv.pm(0, 0, 0), first, PtMap{0, 0}, pl.E, 1, sv.s));
+
+  int iters = 0;
+  int rc = MGRIT_OK;
+  if (pl.L == 1) {
+    sv.cycle(0, 0, false);
+    iters = 1;
+    if (resnorm_hist) resnorm_hist[0] = 0.0;
+    if (sv.err == hipSuccess && (resnorm_hist || iters_done)) sv.chk(hipStreamSynchronize(sv.s));
+  } else {
+    for (int k = 0; k < p->max_iter && sv.err == hipSuccess; ++k) {
+      sv.cycle(0, k, k > 0);
+      ++iters;
+      if (p->tol > 0.0f) {
+        double v = 0.0;
+        sv.chk(hipMemcpyAsync(&v, sv.hist_dev + k, sizeof(double), hipMemcpyDeviceToHost, sv.s));
+        sv.chk(hipStreamSynchronize(sv.s));
+        if (sv.err != hipSuccess) break;
+        if (resnorm_hist) resnorm_hist[k] = v;
+        if (!isfinite(v)) { rc = MGRIT_ERR_NONFINITE; break; }
+        if (v <= (double)p->tol) break;
+      }
+    }
+    if (!(p->tol > 0.0f) && resnorm_hist && sv.err == hipSuccess) {
+      sv.chk(hipMemcpyAsync(resnorm_hist, sv.hist_dev, sizeof(double) * iters, hipMemcpyDeviceToHost, sv.s));
+      sv.chk(hipStreamSynchronize(sv.s));
+      if (sv.err == hipSuccess) rc = check_finite(resnorm_hist, iters);
+    } else if (iters_done && sv.err == hipSuccess) {
+      sv.chk(hipStreamSynchronize(sv.s));
+    }
+  }
+  if (iters_done) *iters_done = iters;
+  if (sv.err != hipSuccess) return MGRIT_ERR_HIP;
+  return rc;
+}
+
+void bind_workspace(Solver& sv, void* workspace) {
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  const Plan& pl = sv.pl;
+  for (int l = 1; l < pl.L; ++l) {
+    sv.X[l] = reinterpret_cast<float*>(ws + pl.off_X[l]);
+    sv.g[l] = reinterpret_cast<float*>(ws + pl.off_g[l]);
+  }
+  for (int l = 0; l + 1 < pl.L; ++l) sv.R[l] = reinterpret_cast<float*>(ws + pl.off_R[l]);
+  sv.partial = reinterpret_cast<float*>(ws + pl.off_partial);
+  sv.hist_dev = reinterpret_cast<double*>(ws + pl.off_hist);
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t mgrit_level_map(const mgrit_problem_t* p, int32_t* n_levels, int32_t* N_l, int32_t* fine_index) {
+  if (!p || !n_levels) return MGRIT_ERR_POINTER;
+  int L, Nl[MGRIT_MAX_LEVELS];
+  const int rc = build_levels(p, &L, Nl);
+  if (rc != MGRIT_OK) return rc;
+  *n_levels = L;
+  long long mp = 1;
+  size_t pos = 0;
+  for (int l = 0; l < L; ++l) {
+    if (N_l) N_l[l] = Nl[l];
+    if (fine_index)
+      for (int j = 0; j <= Nl[l]; ++j) fine_index[pos++] = (int32_t)(j * mp);
+    mp *= p->m;
+  }
+  return MGRIT_OK;
+}
+
+size_t mgrit_workspace_bytes(const mgrit_problem_t* p) {
+  Plan pl;
+  if (!p || make_plan(p, &pl) != MGRIT_OK) return 0;
+  return pl.bytes_fwd;
+}
+
+size_t mgrit_adjoint_workspace_bytes(const mgrit_problem_t* p) {
+  Plan pl;
+  if (!p || make_plan(p, &pl) != MGRIT_OK) return 0;
+  return pl.bytes_adj;
+}
+
+int32_t mgrit_fas_forward(const mgrit_problem_t* p, const void* W, const float* b, const float* u0, float* U,
+                          double* resnorm_hist, int32_t* iters_done, void* workspace, size_t workspace_bytes,
+                          void* hip_stream) {
+  if (!p || !W || !b || !u0 || !U || !workspace) return MGRIT_ERR_POINTER;
+  if (!aligned(W) || !aligned(b) || !aligned(u0) || !aligned(U) || !aligned(workspace)) return MGRIT_ERR_POINTER;
+  Solver sv;
+  int rc = make_plan(p, &sv.pl);
+  if (rc != MGRIT_OK) return rc;
+  if (workspace_bytes < sv.pl.bytes_fwd) return MGRIT_ERR_WORKSPACE;
+  sv.p = p; sv.s = static_cast<hipStream_t>(hip_stream); sv.adjoint = false;
+  memset(sv.X, 0, sizeof(sv.X)); memset(sv.g, 0, sizeof(sv.g)); memset(sv.R, 0, sizeof(sv.R));
+  sv.X[0] = U;
+  sv.W = W; sv.bias = b; sv.Dm = nullptr; sv.act = p->act;
+  bind_workspace(sv, workspace);
+  return run_solver(sv, u0, resnorm_hist, iters_done);
+}
+
+int32_t mgrit_fas_adjoint(const mgrit_problem_t* p, const void* W, const float* b, const float* U, const float* lamN,
+                          float* Lam, float* dW, float* db, double* resnorm_hist, int32_t* iters_done,
+                          void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!p || !W || !b || !U || !lamN || !Lam || !workspace) return MGRIT_ERR_POINTER;
+  if (!aligned(W) || !aligned(b) || !aligned(U) || !aligned(lamN) || !aligned(Lam) || !aligned(workspace) ||
+      !aligned(dW) || !aligned(db))
+    return MGRIT_ERR_POINTER;
+  Solver sv;
+  int rc = make_plan(p, &sv.pl);
+  if (rc != MGRIT_OK) return rc;
+  if (p->layer != MGRIT_LAYER_DENSE && (dW || db)) return MGRIT_ERR_UNSUPPORTED;
+  if (workspace_bytes < sv.pl.bytes_adj) return MGRIT_ERR_WORKSPACE;
+  const Plan& pl = sv.pl;
+  sv.p = p; sv.s = static_cast<hipStream_t>(hip_stream); sv.adjoint = true;
+  memset(sv.X, 0, sizeof(sv.X)); memset(sv.g, 0, sizeof(sv.g)); memset(sv.R, 0, sizeof(sv.R));
+  sv.X[0] = Lam;
+  bind_workspace(sv, workspace);
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  void* Wt = ws + pl.off_Wt;
+  float* D = reinterpret_cast<float*>(ws + pl.off_D);
+  // transposed parameters, and act'(A_n U^n + b_n) for every layer in one grouped launch
+  sv.chk(launch_transpose_weights(W, Wt, p->layer, p->dtype, p->N, pl.Nf, sv.s));
+  {
+    sv.W = W; sv.bias = b; sv.Dm = nullptr; sv.act = p->act;
+    StepArgs a = sv.base_args(0, 1, 1);
+    a.wm = PtMap{0, 1};
+    a.mode = MODE_DACT;
+    a.X = U; a.xm = PtMap{0, 1};
+    a.Out = D; a.om = PtMap{0, 1};
+    sv.launch(a, p->N);
+  }
+  sv.W = Wt; sv.bias = nullptr; sv.Dm = D; sv.act = ACT_IDENT;
+  rc = run_solver(sv, lamN, resnorm_hist, iters_done);
+  if (rc != MGRIT_OK && rc != MGRIT_ERR_NONFINITE) return rc;
+  if (dW || db) {
+    GradArgs ga;
+    memset(&ga, 0, sizeof(ga));
+    ga.U = U; ga.um = PtMap{0, 1};
+    ga.Lam = Lam; ga.lm = PtMap{1, 1};
+    ga.Dm = D; ga.dm = PtMap{0, 1};
+    ga.dW = dW; ga.db = db; ga.hs = p->h;
+    ga.M = pl.M; ga.Nf = pl.Nf; ga.K = pl.K; ga.Himg = p->Himg; ga.Wimg = p->Wimg; ga.B = p->B;
+    ga.E = pl.E; ga.wsize = pl.wsize;
+    if (launch_grad(ga, p->layer, p->dtype, p->N, sv.s) != hipSuccess) return MGRIT_ERR_HIP;
+    if (resnorm_hist || iters_done)
+      if (hipStreamSynchronize(sv.s) != hipSuccess) return MGRIT_ERR_HIP;
+  }
+  return rc;
+}
+
+int32_t mgrit_residual_norm(const mgrit_problem_t* p, const void* W, const float* b, const float* u0, const float* U,
+                            double* norm_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!p || !W || !b || !u0 || !U || !norm_out || !workspace) return MGRIT_ERR_POINTER;
+  if (!aligned(W) || !aligned(b) || !aligned(u0) || !aligned(U) || !aligned(workspace)) return MGRIT_ERR_POINTER;
+  Solver sv;
+  int rc = make_plan(p, &sv.pl);
+  if (rc != MGRIT_OK) return rc;
+  if (workspace_bytes < sv.pl.bytes_fwd) return MGRIT_ERR_WORKSPACE;
+  const Plan& pl = sv.pl;
+  sv.p = p; sv.s = static_cast<hipStream_t>(hip_stream); sv.adjoint = false;
+  memset(sv.X, 0, sizeof(sv.X)); memset(sv.g, 0, sizeof(sv.g)); memset(sv.R, 0, sizeof(sv.R));
+  sv.W = W; sv.bias = b; sv.Dm = nullptr; sv.act = p->act;
+  bind_workspace(sv, workspace);
+  // rows n = 1..N of f_h - L_h(U): Phi(U[n-1]) - U[n]; row 0: u0 - U[0]
+  StepArgs a = sv.base_args(0, 1, 1);
+  a.X = U; a.xm = PtMap{0, 1};
+  a.E1 = U; a.e1m = PtMap{1, 1}; a.c1 = -1.0f;
+  a.norm_partial = sv.partial;
+  sv.launch(a, p->N);
+  const int nb = step_grid_blocks(a, p->layer, p->dtype, p->N) * p->N;
+  int nb0 = 0;
+  sv.chk(launch_diff_sq(u0, U, pl.E, sv.partial + nb, &nb0, sv.s));
+  const double scale = p->norm_kind == MGRIT_NORM_RMS ? 1.0 / sqrt((double)(p->N + 1) * (double)pl.E) : 1.0;
+  sv.chk(launch_norm_final(sv.partial, nb + nb0, scale, sv.hist_dev, sv.s));
+  double v = 0.0;
+  sv.chk(hipMemcpyAsync(&v, sv.hist_dev, sizeof(double), hipMemcpyDeviceToHost, sv.s));
+  sv.chk(hipStreamSynchronize(sv.s));
+  if (sv.err != hipSuccess) return MGRIT_ERR_HIP;
+  *norm_out = v;
+  return isfinite(v) ? MGRIT_OK : MGRIT_ERR_NONFINITE;
+}
+
+}  // extern "C"

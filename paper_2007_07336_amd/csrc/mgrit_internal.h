@@ -1,0 +1,87 @@
+// Internal declarations shared by the host schedule and the HIP kernels of the MGRIT-FAS
+// library.  Not part of the public C ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mgrit {
+
+// Affine map from the group index of a launch to a point (or layer) index of an array that
+// is laid out [points][E]:  idx = base + gi * stride.  A negative stride walks the layer
+// axis backwards (adjoint sweeps).
+struct PtMap {
+  long long base;
+  long long stride;
+};
+
+// One layer-batched step launch: every group gi evaluates, for its own input point and its
+// own layer parameters,
+//     z   = A_layer * (Dm ? Dm .* X : X) + bias
+//     phi = X + hs * act(z)                                   (Sec. II, Eq. (1))
+//     out = sp * phi + c1 * E1 + c2 * E2                      (mode PHI)
+//     out = act'(z)                                           (mode DACT)
+// which covers F-/C-relaxation, the C-point residual, the FAS right-hand side and the adjoint
+// steps (Sec. III-B, III-C).  If norm_partial is set, every workgroup also writes the sum of
+// out^2 over its tile to norm_partial[linear block index].
+struct StepArgs {
+  const float* X;   PtMap xm;
+  const float* Dm;  PtMap dm;      // optional elementwise multiplier of the matrix operand
+  const void*  W;   PtMap wm;      // weights of layer wm(gi); element type = template parameter
+  const float* bias;               // [layers][Nf] or null (same layer index as W)
+  float* Out;       PtMap om;      // may be null when only the norm is wanted
+  const float* E1;  PtMap e1m;  float c1;
+  const float* E2;  PtMap e2m;  float c2;
+  float sp, hs;
+  float* norm_partial;
+  int mode;                        // MODE_PHI / MODE_DACT
+  int act;                         // 0 tanh, 1 relu, 2 identity
+  int M;                           // rows per state: B (dense) or B*Himg*Wimg (conv)
+  int Nf;                          // features per row: q (dense) or C (conv)
+  int K;                           // contraction length per output: q or 9*C
+  int Himg, Wimg, TH;              // conv only: image size and rows of an output tile
+  long long E;                     // M * Nf
+  long long wsize;                 // Nf * K elements per layer
+};
+
+enum { MODE_PHI = 0, MODE_DACT = 1 };
+enum { ACT_TANH = 0, ACT_RELU = 1, ACT_IDENT = 2 };
+
+// Parameter gradient launch (one group per layer n):
+//   G = Dm[n] .* Lam[n+1];  dW[n] = hs * G^T (*) U[n];  db[n] = hs * sum G
+struct GradArgs {
+  const float* U;   PtMap um;
+  const float* Lam; PtMap lm;
+  const float* Dm;  PtMap dm;
+  float* dW;                        // [layers][Nf][K] float
+  float* db;                        // [layers][Nf] or null
+  float hs;
+  int M, Nf, K, Himg, Wimg, B;
+  long long E, wsize;
+};
+
+// ---- launch wrappers (defined in mgrit_kernels.hip); all enqueue on `s` and return the HIP status
+hipError_t launch_step(const StepArgs& a, int layer_kind, int dtype, int groups, hipStream_t s);
+int        step_grid_blocks(const StepArgs& a, int layer_kind, int dtype, int groups);  // workgroups per group
+int        conv_tile_rows(int Himg, int Wimg, int C, int dtype);            // TH, or 0 if unsupported
+hipError_t launch_grad(const GradArgs& a, int layer_kind, int dtype, int groups, hipStream_t s);
+
+// out[om(gi)] = in[im(gi)]                      (injection restriction, initial guesses)
+hipError_t launch_copy_points(float* out, PtMap om, const float* in, PtMap im, long long E, int groups,
+                              hipStream_t s);
+// out[om(gi)] = 0
+hipError_t launch_zero_points(float* out, PtMap om, long long E, int groups, hipStream_t s);
+// U[um(gi)] += V[vm(gi)] - U[um(gi)]  evaluated as  U + (V - U)      (C-point correction)
+hipError_t launch_correct(float* U, PtMap um, const float* V, PtMap vm, long long E, int groups,
+                          hipStream_t s);
+// partial[slot0 + block] = sum over this block's chunk of (a - b)^2 ; returns blocks used
+hipError_t launch_diff_sq(const float* a, const float* b, long long n, float* partial, int* blocks_used,
+                          hipStream_t s);
+int        diff_sq_blocks(long long n);
+// out[0] = sqrt(sum_{i<n} partial[i]) * scale, summed in a fixed order in double
+hipError_t launch_norm_final(const float* partial, int n, double scale, double* out, hipStream_t s);
+// transposed parameter copies for the adjoint: dense Wt[n][i][o] = W[n][o][i];
+// conv Kt[n][i][2-dy][2-dx][o] = K[n][o][dy][dx][i]
+hipError_t launch_transpose_weights(const void* W, void* Wt, int layer_kind, int dtype, int layers, int Nf,
+                                    hipStream_t s);
+
+}  // namespace mgrit

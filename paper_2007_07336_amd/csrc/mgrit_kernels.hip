@@ -1,0 +1,670 @@
+// HIP kernels (gfx950 / CDNA4) of the MGRIT-FAS library: layer-batched residual-block steps
+// as grouped MFMA GEMMs / implicit-GEMM 3x3 convolutions with a fused epilogue, the
+// bandwidth-bound transfer kernels, the norm reduction and the parameter-gradient kernel.
+#include "mgrit_internal.h"
+
+namespace mgrit {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+
+constexpr int NT = 256;  // threads per workgroup (4 wavefronts of 64)
+
+// ------------------------------------------------------------------------------------------
+// Operand traits.  Matrix-core operands live in LDS as rows of KSTEP-multiples, k fastest.
+//   float : v_mfma_f32_32x32x2_f32, a lane feeds 4 consecutive k over 4 instructions
+//   bf16  : v_mfma_f32_32x32x16_bf16, a lane feeds 8 consecutive k per instruction
+// ------------------------------------------------------------------------------------------
+template <typename T> struct Op;
+template <> struct Op<float> {
+  static constexpr int KSTEP = 8;   // k consumed by one mma_step
+  static constexpr int VEC = 4;     // elements per 16-byte piece
+  static constexpr int PAD = 4;     // row padding in LDS (elements)
+  static constexpr int BK = 16;     // k per LDS stage of the dense kernel
+};
+template <> struct Op<__bf16> {
+  static constexpr int KSTEP = 16;
+  static constexpr int VEC = 8;
+  static constexpr int PAD = 8;
+  static constexpr int BK = 32;
+};
+
+__device__ __forceinline__ void cvt_store4(float* dst, float4 v) { *reinterpret_cast<float4*>(dst) = v; }
+__device__ __forceinline__ void cvt_store4(__bf16* dst, float4 v) {
+  bf16x4 o;
+  o[0] = static_cast<__bf16>(v.x);   // round to nearest even
+  o[1] = static_cast<__bf16>(v.y);
+  o[2] = static_cast<__bf16>(v.z);
+  o[3] = static_cast<__bf16>(v.w);
+  *reinterpret_cast<bf16x4*>(dst) = o;
+}
+
+// One KSTEP of the contraction for a TM x TN arrangement of 32x32 blocks.  ap[tm] / bp[tn]
+// point at this lane's row (lane % 32 already applied) at the current k offset.
+template <int TM, int TN>
+__device__ __forceinline__ void mma_step(const float* const (&ap)[TM], const float* const (&bp)[TN],
+                                         floatx16 (&acc)[TM][TN], int g) {
+  float4 a[TM], b[TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const float4*>(ap[i] + 4 * g);
+#pragma unroll
+  for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const float4*>(bp[j] + 4 * g);
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].x, b[j].x, acc[i][j], 0, 0, 0);
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].y, b[j].y, acc[i][j], 0, 0, 0);
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].z, b[j].z, acc[i][j], 0, 0, 0);
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].w, b[j].w, acc[i][j], 0, 0, 0);
+    }
+}
+template <int TM, int TN>
+__device__ __forceinline__ void mma_step(const __bf16* const (&ap)[TM], const __bf16* const (&bp)[TN],
+                                         floatx16 (&acc)[TM][TN], int g) {
+  bf16x8 a[TM], b[TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const bf16x8*>(ap[i] + 8 * g);
+#pragma unroll
+  for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const bf16x8*>(bp[j] + 8 * g);
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+}
+
+__device__ __forceinline__ float act_fn(float z, int act) {
+  if (act == ACT_TANH) return tanhf(z);
+  if (act == ACT_RELU) return fmaxf(z, 0.0f);
+  return z;
+}
+__device__ __forceinline__ float act_prime(float z, int act) {
+  if (act == ACT_TANH) { float t = tanhf(z); return 1.0f - t * t; }
+  if (act == ACT_RELU) return z > 0.0f ? 1.0f : 0.0f;
+  return 1.0f;
+}
+
+__device__ __forceinline__ float block_sum(float v, float* red) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  const int w = threadIdx.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[w] = v;
+  __syncthreads();
+  return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+// XCD-aware workgroup order: hardware deals consecutive workgroup ids round-robin to the 8
+// XCDs; remap so that consecutive logical tiles (which share a group's state and weights)
+// land on the same XCD and meet in its L2.
+__device__ __forceinline__ int logical_block() {
+  int total = gridDim.x, L = blockIdx.x;
+  if ((total & 7) == 0) L = (L & 7) * (total >> 3) + (L >> 3);
+  return L;
+}
+
+// Fused epilogue shared by the dense and the conv kernel.  Accumulator block (tm,tn), register
+// r of lane (g, c): row = row0[tm] + 8*(r/4) + 4*g + r%4, column = col0[tn] + c.
+template <int TM, int TN>
+__device__ __forceinline__ void epilogue(const StepArgs& a, int gi, long long layer, floatx16 (&acc)[TM][TN],
+                                         const long long (&row0)[TM], long long row_end,
+                                         const int (&col0)[TN], int L, float* red) {
+  const int lane = threadIdx.x & 63, g = lane >> 5, c = lane & 31;
+  const float* Xp = a.X + (a.xm.base + gi * a.xm.stride) * a.E;
+  float* Op_ = a.Out ? a.Out + (a.om.base + gi * a.om.stride) * a.E : nullptr;
+  const float* E1p = a.E1 ? a.E1 + (a.e1m.base + gi * a.e1m.stride) * a.E : nullptr;
+  const float* E2p = a.E2 ? a.E2 + (a.e2m.base + gi * a.e2m.stride) * a.E : nullptr;
+  const float* bp = a.bias ? a.bias + layer * a.Nf : nullptr;
+  float sq = 0.0f;
+#pragma unroll
+  for (int tn = 0; tn < TN; ++tn) {
+    const int col = col0[tn] + c;
+    if (col >= a.Nf) continue;
+    const float bv = bp ? bp[col] : 0.0f;
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const long long row = row0[tm] + 8 * (r >> 2) + 4 * g + (r & 3);
+        if (row >= row_end) continue;
+        const long long off = row * a.Nf + col;
+        const float z = acc[tm][tn][r] + bv;
+        float o;
+        if (a.mode == MODE_DACT) {
+          o = act_prime(z, a.act);
+        } else {
+          const float phi = Xp[off] + a.hs * act_fn(z, a.act);
+          o = a.sp * phi;
+          if (E1p) o += a.c1 * E1p[off];
+          if (E2p) o += a.c2 * E2p[off];
+        }
+        if (Op_) Op_[off] = o;
+        sq += o * o;
+      }
+    }
+  }
+  if (a.norm_partial) {
+    const float s = block_sum(sq, red);
+    if (threadIdx.x == 0) a.norm_partial[(long long)blockIdx.y * gridDim.x + L] = s;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Dense layer-batched step: per group  [M x K] * [Nf x K]^T,  M = batch, Nf = K = q.
+// 4 wavefronts arranged WR x WC, each owning TM x TN blocks of 32x32.  Both operands are
+// staged through LDS in BK-wide slabs with a register prefetch of the next slab.
+// ------------------------------------------------------------------------------------------
+template <typename WT, int BM, int BN, int WR, int WC>
+__global__ __launch_bounds__(NT) void dense_step_kernel(StepArgs a) {
+  constexpr int BK = Op<WT>::BK, ST = BK + Op<WT>::PAD, VEC = Op<WT>::VEC, KSTEP = Op<WT>::KSTEP;
+  constexpr int TM = BM / WR / 32, TN = BN / WC / 32;
+  constexpr int AP = BM * BK / 4 / NT;      // float4 pieces of the state slab per thread
+  constexpr int BP = BN * BK / VEC / NT;    // 16-byte pieces of the weight slab per thread
+  static_assert(AP >= 1 && BP >= 1 && WR * WC == 4, "tile too small for 256 threads");
+  __shared__ __attribute__((aligned(16))) WT As[BM * ST];
+  __shared__ __attribute__((aligned(16))) WT Bs[BN * ST];
+  __shared__ float red[4];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, c = lane & 31;
+  const int tiles_n = (a.Nf + BN - 1) / BN;
+  const int L = logical_block();
+  const int gi = blockIdx.y;
+  const int m0 = (L / tiles_n) * BM, n0 = (L % tiles_n) * BN;
+  const long long layer = a.wm.base + gi * a.wm.stride;
+  const float* Xp = a.X + (a.xm.base + gi * a.xm.stride) * a.E;
+  const float* Dp = a.Dm ? a.Dm + (a.dm.base + gi * a.dm.stride) * a.E : nullptr;
+  const WT* Wp = reinterpret_cast<const WT*>(a.W) + layer * a.wsize;
+  const int K = a.K;
+
+  float4 areg[AP];
+  uint4 breg[BP];
+  auto load_slab = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < AP; ++i) {
+      const int p = tid + NT * i, row = p / (BK / 4), kc = (p % (BK / 4)) * 4;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (m0 + row < a.M && k0 + kc < K) {
+        const long long off = (long long)(m0 + row) * K + k0 + kc;
+        v = *reinterpret_cast<const float4*>(Xp + off);
+        if (Dp) {
+          const float4 d = *reinterpret_cast<const float4*>(Dp + off);
+          v.x *= d.x; v.y *= d.y; v.z *= d.z; v.w *= d.w;
+        }
+      }
+      areg[i] = v;
+    }
+#pragma unroll
+    for (int i = 0; i < BP; ++i) {
+      const int p = tid + NT * i, row = p / (BK / VEC), kc = (p % (BK / VEC)) * VEC;
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (n0 + row < a.Nf && k0 + kc < K)
+        v = *reinterpret_cast<const uint4*>(Wp + (long long)(n0 + row) * K + k0 + kc);
+      breg[i] = v;
+    }
+  };
+  auto store_slab = [&]() {
+#pragma unroll
+    for (int i = 0; i < AP; ++i) {
+      const int p = tid + NT * i, row = p / (BK / 4), kc = (p % (BK / 4)) * 4;
+      cvt_store4(&As[row * ST + kc], areg[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < BP; ++i) {
+      const int p = tid + NT * i, row = p / (BK / VEC), kc = (p % (BK / VEC)) * VEC;
+      *reinterpret_cast<uint4*>(&Bs[row * ST + kc]) = breg[i];
+    }
+  };
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+  const int wm0 = (wave / WC) * (BM / WR), wn0 = (wave % WC) * (BN / WC);
+  load_slab(0);
+  for (int k0 = 0; k0 < K; k0 += BK) {
+    __syncthreads();
+    store_slab();
+    __syncthreads();
+    if (k0 + BK < K) load_slab(k0 + BK);
+#pragma unroll
+    for (int ks = 0; ks < BK; ks += KSTEP) {
+      const WT* ap[TM];
+      const WT* bp[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) ap[i] = &As[(wm0 + i * 32 + c) * ST + ks];
+#pragma unroll
+      for (int j = 0; j < TN; ++j) bp[j] = &Bs[(wn0 + j * 32 + c) * ST + ks];
+      mma_step<TM, TN>(ap, bp, acc, g);
+    }
+  }
+
+  long long row0[TM];
+  int col0[TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) row0[i] = m0 + wm0 + i * 32;
+#pragma unroll
+  for (int j = 0; j < TN; ++j) col0[j] = n0 + wn0 + j * 32;
+  epilogue<TM, TN>(a, gi, layer, acc, row0, (long long)a.M, col0, L, red);
+}
+
+// ------------------------------------------------------------------------------------------
+// 3x3 convolution layer-batched step as an implicit GEMM: per group M = B*H*W pixels,
+// N = C output channels, K = 9*C.  A workgroup owns TH full image rows of one image (at most
+// 256 pixels = 8 blocks of 32, two per wavefront); the input patch with its one-pixel halo is
+// loaded to LDS once (zero padding materialised there) and the nine taps read it at shifted
+// offsets, while the [C_out][C_in] weight slice of each tap streams through LDS.
+// ------------------------------------------------------------------------------------------
+template <typename WT, int TN>
+__global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
+  constexpr int VEC = Op<WT>::VEC, KSTEP = Op<WT>::KSTEP, PAD = Op<WT>::PAD;
+  constexpr int TM = 2;
+  constexpr int CPMAX = 32 * TN;
+  constexpr int WP = (32 * TN * CPMAX / VEC + NT - 1) / NT;   // weight pieces per thread per tap
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  __shared__ float red[4];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, c = lane & 31;
+  const int C = a.Nf, H = a.Himg, Wd = a.Wimg, TH = a.TH;
+  const int Cp = (C + KSTEP - 1) / KSTEP * KSTEP;
+  const int CS = Cp + PAD;
+  const int PW = Wd + 2;
+  WT* patch = reinterpret_cast<WT*>(smem_raw);
+  WT* wts = patch + (TH + 2) * PW * CS;
+
+  const int L = logical_block();
+  const int gi = blockIdx.y;
+  const int tiles_per_img = (H + TH - 1) / TH;
+  const int bimg = L / tiles_per_img, y0 = (L % tiles_per_img) * TH;
+  const long long layer = a.wm.base + gi * a.wm.stride;
+  const float* Xp = a.X + (a.xm.base + gi * a.xm.stride) * a.E;
+  const float* Dp = a.Dm ? a.Dm + (a.dm.base + gi * a.dm.stride) * a.E : nullptr;
+  const WT* Wp = reinterpret_cast<const WT*>(a.W) + layer * a.wsize;
+
+  // ---- input patch -> LDS (converted to the operand type)
+  {
+    const int cq = Cp / 4;
+    const int total = (TH + 2) * PW * cq;
+    for (int p = tid; p < total; p += NT) {
+      const int pp = p / cq, c4 = (p % cq) * 4;
+      const int gy = y0 - 1 + pp / PW, gx = pp % PW - 1;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (gy >= 0 && gy < H && gx >= 0 && gx < Wd && c4 < C) {
+        const long long off = (((long long)bimg * H + gy) * Wd + gx) * C + c4;
+        v = *reinterpret_cast<const float4*>(Xp + off);
+        if (Dp) {
+          const float4 d = *reinterpret_cast<const float4*>(Dp + off);
+          v.x *= d.x; v.y *= d.y; v.z *= d.z; v.w *= d.w;
+        }
+      }
+      cvt_store4(&patch[pp * CS + c4], v);
+    }
+  }
+
+  // ---- weight slice of one tap: rows = output channel, k = input channel
+  const int wq = Cp / VEC;
+  const int wtotal = 32 * TN * wq;
+  uint4 wreg[WP];
+  auto load_w = [&](int tap) {
+#pragma unroll
+    for (int i = 0; i < WP; ++i) {
+      const int p = tid + NT * i;
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (p < wtotal) {
+        const int row = p / wq, kc = (p % wq) * VEC;
+        if (row < C && kc < C) v = *reinterpret_cast<const uint4*>(Wp + ((long long)row * 9 + tap) * C + kc);
+      }
+      wreg[i] = v;
+    }
+  };
+  auto store_w = [&]() {
+#pragma unroll
+    for (int i = 0; i < WP; ++i) {
+      const int p = tid + NT * i;
+      if (p < wtotal) {
+        const int row = p / wq, kc = (p % wq) * VEC;
+        *reinterpret_cast<uint4*>(&wts[row * CS + kc]) = wreg[i];
+      }
+    }
+  };
+
+  const int npx = min(TH, H - y0) * Wd;      // valid pixels of this tile
+  int aoff[TM];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    int p = (wave * TM + i) * 32 + c;
+    if (p >= npx) p = 0;                      // masked rows compute on pixel 0 and are dropped
+    aoff[i] = ((p / Wd) * PW + (p % Wd)) * CS;
+  }
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+  const bool wave_active = (wave * TM) * 32 < npx;
+  load_w(0);
+  for (int tap = 0; tap < 9; ++tap) {
+    __syncthreads();
+    store_w();
+    __syncthreads();
+    if (tap + 1 < 9) load_w(tap + 1);
+    if (wave_active) {
+      const int toff = ((tap / 3) * PW + (tap % 3)) * CS;
+      for (int ks = 0; ks < Cp; ks += KSTEP) {
+        const WT* ap[TM];
+        const WT* bp[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) ap[i] = patch + aoff[i] + toff + ks;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bp[j] = wts + (j * 32 + c) * CS + ks;
+        mma_step<TM, TN>(ap, bp, acc, g);
+      }
+    }
+  }
+
+  const long long img_row0 = ((long long)bimg * H + y0) * Wd;   // global pixel row of tile pixel 0
+  long long row0[TM];
+  int col0[TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) row0[i] = img_row0 + (wave * TM + i) * 32;
+#pragma unroll
+  for (int j = 0; j < TN; ++j) col0[j] = j * 32;
+  epilogue<TM, TN>(a, gi, layer, acc, row0, img_row0 + npx, col0, L, red);
+}
+
+// ------------------------------------------------------------------------------------------
+// launch configuration
+// ------------------------------------------------------------------------------------------
+int conv_tile_rows(int Himg, int Wimg, int C, int dtype) {
+  if (Wimg > 256 || Wimg < 1 || Himg < 1 || C < 1 || C > 64) return 0;
+  int thmax = 256 / Wimg;
+  if (thmax > Himg) thmax = Himg;
+  const int kstep = dtype == 0 ? 8 : 16, pad = dtype == 0 ? 4 : 8, es = dtype == 0 ? 4 : 2;
+  const int Cp = (C + kstep - 1) / kstep * kstep, CS = Cp + pad;
+  const int tn = C <= 32 ? 1 : 2;
+  while (thmax > 1 && ((size_t)(thmax + 2) * (Wimg + 2) + 32 * tn) * CS * es > 60 * 1024) --thmax;
+  const int ntiles = (Himg + thmax - 1) / thmax;
+  return (Himg + ntiles - 1) / ntiles;        // balanced tile height
+}
+
+static size_t conv_smem_bytes(const StepArgs& a, int dtype) {
+  const int kstep = dtype == 0 ? 8 : 16, pad = dtype == 0 ? 4 : 8, es = dtype == 0 ? 4 : 2;
+  const int Cp = (a.Nf + kstep - 1) / kstep * kstep, CS = Cp + pad;
+  const int tn = a.Nf <= 32 ? 1 : 2;
+  return ((size_t)(a.TH + 2) * (a.Wimg + 2) + 32 * tn) * CS * es;
+}
+
+// dense tile choice: large tiles when they still fill the chip, else 64x64
+static bool dense_big_tile(const StepArgs& a, int groups) {
+  const long long big = (long long)((a.M + 127) / 128) * ((a.Nf + 127) / 128) * groups;
+  return big >= 512;
+}
+
+int step_grid_blocks(const StepArgs& a, int layer_kind, int dtype, int groups) {
+  (void)dtype;
+  if (layer_kind == 1) {
+    const int B = a.M / (a.Himg * a.Wimg);
+    return B * ((a.Himg + a.TH - 1) / a.TH);
+  }
+  if (dense_big_tile(a, groups)) return ((a.M + 127) / 128) * ((a.Nf + 127) / 128);
+  return ((a.M + 63) / 64) * ((a.Nf + 63) / 64);
+}
+
+hipError_t launch_step(const StepArgs& a, int layer_kind, int dtype, int groups, hipStream_t s) {
+  if (groups <= 0) return hipSuccess;
+  if (layer_kind == 1) {
+    const int B = a.M / (a.Himg * a.Wimg);
+    dim3 grid(B * ((a.Himg + a.TH - 1) / a.TH), groups);
+    const size_t smem = conv_smem_bytes(a, dtype);
+    if (a.Nf <= 32) {
+      if (dtype == 0) hipLaunchKernelGGL((conv_step_kernel<float, 1>), grid, dim3(NT), smem, s, a);
+      else            hipLaunchKernelGGL((conv_step_kernel<__bf16, 1>), grid, dim3(NT), smem, s, a);
+    } else {
+      if (dtype == 0) hipLaunchKernelGGL((conv_step_kernel<float, 2>), grid, dim3(NT), smem, s, a);
+      else            hipLaunchKernelGGL((conv_step_kernel<__bf16, 2>), grid, dim3(NT), smem, s, a);
+    }
+    return hipGetLastError();
+  }
+  if (dense_big_tile(a, groups)) {
+    dim3 grid(((a.M + 127) / 128) * ((a.Nf + 127) / 128), groups);
+    if (dtype == 0) hipLaunchKernelGGL((dense_step_kernel<float, 128, 128, 2, 2>), grid, dim3(NT), 0, s, a);
+    else            hipLaunchKernelGGL((dense_step_kernel<__bf16, 128, 128, 2, 2>), grid, dim3(NT), 0, s, a);
+  } else {
+    dim3 grid(((a.M + 63) / 64) * ((a.Nf + 63) / 64), groups);
+    if (dtype == 0) hipLaunchKernelGGL((dense_step_kernel<float, 64, 64, 2, 2>), grid, dim3(NT), 0, s, a);
+    else            hipLaunchKernelGGL((dense_step_kernel<__bf16, 64, 64, 2, 2>), grid, dim3(NT), 0, s, a);
+  }
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Transfer kernels: one float4 per thread, grid = (chunks of a state, points)
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(NT) void copy_points_kernel(float* out, PtMap om, const float* in, PtMap im,
+                                                         long long E4) {
+  const long long gi = blockIdx.y;
+  const float4* src = reinterpret_cast<const float4*>(in) + (im.base + gi * im.stride) * E4;
+  float4* dst = reinterpret_cast<float4*>(out) + (om.base + gi * om.stride) * E4;
+  for (long long i = (long long)blockIdx.x * NT + threadIdx.x; i < E4; i += (long long)gridDim.x * NT) dst[i] = src[i];
+}
+__global__ __launch_bounds__(NT) void zero_points_kernel(float* out, PtMap om, long long E4) {
+  const long long gi = blockIdx.y;
+  float4* dst = reinterpret_cast<float4*>(out) + (om.base + gi * om.stride) * E4;
+  for (long long i = (long long)blockIdx.x * NT + threadIdx.x; i < E4; i += (long long)gridDim.x * NT)
+    dst[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+__global__ __launch_bounds__(NT) void correct_kernel(float* U, PtMap um, const float* V, PtMap vm, long long E4) {
+  const long long gi = blockIdx.y;
+  float4* u = reinterpret_cast<float4*>(U) + (um.base + gi * um.stride) * E4;
+  const float4* v = reinterpret_cast<const float4*>(V) + (vm.base + gi * vm.stride) * E4;
+  for (long long i = (long long)blockIdx.x * NT + threadIdx.x; i < E4; i += (long long)gridDim.x * NT) {
+    float4 x = u[i];
+    const float4 y = v[i];
+    x.x += y.x - x.x; x.y += y.y - x.y; x.z += y.z - x.z; x.w += y.w - x.w;
+    u[i] = x;
+  }
+}
+static dim3 xfer_grid(long long E4, int groups) {
+  long long bx = (E4 + NT - 1) / NT;
+  if (bx > 4096) bx = 4096;
+  if (bx < 1) bx = 1;
+  return dim3((unsigned)bx, (unsigned)groups);
+}
+hipError_t launch_copy_points(float* out, PtMap om, const float* in, PtMap im, long long E, int groups,
+                              hipStream_t s) {
+  if (groups <= 0) return hipSuccess;
+  hipLaunchKernelGGL(copy_points_kernel, xfer_grid(E / 4, groups), dim3(NT), 0, s, out, om, in, im, E / 4);
+  return hipGetLastError();
+}
+hipError_t launch_zero_points(float* out, PtMap om, long long E, int groups, hipStream_t s) {
+  if (groups <= 0) return hipSuccess;
+  hipLaunchKernelGGL(zero_points_kernel, xfer_grid(E / 4, groups), dim3(NT), 0, s, out, om, E / 4);
+  return hipGetLastError();
+}
+hipError_t launch_correct(float* U, PtMap um, const float* V, PtMap vm, long long E, int groups, hipStream_t s) {
+  if (groups <= 0) return hipSuccess;
+  hipLaunchKernelGGL(correct_kernel, xfer_grid(E / 4, groups), dim3(NT), 0, s, U, um, V, vm, E / 4);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Norm reduction: float partial sums per workgroup, summed in a fixed order in double.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(NT) void diff_sq_kernel(const float* a, const float* b, long long n4, float* partial) {
+  __shared__ float red[4];
+  const float4* x = reinterpret_cast<const float4*>(a);
+  const float4* y = reinterpret_cast<const float4*>(b);
+  float s = 0.0f;
+  for (long long i = (long long)blockIdx.x * NT + threadIdx.x; i < n4; i += (long long)gridDim.x * NT) {
+    const float4 p = x[i], q = y[i];
+    const float d0 = p.x - q.x, d1 = p.y - q.y, d2 = p.z - q.z, d3 = p.w - q.w;
+    s += (d0 * d0 + d1 * d1) + (d2 * d2 + d3 * d3);
+  }
+  s = block_sum(s, red);
+  if (threadIdx.x == 0) partial[blockIdx.x] = s;
+}
+int diff_sq_blocks(long long n) {
+  long long b = (n / 4 + NT * 4 - 1) / (NT * 4);
+  if (b > 1024) b = 1024;
+  if (b < 1) b = 1;
+  return (int)b;
+}
+hipError_t launch_diff_sq(const float* a, const float* b, long long n, float* partial, int* blocks_used,
+                          hipStream_t s) {
+  const int nb = diff_sq_blocks(n);
+  hipLaunchKernelGGL(diff_sq_kernel, dim3(nb), dim3(NT), 0, s, a, b, n / 4, partial);
+  if (blocks_used) *blocks_used = nb;
+  return hipGetLastError();
+}
+__global__ __launch_bounds__(NT) void norm_final_kernel(const float* partial, int n, double scale, double* out) {
+  __shared__ double red[NT];
+  double s = 0.0;
+  for (int i = threadIdx.x; i < n; i += NT) s += (double)partial[i];
+  red[threadIdx.x] = s;
+  __syncthreads();
+  for (int o = NT / 2; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) out[0] = sqrt(red[0]) * scale;
+}
+hipError_t launch_norm_final(const float* partial, int n, double scale, double* out, hipStream_t s) {
+  hipLaunchKernelGGL(norm_final_kernel, dim3(1), dim3(NT), 0, s, partial, n, scale, out);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Transposed parameter copies for the adjoint sweep
+// ------------------------------------------------------------------------------------------
+template <typename WT>
+__global__ __launch_bounds__(NT) void transpose_dense_kernel(const WT* W, WT* Wt, int q) {
+  __shared__ WT tile[32][33];
+  const long long layer = blockIdx.z;
+  const WT* src = W + layer * (long long)q * q;
+  WT* dst = Wt + layer * (long long)q * q;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;     // 32 x 8
+  const int x0 = blockIdx.x * 32, y0 = blockIdx.y * 32;
+  for (int j = ty; j < 32; j += 8)
+    if (y0 + j < q && x0 + tx < q) tile[j][tx] = src[(long long)(y0 + j) * q + x0 + tx];
+  __syncthreads();
+  for (int j = ty; j < 32; j += 8)
+    if (x0 + j < q && y0 + tx < q) dst[(long long)(x0 + j) * q + y0 + tx] = tile[tx][j];
+}
+template <typename WT>
+__global__ __launch_bounds__(NT) void transpose_conv_kernel(const WT* K, WT* Kt, int C, long long total) {
+  // Kt[n][i][2-dy][2-dx][o] = K[n][o][dy][dx][i]
+  for (long long idx = (long long)blockIdx.x * NT + threadIdx.x; idx < total; idx += (long long)gridDim.x * NT) {
+    const int o = idx % C;
+    long long t = idx / C;
+    const int tapf = t % 9;
+    t /= 9;
+    const int i = t % C;
+    const long long n = t / C;
+    Kt[idx] = K[((n * C + o) * 9 + (8 - tapf)) * C + i];
+  }
+}
+hipError_t launch_transpose_weights(const void* W, void* Wt, int layer_kind, int dtype, int layers, int Nf,
+                                    hipStream_t s) {
+  if (layer_kind == 0) {
+    dim3 grid((Nf + 31) / 32, (Nf + 31) / 32, layers);
+    if (dtype == 0) hipLaunchKernelGGL((transpose_dense_kernel<float>), grid, dim3(NT), 0, s, (const float*)W, (float*)Wt, Nf);
+    else hipLaunchKernelGGL((transpose_dense_kernel<uint16_t>), grid, dim3(NT), 0, s, (const uint16_t*)W, (uint16_t*)Wt, Nf);
+  } else {
+    const long long total = (long long)layers * Nf * 9 * Nf;
+    long long nb = (total + NT - 1) / NT;
+    if (nb > 65535) nb = 65535;
+    if (dtype == 0) hipLaunchKernelGGL((transpose_conv_kernel<float>), dim3((unsigned)nb), dim3(NT), 0, s, (const float*)W, (float*)Wt, Nf, total);
+    else hipLaunchKernelGGL((transpose_conv_kernel<uint16_t>), dim3((unsigned)nb), dim3(NT), 0, s, (const uint16_t*)W, (uint16_t*)Wt, Nf, total);
+  }
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Parameter gradient (dense): dW[n] = hs * G^T U[n], G = Dm[n] .* Lam[n+1]; contraction over
+// the batch.  Output tile 64x64 per workgroup, operands transposed into LDS (k = batch row
+// fastest) so the same MFMA step applies.
+// ------------------------------------------------------------------------------------------
+template <typename OT>
+__global__ __launch_bounds__(NT) void dense_grad_kernel(GradArgs a) {
+  constexpr int BK = Op<OT>::BK, ST = BK + Op<OT>::PAD, KSTEP = Op<OT>::KSTEP;
+  constexpr int BM = 64, BN = 64;
+  __shared__ __attribute__((aligned(16))) OT As[BM * ST];
+  __shared__ __attribute__((aligned(16))) OT Bs[BN * ST];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, c = lane & 31;
+  const int q = a.Nf;
+  const int tiles_n = (q + BN - 1) / BN;
+  const int L = logical_block();
+  const int gi = blockIdx.y;
+  const int m0 = (L / tiles_n) * BM, n0 = (L % tiles_n) * BN;
+  const float* Up = a.U + (a.um.base + gi * a.um.stride) * a.E;
+  const float* Lp = a.Lam + (a.lm.base + gi * a.lm.stride) * a.E;
+  const float* Dp = a.Dm + (a.dm.base + gi * a.dm.stride) * a.E;
+  float* dWp = a.dW + (long long)gi * a.wsize;
+
+  floatx16 acc[1][1];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[0][0][r] = 0.0f;
+  // each thread moves BK*64/256 elements of each operand per slab: column = tid % 64
+  const int col = tid & 63, rsub = tid >> 6;
+  const int wm0 = (wave >> 1) * 32, wn0 = (wave & 1) * 32;
+  for (int k0 = 0; k0 < a.M; k0 += BK) {
+    __syncthreads();
+#pragma unroll
+    for (int r = rsub; r < BK; r += 4) {
+      float gv = 0.0f, uv = 0.0f;
+      const int row = k0 + r;
+      if (row < a.M) {
+        if (m0 + col < q) { const long long off = (long long)row * q + m0 + col; gv = Dp[off] * Lp[off]; }
+        if (n0 + col < q) uv = Up[(long long)row * q + n0 + col];
+      }
+      As[col * ST + r] = static_cast<OT>(gv);
+      Bs[col * ST + r] = static_cast<OT>(uv);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int ks = 0; ks < BK; ks += KSTEP) {
+      const OT* ap[1] = {&As[(wm0 + c) * ST + ks]};
+      const OT* bp[1] = {&Bs[(wn0 + c) * ST + ks]};
+      mma_step<1, 1>(ap, bp, acc, g);
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int row = m0 + wm0 + 8 * (r >> 2) + 4 * g + (r & 3), cc = n0 + wn0 + c;
+    if (row < q && cc < q) dWp[(long long)row * q + cc] = a.hs * acc[0][0][r];
+  }
+}
+// db[n][o] = hs * sum over rows of Dm .* Lam (fixed order); for conv, rows = batch * pixels
+__global__ __launch_bounds__(NT) void bias_grad_kernel(GradArgs a) {
+  const int gi = blockIdx.y;
+  const float* Lp = a.Lam + (a.lm.base + gi * a.lm.stride) * a.E;
+  const float* Dp = a.Dm + (a.dm.base + gi * a.dm.stride) * a.E;
+  const int o = blockIdx.x * NT + threadIdx.x;
+  if (o >= a.Nf) return;
+  float s = 0.0f;
+  for (int r = 0; r < a.M; ++r) { const long long off = (long long)r * a.Nf + o; s += Dp[off] * Lp[off]; }
+  a.db[(long long)gi * a.Nf + o] = a.hs * s;
+}
+
+hipError_t launch_grad(const GradArgs& a, int layer_kind, int dtype, int groups, hipStream_t s) {
+  if (groups <= 0) return hipSuccess;
+  if (layer_kind != 0) return hipErrorNotSupported;
+  if (a.dW) {
+    dim3 grid(((a.Nf + 63) / 64) * ((a.Nf + 63) / 64), groups);
+    if (dtype == 0) hipLaunchKernelGGL((dense_grad_kernel<float>), grid, dim3(NT), 0, s, a);
+    else            hipLaunchKernelGGL((dense_grad_kernel<__bf16>), grid, dim3(NT), 0, s, a);
+  }
+  if (a.db) hipLaunchKernelGGL(bias_grad_kernel, dim3((a.Nf + NT - 1) / NT, groups), dim3(NT), 0, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace mgrit

@@ -1,0 +1,187 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element, on
+the same seeded inputs.  Tolerances (relative L2 per state / per layer gradient):
+  fp32 path  1e-5      bf16 operand path  2e-2
+Integer work (level maps) is compared bit-exactly in test_host_logic.py.
+"""
+import dataclasses
+
+import numpy as np
+import pytest
+
+import mgrit_inputs as I
+from oracle import mgrit_oracle as O
+from tests.gpu_util import GpuProblem, oracle_forward, oracle_adjoint, rel_l2_per_state
+
+pytestmark = pytest.mark.gpu
+
+TOL = {I.FP32: 1e-5, I.BF16: 2e-2}
+
+
+def _announce(name):
+    print(f"\n[case] {name}", flush=True)
+
+
+def _check_forward(wl, init=1, U_init=None, hist_rtol=None):
+    _announce(wl.name)
+    data = I.generate(wl)
+    gp = GpuProblem(wl, data, init=init)
+    rc, U, hist, it = gp.forward(U_init=U_init)
+    Uo, hist_o, it_o = oracle_forward(wl, data, init=init, U_init=U_init)
+    err = rel_l2_per_state(U, Uo)
+    assert err <= TOL[wl.dtype], (wl.name, err)
+    assert it == it_o
+    if hist_rtol is None:
+        hist_rtol = 1e-3 if wl.dtype == I.FP32 else 0.2
+    for a, b in zip(hist, hist_o):
+        assert abs(a - b) <= hist_rtol * max(abs(b), 1e-6), (hist, hist_o)
+    return U, Uo, hist
+
+
+# ------------------------------------------------------------------ the first benchmark config, as is
+def test_cfg1_two_level_f_relax_reproduces_serial():
+    wl = I.cfg1()
+    U, Uo, hist = _check_forward(wl)
+    data = I.generate(wl)
+    Us = O.serial_forward(data["W"], data["b"], data["u0"], wl.h, wl.layer, wl.act)
+    assert rel_l2_per_state(U, Us) <= 1e-5          # N/m = 4 cycles of F-relaxation are exact
+
+
+# ------------------------------------------------------------------ dense, reduced sizes
+DENSE_CASES = [
+    # ragged in batch and width (several tiles + a tail), 3 levels, FCF
+    I.reduced(I.cfg2(3), name="dense_fp32_q72_B37_N64_L3", q=72, B=37, N=64),
+    I.reduced(I.cfg2(2), name="dense_fp32_q264_B150_N32_L2_F", q=264, B=150, N=32, max_levels=2, relax=I.RELAX_F),
+    I.reduced(I.cfg2(2), name="dense_fp32_q8_B1_N8_m2", q=8, B=1, N=8, m=2),
+    I.reduced(I.cfg5(2), name="dense_bf16_q136_B50_N64_m4", q=136, B=50, N=64, m=4, head_classes=0),
+    I.reduced(I.cfg5(2), name="dense_bf16_q256_B130_N256_m16", q=256, B=130, N=256, head_classes=0),
+    I.reduced(I.cfg2(1), name="dense_fp32_serial_L1", q=40, B=9, N=13, max_levels=1),
+]
+
+
+@pytest.mark.parametrize("wl", DENSE_CASES, ids=lambda w: w.name)
+def test_dense_forward(wl):
+    _check_forward(wl)
+
+
+# ------------------------------------------------------------------ conv, reduced sizes
+CONV_CASES = [
+    I.reduced(I.cfg3(2), name="conv_fp32_c16_14x12_B3_N16", B=3, Himg=14, Wimg=12, N=16),
+    I.reduced(I.cfg3(2), name="conv_fp32_c8_28x28_B2_N8_tanh", B=2, C=8, N=8, act=I.TANH, m=2),
+    I.reduced(I.cfg3(1), name="conv_fp32_c40_9x7_B2_N8", B=2, C=40, Himg=9, Wimg=7, N=8, m=2, lifted_input=False),
+    I.reduced(I.cfg4(2), name="conv_bf16_c64_12x10_B2_N64_L3", B=2, Himg=12, Wimg=10, N=64),
+    I.reduced(I.cfg4(1), name="conv_bf16_c24_32x32_B1_N16_m4", B=1, C=24, N=16, m=4, max_levels=2),
+]
+
+
+@pytest.mark.parametrize("wl", CONV_CASES, ids=lambda w: w.name)
+def test_conv_forward(wl):
+    _check_forward(wl)
+
+
+# ------------------------------------------------------------------ options of the boundary
+def test_init_modes_and_user_guess():
+    wl = I.reduced(I.cfg2(2), name="dense_fp32_init", q=24, B=5, N=16, max_levels=2)
+    _check_forward(wl, init=0)
+    rng = np.random.default_rng(3)
+    Uinit = rng.standard_normal((wl.N + 1,) + wl.state_shape).astype(np.float32)
+    _check_forward(wl, init=2, U_init=Uinit)
+
+
+def test_tolerance_stop_and_rms_norm():
+    wl = I.reduced(I.cfg2(30), name="dense_fp32_tol", q=32, B=8, N=64, tol=1e-4, norm_kind=1)
+    _announce(wl.name)
+    data = I.generate(wl)
+    gp = GpuProblem(wl, data)
+    rc, U, hist, it = gp.forward()
+    Uo, hist_o, it_o = oracle_forward(wl, data)
+    assert hist[-1] <= 1e-4 and all(h > 1e-4 for h in hist[:-1])
+    assert abs(it - it_o) <= 1                 # the stopping cycle may differ by one between fp32 and fp64
+    k = min(it, it_o)
+    for a, b in zip(hist[:k - 1], hist_o[:k - 1]):
+        assert abs(a - b) <= 2e-2 * b
+
+
+def test_fixed_point_of_the_cycle():
+    """Started from serial propagation computed on the GPU, a cycle reports a residual at rounding level and
+    leaves the iterate where it is."""
+    wl = I.reduced(I.cfg2(1), name="dense_fp32_fixed_point", q=64, B=16, N=64)
+    _announce(wl.name)
+    data = I.generate(wl)
+    ser = GpuProblem(dataclasses.replace(wl, max_levels=1), data)
+    _, Us, _, _ = ser.forward()
+    gp = GpuProblem(wl, data, init=2)
+    rc, U, hist, it = gp.forward(U_init=Us)
+    assert hist[0] < 1e-5
+    assert rel_l2_per_state(U, Us) < 1e-6
+
+
+def test_residual_norm_entry_point():
+    wl = I.reduced(I.cfg2(1), name="dense_fp32_resnorm", q=48, B=7, N=32)
+    _announce(wl.name)
+    data = I.generate(wl)
+    rng = np.random.default_rng(5)
+    U = rng.standard_normal((wl.N + 1,) + wl.state_shape).astype(np.float32)
+    gp = GpuProblem(wl, data)
+    for nk in (0, 1):
+        gp.p.norm_kind = nk
+        got = gp.residual_norm(U)
+        ref = O.residual_norm(data["W"], data["b"], data["u0"], U, wl.h, wl.layer, wl.act, norm_kind=nk)
+        assert abs(got - ref) <= 1e-5 * ref
+    wlc = I.reduced(I.cfg3(1), name="conv_fp32_resnorm", B=2, Himg=10, Wimg=9, N=6, m=2)
+    data = I.generate(wlc)
+    U = rng.standard_normal((wlc.N + 1,) + wlc.state_shape).astype(np.float32)
+    gp = GpuProblem(wlc, data)
+    got = gp.residual_norm(U)
+    ref = O.residual_norm(data["W"], data["b"], data["u0"], U, wlc.h, wlc.layer, wlc.act)
+    assert abs(got - ref) <= 1e-5 * ref
+
+
+def test_repeated_runs_are_bitwise_identical():
+    wl = I.reduced(I.cfg2(3), name="dense_fp32_determinism", q=72, B=37, N=64)
+    _announce(wl.name)
+    data = I.generate(wl)
+    gp = GpuProblem(wl, data)
+    _, U1, h1, _ = gp.forward()
+    _, U2, h2, _ = gp.forward()
+    assert np.array_equal(U1, U2) and h1 == h2
+
+
+# ------------------------------------------------------------------ adjoint solve and parameter gradient
+ADJ_CASES = [
+    I.reduced(I.cfg5(3), name="adj_dense_fp32_q72_B37_N64_m4", q=72, B=37, N=64, m=4, dtype=I.FP32),
+    I.reduced(I.cfg5(2), name="adj_dense_bf16_q136_B50_N64_m4", q=136, B=50, N=64, m=4),
+    I.reduced(I.cfg5(2), name="adj_dense_fp32_relu_F_L2", q=40, B=12, N=32, m=4, dtype=I.FP32, act=I.RELU,
+              max_levels=2, relax=I.RELAX_F),
+]
+
+
+@pytest.mark.parametrize("wl", ADJ_CASES, ids=lambda w: w.name)
+def test_dense_adjoint_and_gradient(wl):
+    _announce(wl.name)
+    data = I.generate(wl)
+    # linearise about an approximate forward solve (2 cycles), as the training step does
+    Uo, _, _ = oracle_forward(wl, data, max_iter=2)
+    U = Uo.astype(np.float32)
+    lamN = I.terminal_adjoint(wl, data, U[-1])
+    gp = GpuProblem(wl, data)
+    Lam, dW, db, hist, it = gp.adjoint(U, lamN)
+    Lo, dWo, dbo, hist_o, it_o = oracle_adjoint(wl, data, U, lamN)
+    tol = TOL[wl.dtype]
+    assert rel_l2_per_state(Lam, Lo) <= tol
+    assert rel_l2_per_state(dW, dWo) <= tol
+    assert rel_l2_per_state(db, dbo) <= tol
+    assert it == it_o
+
+
+def test_conv_adjoint_states():
+    wl = I.reduced(I.cfg3(2), name="adj_conv_fp32_c16_10x9_B2_N16", B=2, Himg=10, Wimg=9, N=16, act=I.TANH)
+    _announce(wl.name)
+    data = I.generate(wl)
+    Uo, _, _ = oracle_forward(wl, data, max_iter=2)
+    U = Uo.astype(np.float32)
+    rng = np.random.default_rng(9)
+    lamN = rng.standard_normal(wl.state_shape).astype(np.float32)
+    gp = GpuProblem(wl, data)
+    Lam, _, _, hist, it = gp.adjoint(U, lamN, want_grad=False)
+    Lo, _, _, hist_o, _ = oracle_adjoint(wl, data, U, lamN)
+    assert rel_l2_per_state(Lam, Lo) <= 1e-5

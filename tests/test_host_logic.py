@@ -1,0 +1,135 @@
+"""Host-side logic of the C-ABI library that needs no GPU: exported symbols, the level maps
+(bit-exact against the oracle), workspace sizes and argument validation."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import mgrit_inputs as I
+import paper_2007_07336_amd as M
+from paper_2007_07336_amd import binding as Bd
+from oracle import mgrit_oracle as O
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "mgrit.h")).read()
+    names = set(re.findall(r"\b(mgrit_[a-z_]+)\s*\(", hdr))
+    assert {"mgrit_level_map", "mgrit_workspace_bytes", "mgrit_adjoint_workspace_bytes", "mgrit_fas_forward",
+            "mgrit_fas_adjoint", "mgrit_residual_norm"} <= names
+    L = M.lib()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_problem_struct_matches_header_field_order():
+    hdr = open(os.path.join(ROOT, "include", "mgrit.h")).read()
+    body = hdr[hdr.index("typedef struct mgrit_problem {"):hdr.index("} mgrit_problem_t;")]
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = []
+    for decl in re.findall(r"(?:int32_t|float)\s+([^;]+);", body):
+        fields += [f.strip() for f in decl.split(",")]
+    assert fields == [f[0] for f in Bd.mgrit_problem_t._fields_]
+
+
+def _problem(**kw):
+    base = dict(N=16, h=1 / 16, m=4, max_levels=2, relax=0, max_iter=2, layer=0, act=0, dtype=0, B=4, q=8)
+    base.update(kw)
+    return M.make_problem(**base)
+
+
+def test_level_maps_bit_exact_against_oracle():
+    for m in (2, 3, 4, 8, 16):
+        for N in list(range(1, 80)) + [256, 512, 1024, 4096]:
+            for max_levels in (1, 2, 3, 6):
+                for min_coarse in (0, 1, 8):
+                    p = _problem(N=N, m=m, max_levels=max_levels, min_coarse=min_coarse)
+                    try:
+                        sizes_o, fidx_o = O.level_map(N, m, max_levels, min_coarse)
+                    except ValueError:
+                        with pytest.raises(M.MgritError) as e:
+                            M.mgrit_level_map(p)
+                        assert e.value.code == Bd.MGRIT_ERR_PROBLEM
+                        continue
+                    sizes, fidx = M.mgrit_level_map(p)
+                    assert sizes == sizes_o
+                    assert all(list(map(int, a)) == b for a, b in zip(fidx_o, fidx))
+
+
+def test_benchmark_hierarchies():
+    want = {"cfg1": [16, 4], "cfg2": [256, 64, 16], "cfg3": [64, 16], "cfg4": [512, 64, 8], "cfg5": [1024, 64, 4]}
+    for k, f in I.ALL.items():
+        assert M.mgrit_level_map(M.problem_from_workload(f()))[0] == want[k]
+
+
+def test_workspace_sizes():
+    p = M.problem_from_workload(I.cfg2())
+    E = 128 * 256 * 4
+    fwd = M.mgrit_workspace_bytes(p)
+    # two coarse levels hold a state and a right-hand side per point, each fine level a C-point residual
+    assert fwd >= (2 * 65 + 2 * 17 + 65 + 17) * E
+    assert fwd < (2 * 65 + 2 * 17 + 65 + 17) * E + (1 << 20)
+    adj = M.mgrit_adjoint_workspace_bytes(p)
+    assert adj >= fwd + 256 * 256 * 256 * 4 + 256 * E
+    assert M.mgrit_workspace_bytes(_problem(m=1)) == 0
+    assert M.mgrit_workspace_bytes(_problem(q=12)) == 0
+
+
+# Non-null, 256-byte aligned and never dereferenced: every call below passes workspace_bytes = 0 (or 8),
+# so even a problem that is valid is turned away with MGRIT_ERR_WORKSPACE before anything is launched.
+FAKE = 1 << 20
+
+
+def _fwd(p, W=FAKE, b=FAKE, u0=FAKE, U=FAKE, ws=FAKE, ws_bytes=0):
+    return M.lib().mgrit_fas_forward(ctypes.byref(p), W, b, u0, U, None, None, ws, ws_bytes, None)
+
+
+def test_forward_argument_validation():
+    p = _problem()
+    assert _fwd(p, W=None) == Bd.MGRIT_ERR_POINTER
+    assert _fwd(p, U=None) == Bd.MGRIT_ERR_POINTER
+    assert _fwd(p, u0=FAKE + 4) == Bd.MGRIT_ERR_POINTER              # misaligned
+    assert _fwd(p, ws=None) == Bd.MGRIT_ERR_POINTER
+    assert _fwd(p) == Bd.MGRIT_ERR_WORKSPACE
+    assert _fwd(p, ws_bytes=M.mgrit_workspace_bytes(p) - 1) == Bd.MGRIT_ERR_WORKSPACE
+    for bad in (dict(N=0), dict(m=1), dict(max_levels=0), dict(max_levels=17), dict(relax=2), dict(cycle=1),
+                dict(max_iter=0), dict(norm_kind=2), dict(layer=2), dict(act=5), dict(dtype=3), dict(init=3),
+                dict(h=0.0), dict(B=0), dict(q=0), dict(N=18, m=4), dict(N=24, m=4, max_levels=3)):
+        assert _fwd(_problem(**bad)) == Bd.MGRIT_ERR_PROBLEM, bad
+    for uns in (dict(q=12), dict(layer=1, C=12, Himg=4, Wimg=4), dict(layer=1, C=128, Himg=4, Wimg=4),
+                dict(layer=1, C=16, Himg=4, Wimg=300)):
+        assert _fwd(_problem(**uns)) == Bd.MGRIT_ERR_UNSUPPORTED, uns
+    assert _fwd(_problem(layer=1, C=0, Himg=4, Wimg=4)) == Bd.MGRIT_ERR_PROBLEM
+
+
+def test_adjoint_and_norm_argument_validation():
+    L = M.lib()
+    p = _problem()
+    rc = L.mgrit_fas_adjoint(ctypes.byref(p), FAKE, FAKE, FAKE, None, FAKE, None, None, None, None, FAKE, 0, None)
+    assert rc == Bd.MGRIT_ERR_POINTER
+    rc = L.mgrit_fas_adjoint(ctypes.byref(p), FAKE, FAKE, FAKE, FAKE, FAKE, None, None, None, None, FAKE, 8, None)
+    assert rc == Bd.MGRIT_ERR_WORKSPACE
+    rc = L.mgrit_residual_norm(ctypes.byref(p), FAKE, FAKE, FAKE, FAKE, None, FAKE, 0, None)
+    assert rc == Bd.MGRIT_ERR_POINTER
+    out = ctypes.c_double()
+    rc = L.mgrit_residual_norm(ctypes.byref(p), FAKE, FAKE, FAKE, FAKE, ctypes.byref(out), FAKE, 8, None)
+    assert rc == Bd.MGRIT_ERR_WORKSPACE
+    rc = L.mgrit_level_map(None, None, None, None)
+    assert rc == Bd.MGRIT_ERR_POINTER
+
+
+def test_inputs_are_reproducible_and_bf16_exact():
+    import numpy as np
+    wl = I.reduced(I.cfg5(1), q=16, B=3, N=4, m=2)
+    a, b = I.generate(wl), I.generate(wl)
+    assert all(np.array_equal(a[k], b[k]) for k in a)
+    W = a["W"]
+    assert np.array_equal(W.view(np.uint32) & 0xFFFF, np.zeros(W.shape, np.uint32))
+    x = np.array([1.0, 1.00390625, 1.005859375, -1.01171875, 3.0e38], np.float32)
+    # ties to even: 1 + 2^-8 (exact tie between 1 and 1 + 2^-7) rounds to 1
+    assert list(I.round_to_bf16(x)[:2]) == [1.0, 1.0]
+    import torch
+    ref = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(I.round_to_bf16(x), ref)
