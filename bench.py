@@ -1,0 +1,220 @@
+#!/usr/bin/env python3
+"""Benchmark of the MGRIT-FAS hot path on one MI355X.
+
+One "step" is one pass of the whole path over one synthetic batch: a forward FAS solve of
+`--cycles` V-cycles (relaxation, C-point residual + norm, injection, FAS right-hand side, coarse
+solve, correction), then the adjoint solve of as many cycles about the computed states (act'
+cache, adjoint relaxation and transfers) and the parameter gradient.  Inputs are resident in HBM
+before the timed region.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2] [--cycles 2]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK = {"fp32_mfma": 157.3, "bf16_mfma": 2500.0}       # TFLOP/s, published dense peaks of MI355X
+
+
+def layer_steps_per_solve(sizes, m, relax, iters):
+    """Layer-step evaluations (one u + h F(u) for the whole batch at one point of one level) that
+    a solve of `iters` V-cycles performs -- mirrors the launch schedule exactly."""
+    L = len(sizes)
+    if L == 1:
+        return sizes[0]
+
+    def cyc(l, opening):
+        if l == L - 1:
+            return sizes[l]
+        Nc = sizes[l + 1]
+        n = (m - 1) * Nc if opening else 0
+        if relax == 1:
+            n += Nc + (m - 1) * Nc
+        n += Nc                      # C-point residual
+        n += Nc                      # FAS right-hand side (coarse step)
+        n += cyc(l + 1, True)
+        n += (m - 1) * Nc            # F-relaxation after the correction
+        return n
+
+    return sum(cyc(0, k == 0) for k in range(iters))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--cycles", type=int, default=2, help="V-cycles per forward / adjoint solve (Sec. IV-A: two)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip time-to-tolerance and serial comparisons")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import mgrit_inputs as I
+    import paper_2007_07336_amd as M
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    wl = I.ALL[args.workload](args.cycles)
+    adjoint = wl.layer == I.DENSE          # parameter gradient kernels exist for dense layers
+    data = I.generate(wl)
+    p = M.problem_from_workload(wl)
+    sizes, _ = M.mgrit_level_map(p)
+    W = torch.from_numpy(data["W"]).to(dev)
+    if wl.dtype == I.BF16:
+        W = W.to(torch.bfloat16)
+    b = torch.from_numpy(data["b"]).to(dev)
+    u0 = torch.from_numpy(data["u0"]).to(dev)
+    U = torch.zeros((wl.N + 1,) + wl.state_shape, dtype=torch.float32, device=dev)
+    ws = torch.empty(M.mgrit_adjoint_workspace_bytes(p) if adjoint else M.mgrit_workspace_bytes(p),
+                     dtype=torch.uint8, device=dev)
+    if adjoint:
+        rng = np.random.default_rng(1)
+        if wl.head_classes:
+            lamN_np = None
+        else:
+            lamN_np = rng.standard_normal(wl.state_shape).astype(np.float32) / wl.B
+        Lam = torch.zeros_like(U)
+        dW = torch.zeros(W.shape, dtype=torch.float32, device=dev)
+        db = torch.zeros_like(b)
+        lamN = torch.zeros(wl.state_shape, dtype=torch.float32, device=dev)
+        if lamN_np is not None:
+            lamN.copy_(torch.from_numpy(lamN_np))
+
+    def step():
+        M.mgrit_fas_forward(p, W, b, u0, U, ws, want_hist=False)
+        if adjoint:
+            M.mgrit_fas_adjoint(p, W, b, U, lamN, Lam, dW, db, ws, want_hist=False)
+
+    if adjoint and wl.head_classes:       # terminal adjoint of the softmax head from a first forward solve
+        M.mgrit_fas_forward(p, W, b, u0, U, ws, want_hist=False)
+        torch.cuda.synchronize()
+        lamN.copy_(torch.from_numpy(I.terminal_adjoint(wl, data, U[-1].cpu().numpy())))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    fwd_steps = layer_steps_per_solve(sizes, wl.m, wl.relax, args.cycles)
+    steps_per_step = fwd_steps
+    if adjoint:
+        steps_per_step += wl.N                 # act' cache: one affine map per layer
+        steps_per_step += fwd_steps            # adjoint solve
+        steps_per_step += wl.N                 # parameter gradient: one contraction per layer
+    value = steps_per_step / (ms_per_step * 1e-3)
+
+    # ---- roofline of the dominant kernel: same steps again with the library's event trace on
+    M.mgrit_trace_begin()
+    for _ in range(args.steps):
+        step()
+    tr = M.mgrit_trace_end()
+    torch.cuda.synchronize()
+    step_classes = {k: v for k, v in tr.items() if k != "dense_grad_kernel"}
+    dom = max(step_classes, key=lambda k: step_classes[k][0])
+    ms_tot, launches, units = step_classes[dom]
+    if wl.layer == I.DENSE:
+        flops_per_unit = 2.0 * wl.B * wl.q * wl.q
+        bytes_per_unit = wl.q * wl.q * (4 if wl.dtype == I.FP32 else 2) + 2 * wl.B * wl.q * 4
+    else:
+        flops_per_unit = 2.0 * wl.B * wl.Himg * wl.Wimg * wl.C * 9 * wl.C
+        bytes_per_unit = 9 * wl.C * wl.C * (4 if wl.dtype == I.FP32 else 2) + 2 * wl.E * 4
+    peak = PEAK["fp32_mfma"] if wl.dtype == I.FP32 else PEAK["bf16_mfma"]
+    avg_us = ms_tot * 1e3 / launches
+    achieved = units * flops_per_unit / (ms_tot * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 3), "peak": peak,
+                "unit": "TFLOP/s", "frac": round(achieved / peak, 5), "traffic": None,
+                "launches": launches, "avg_launch_us": round(avg_us, 3),
+                "flops_per_launch": units * flops_per_unit / launches,
+                "algorithmic_bytes_per_launch": units * bytes_per_unit / launches,
+                "hbm_GBps_algorithmic": round(units * bytes_per_unit / (ms_tot * 1e-3) / 1e9, 1),
+                "all_kernels_ms": {k: round(v[0] / args.steps, 4) for k, v in tr.items()}}
+
+    out = {"metric": "layer-steps/sec per FAS cycle (forward + adjoint + gradient), 1xMI355X",
+           "value": round(value, 1), "unit": "layer-steps/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None,
+           "dtype": "f32" if wl.dtype == I.FP32 else "bf16", "data": "synthetic",
+           "config": {"workload": wl.name, "levels": sizes, "m": wl.m, "relax": "FCF" if wl.relax else "F",
+                      "cycles_per_solve": args.cycles, "layer_steps_per_step": steps_per_step,
+                      "sample_steps_per_s": round(value * wl.B, 1), "adjoint": adjoint},
+           "roofline": roofline}
+
+    # ---- time to tolerance and the serial comparisons the metric names
+    if not args.no_extras:
+        def timed(fn, reps=10):
+            fn()
+            torch.cuda.synchronize()
+            ts = []
+            for _ in range(reps):
+                a = time.perf_counter()
+                fn()
+                torch.cuda.synchronize()
+                ts.append((time.perf_counter() - a) * 1e3)
+            return float(np.median(ts))
+
+        p_tol = M.problem_from_workload(wl, max_iter=40, tol=1e-6, norm_kind=1)
+        ws_tol = torch.empty(M.mgrit_workspace_bytes(p_tol), dtype=torch.uint8, device=dev)
+        res = {}
+
+        def solve_tol():
+            res["r"] = M.mgrit_fas_forward(p_tol, W, b, u0, U, ws_tol)
+        t_tol = timed(solve_tol, 5)
+        p_ser = M.problem_from_workload(wl, max_levels=1)
+        t_ser = timed(lambda: M.mgrit_fas_forward(p_ser, W, b, u0, U, ws_tol, want_hist=False))
+        p_one = M.problem_from_workload(wl, max_iter=1)
+        t_one = timed(lambda: M.mgrit_fas_forward(p_one, W, b, u0, U, ws, want_hist=False))
+        t_two = timed(lambda: M.mgrit_fas_forward(p, W, b, u0, U, ws, want_hist=False))
+        out["extras"] = {"time_to_rms_1e-6_ms": round(t_tol, 3), "cycles_to_rms_1e-6": res["r"][2],
+                         "final_rms_residual": res["r"][1][-1],
+                         "serial_forward_gpu_ms": round(t_ser, 3),
+                         "forward_1_cycle_ms": round(t_one, 3), "forward_%d_cycles_ms" % args.cycles: round(t_two, 3),
+                         "forward_cycle_layer_steps_per_s":
+                             round(layer_steps_per_solve(sizes, wl.m, wl.relax, 1) / (t_one * 1e-3), 1)}
+
+    # ---- the CPU oracle on the host cores, same workload, bounded sample
+    if not args.no_cpu_baseline:
+        from oracle import mgrit_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([d.get("num_threads", 1) for d in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        small = wl.N * (2.0 * wl.E * (wl.q if wl.layer == I.DENSE else 9 * wl.C)) < 3e10
+        cyc = args.cycles if small else 1
+        a = time.perf_counter()
+        Uo, _, _ = O.fas_forward(data["W"], data["b"], data["u0"], wl.h, wl.m, wl.max_levels, wl.min_coarse,
+                                 wl.relax, cyc, wl.layer, wl.act)
+        n_cpu = layer_steps_per_solve(sizes, wl.m, wl.relax, cyc) + (cyc - 1) * (wl.m - 1) * sizes[1]
+        sample = "forward solve of %d cycle(s)" % cyc
+        if adjoint and small:
+            lam_np = lamN.cpu().numpy()
+            O.fas_adjoint(data["W"], data["b"], Uo, lam_np, wl.h, wl.m, wl.max_levels, wl.min_coarse, wl.relax,
+                          cyc, wl.layer, wl.act)
+            n_cpu = 2 * n_cpu + 2 * wl.N
+            sample += " + adjoint solve + gradient"
+        dt = time.perf_counter() - a
+        out["cpu_baseline"] = {"value": round(n_cpu / dt, 1), "unit": "layer-steps/s", "cores": int(cores),
+                               "kind": "oracle", "sample": sample + " of %s (fp64 numpy, %.1f s)" % (wl.name, dt)}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

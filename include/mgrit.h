@@ -11,7 +11,8 @@
  *
  * Memory.  The caller owns every buffer.  Pointers marked "device" are HIP device pointers
  * aligned to 256 bytes; pointers marked "host" are ordinary host pointers.  The library
- * allocates no device memory and keeps no state between calls.  All device work is enqueued
+ * allocates no device memory and keeps no state between calls (the optional launch trace at
+ * the end of this file aside).  All device work is enqueued
  * on `hip_stream` (a hipStream_t passed as void*; NULL = the default stream).  A call that
  * writes a host output (resnorm_hist, iters_done, norm_out) synchronises that stream before
  * it returns; otherwise it returns with its work in flight on the stream.
@@ -134,6 +135,20 @@ int32_t mgrit_fas_adjoint(const mgrit_problem_t* p, const void* W, const float* 
 int32_t mgrit_residual_norm(const mgrit_problem_t* p, const void* W, const float* b, const float* u0,
                             const float* U, double* norm_out,
                             void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Diagnostic launch tracing, off by default and the one piece of state the library keeps: between
+ * mgrit_trace_begin() and mgrit_trace_end() every layer-step and gradient launch is bracketed by a
+ * pair of HIP events on its stream.  mgrit_trace_end synchronises on the last event and returns,
+ * per kernel class (MGRIT_TRACE_*), the summed elapsed milliseconds, the number of launches and the
+ * number of layer steps (groups) they processed; arrays of n_classes entries, host.  Not thread
+ * safe; meant for the benchmark's roofline figures (Sec. IV-B reports such a timeline). */
+enum {
+  MGRIT_TRACE_DENSE_F32_T64 = 0, MGRIT_TRACE_DENSE_F32_T128, MGRIT_TRACE_DENSE_BF16_T64,
+  MGRIT_TRACE_DENSE_BF16_T128, MGRIT_TRACE_CONV_F32, MGRIT_TRACE_CONV_BF16, MGRIT_TRACE_GRAD,
+  MGRIT_TRACE_NCLASS
+};
+void    mgrit_trace_begin(void);
+int32_t mgrit_trace_end(double* ms, int64_t* launches, int64_t* units, int32_t n_classes);
 
 #ifdef __cplusplus
 }

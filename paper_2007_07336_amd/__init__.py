@@ -6,5 +6,5 @@ this package is its thin Python binding.
 from .binding import (  # noqa: F401
     MgritError, mgrit_problem_t, make_problem, problem_from_workload, lib,
     mgrit_level_map, mgrit_workspace_bytes, mgrit_adjoint_workspace_bytes,
-    mgrit_fas_forward, mgrit_fas_adjoint, mgrit_residual_norm,
+    mgrit_fas_forward, mgrit_fas_adjoint, mgrit_residual_norm, mgrit_trace_begin, mgrit_trace_end,
 )

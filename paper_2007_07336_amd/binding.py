@@ -61,6 +61,11 @@ def lib() -> ctypes.CDLL:
         L.mgrit_fas_adjoint.restype = ctypes.c_int32
         L.mgrit_residual_norm.argtypes = [P, vp, vp, vp, vp, dp, vp, ctypes.c_size_t, vp]
         L.mgrit_residual_norm.restype = ctypes.c_int32
+        L.mgrit_trace_begin.argtypes = []
+        L.mgrit_trace_begin.restype = None
+        L.mgrit_trace_end.argtypes = [dp, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64),
+                                      ctypes.c_int32]
+        L.mgrit_trace_end.restype = ctypes.c_int32
         _lib = L
     return _lib
 
@@ -155,3 +160,24 @@ def mgrit_residual_norm(p: mgrit_problem_t, W, b, u0, U, workspace, *, stream=No
     if check and rc != MGRIT_OK:
         raise MgritError(rc, "mgrit_residual_norm")
     return rc, out.value
+
+
+TRACE_CLASSES = ("dense_step_kernel<float,64,64>", "dense_step_kernel<float,128,128>",
+                 "dense_step_kernel<bf16,64,64>", "dense_step_kernel<bf16,128,128>",
+                 "conv_step_kernel<float>", "conv_step_kernel<bf16>", "dense_grad_kernel")
+
+
+def mgrit_trace_begin() -> None:
+    lib().mgrit_trace_begin()
+
+
+def mgrit_trace_end() -> dict:
+    """{kernel class: (total ms, launches, layer steps)} of the launches since mgrit_trace_begin()."""
+    n = len(TRACE_CLASSES)
+    ms = (ctypes.c_double * n)()
+    la = (ctypes.c_int64 * n)()
+    un = (ctypes.c_int64 * n)()
+    rc = lib().mgrit_trace_end(ms, la, un, n)
+    if rc != MGRIT_OK:
+        raise MgritError(rc, "mgrit_trace_end")
+    return {TRACE_CLASSES[i]: (ms[i], la[i], un[i]) for i in range(n) if la[i] > 0}

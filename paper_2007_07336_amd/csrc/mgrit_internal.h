@@ -84,4 +84,10 @@ hipError_t launch_norm_final(const float* partial, int n, double scale, double* 
 hipError_t launch_transpose_weights(const void* W, void* Wt, int layer_kind, int dtype, int layers, int Nf,
                                     hipStream_t s);
 
+// launch tracing (diagnostic): kernel classes, and begin / collect
+enum { TRACE_DENSE_F32_64 = 0, TRACE_DENSE_F32_128, TRACE_DENSE_BF16_64, TRACE_DENSE_BF16_128,
+       TRACE_CONV_F32, TRACE_CONV_BF16, TRACE_GRAD, TRACE_NCLASS };
+void trace_begin();
+int  trace_end(double* ms, long long* launches, long long* units, int ncls);
+
 }  // namespace mgrit

@@ -3,6 +3,8 @@
 // bandwidth-bound transfer kernels, the norm reduction and the parameter-gradient kernel.
 #include "mgrit_internal.h"
 
+#include <vector>
+
 namespace mgrit {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
@@ -10,6 +12,55 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int NT = 256;  // threads per workgroup (4 wavefronts of 64)
+
+// ------------------------------------------------------------------------------------------
+// Optional launch tracing (diagnostic, off by default): brackets every step / gradient launch
+// with a pair of HIP events on the launch stream and sums elapsed time per kernel class.
+// ------------------------------------------------------------------------------------------
+namespace {
+struct Trace {
+  bool on = false;
+  std::vector<hipEvent_t> ev;       // pairs
+  std::vector<int> cls;
+  std::vector<long long> units;
+  size_t used = 0;                  // pairs in use
+} g_trace;
+
+void trace_before(hipStream_t s) {
+  if (!g_trace.on) return;
+  if (g_trace.used * 2 + 2 > g_trace.ev.size()) {
+    hipEvent_t a, b;
+    if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { g_trace.on = false; return; }
+    g_trace.ev.push_back(a);
+    g_trace.ev.push_back(b);
+  }
+  (void)hipEventRecord(g_trace.ev[g_trace.used * 2], s);
+}
+void trace_after(hipStream_t s, int cls, long long units) {
+  if (!g_trace.on) return;
+  (void)hipEventRecord(g_trace.ev[g_trace.used * 2 + 1], s);
+  if (g_trace.cls.size() <= g_trace.used) { g_trace.cls.resize(g_trace.used + 1); g_trace.units.resize(g_trace.used + 1); }
+  g_trace.cls[g_trace.used] = cls;
+  g_trace.units[g_trace.used] = units;
+  ++g_trace.used;
+}
+}  // namespace
+
+void trace_begin() { g_trace.on = true; g_trace.used = 0; }
+int trace_end(double* ms, long long* launches, long long* units, int ncls) {
+  g_trace.on = false;
+  for (int i = 0; i < ncls; ++i) { ms[i] = 0.0; launches[i] = 0; units[i] = 0; }
+  if (g_trace.used == 0) return 0;
+  if (hipEventSynchronize(g_trace.ev[g_trace.used * 2 - 1]) != hipSuccess) return -1;
+  for (size_t i = 0; i < g_trace.used; ++i) {
+    float t = 0.0f;
+    if (hipEventElapsedTime(&t, g_trace.ev[2 * i], g_trace.ev[2 * i + 1]) != hipSuccess) return -1;
+    const int c = g_trace.cls[i];
+    if (c >= 0 && c < ncls) { ms[c] += t; launches[c] += 1; units[c] += g_trace.units[i]; }
+  }
+  g_trace.used = 0;
+  return 0;
+}
 
 // ------------------------------------------------------------------------------------------
 // Operand traits.  Matrix-core operands live in LDS as rows of KSTEP-multiples, k fastest.
@@ -421,10 +472,13 @@ int step_grid_blocks(const StepArgs& a, int layer_kind, int dtype, int groups) {
 
 hipError_t launch_step(const StepArgs& a, int layer_kind, int dtype, int groups, hipStream_t s) {
   if (groups <= 0) return hipSuccess;
+  trace_before(s);
+  int cls;
   if (layer_kind == 1) {
     const int B = a.M / (a.Himg * a.Wimg);
     dim3 grid(B * ((a.Himg + a.TH - 1) / a.TH), groups);
     const size_t smem = conv_smem_bytes(a, dtype);
+    cls = dtype == 0 ? TRACE_CONV_F32 : TRACE_CONV_BF16;
     if (a.Nf <= 32) {
       if (dtype == 0) hipLaunchKernelGGL((conv_step_kernel<float, 1>), grid, dim3(NT), smem, s, a);
       else            hipLaunchKernelGGL((conv_step_kernel<__bf16, 1>), grid, dim3(NT), smem, s, a);
@@ -432,18 +486,20 @@ hipError_t launch_step(const StepArgs& a, int layer_kind, int dtype, int groups,
       if (dtype == 0) hipLaunchKernelGGL((conv_step_kernel<float, 2>), grid, dim3(NT), smem, s, a);
       else            hipLaunchKernelGGL((conv_step_kernel<__bf16, 2>), grid, dim3(NT), smem, s, a);
     }
-    return hipGetLastError();
-  }
-  if (dense_big_tile(a, groups)) {
+  } else if (dense_big_tile(a, groups)) {
     dim3 grid(((a.M + 127) / 128) * ((a.Nf + 127) / 128), groups);
+    cls = dtype == 0 ? TRACE_DENSE_F32_128 : TRACE_DENSE_BF16_128;
     if (dtype == 0) hipLaunchKernelGGL((dense_step_kernel<float, 128, 128, 2, 2>), grid, dim3(NT), 0, s, a);
     else            hipLaunchKernelGGL((dense_step_kernel<__bf16, 128, 128, 2, 2>), grid, dim3(NT), 0, s, a);
   } else {
     dim3 grid(((a.M + 63) / 64) * ((a.Nf + 63) / 64), groups);
+    cls = dtype == 0 ? TRACE_DENSE_F32_64 : TRACE_DENSE_BF16_64;
     if (dtype == 0) hipLaunchKernelGGL((dense_step_kernel<float, 64, 64, 2, 2>), grid, dim3(NT), 0, s, a);
     else            hipLaunchKernelGGL((dense_step_kernel<__bf16, 64, 64, 2, 2>), grid, dim3(NT), 0, s, a);
   }
-  return hipGetLastError();
+  const hipError_t e = hipGetLastError();
+  trace_after(s, cls, groups);
+  return e;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -658,13 +714,16 @@ __global__ __launch_bounds__(NT) void bias_grad_kernel(GradArgs a) {
 hipError_t launch_grad(const GradArgs& a, int layer_kind, int dtype, int groups, hipStream_t s) {
   if (groups <= 0) return hipSuccess;
   if (layer_kind != 0) return hipErrorNotSupported;
+  trace_before(s);
   if (a.dW) {
     dim3 grid(((a.Nf + 63) / 64) * ((a.Nf + 63) / 64), groups);
     if (dtype == 0) hipLaunchKernelGGL((dense_grad_kernel<float>), grid, dim3(NT), 0, s, a);
     else            hipLaunchKernelGGL((dense_grad_kernel<__bf16>), grid, dim3(NT), 0, s, a);
   }
   if (a.db) hipLaunchKernelGGL(bias_grad_kernel, dim3((a.Nf + NT - 1) / NT, groups), dim3(NT), 0, s, a);
-  return hipGetLastError();
+  const hipError_t e = hipGetLastError();
+  trace_after(s, TRACE_GRAD, groups);
+  return e;
 }
 
 }  // namespace mgrit
