@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libmgrit.so")
-SOURCES = ["mgrit_api.hip", "mgrit_kernels.hip"]
+SOURCES = ["mgrit_api.hip", "mgrit_kernels.hip", "mgrit_chain.hip"]
 
 
 def hipcc() -> str:
@@ -23,6 +23,10 @@ def build(verbose: bool = True) -> str:
     objs = []
     flags = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17",
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+             # the 256x256 tile holds 256 accumulator registers per lane; its fully unrolled epilogue is
+             # past the default cost limit of `#pragma unroll`, and a loop left rolled would index the
+             # accumulators dynamically and push them to scratch memory
+             "-mllvm", "-pragma-unroll-threshold=200000",
              "-I", os.path.join(ROOT, "include")]
     procs = []
     for src in SOURCES:

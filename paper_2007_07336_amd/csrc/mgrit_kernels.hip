@@ -26,6 +26,8 @@ struct Trace {
   size_t used = 0;                  // pairs in use
 } g_trace;
 
+}  // namespace
+
 void trace_before(hipStream_t s) {
   if (!g_trace.on) return;
   if (g_trace.used * 2 + 2 > g_trace.ev.size()) {
@@ -44,7 +46,6 @@ void trace_after(hipStream_t s, int cls, long long units) {
   g_trace.units[g_trace.used] = units;
   ++g_trace.used;
 }
-}  // namespace
 
 void trace_begin() { g_trace.on = true; g_trace.used = 0; }
 int trace_end(double* ms, long long* launches, long long* units, int ncls) {
@@ -72,13 +73,11 @@ template <> struct Op<float> {
   static constexpr int KSTEP = 8;   // k consumed by one mma_step
   static constexpr int VEC = 4;     // elements per 16-byte piece
   static constexpr int PAD = 4;     // row padding in LDS (elements)
-  static constexpr int BK = 16;     // k per LDS stage of the dense kernel
 };
 template <> struct Op<__bf16> {
   static constexpr int KSTEP = 16;
   static constexpr int VEC = 8;
   static constexpr int PAD = 8;
-  static constexpr int BK = 32;
 };
 
 __device__ __forceinline__ void cvt_store4(float* dst, float4 v) { *reinterpret_cast<float4*>(dst) = v; }
@@ -126,13 +125,26 @@ __device__ __forceinline__ void mma_step(const __bf16* const (&ap)[TM], const __
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
 }
 
+__device__ __forceinline__ floatx16 zero16() {
+  floatx16 z;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) z[r] = 0.0f;
+  return z;
+}
+// tanh(z) = 1 - 2 / (e^{2z} + 1) on the hardware exp2 / rcp units: absolute error about 2e-7
+// (the library tanhf costs ~100 instructions per element, which dominated the epilogue).  The
+// result enters the state scaled by h, so the absolute error is what matters.
+__device__ __forceinline__ float fast_tanh(float z) {
+  const float e = __builtin_amdgcn_exp2f(z * 2.885390081777927f);      // e^{2z}; inf / 0 saturate correctly
+  return 1.0f - 2.0f * __builtin_amdgcn_rcpf(e + 1.0f);
+}
 __device__ __forceinline__ float act_fn(float z, int act) {
-  if (act == ACT_TANH) return tanhf(z);
+  if (act == ACT_TANH) return fast_tanh(z);
   if (act == ACT_RELU) return fmaxf(z, 0.0f);
   return z;
 }
 __device__ __forceinline__ float act_prime(float z, int act) {
-  if (act == ACT_TANH) { float t = tanhf(z); return 1.0f - t * t; }
+  if (act == ACT_TANH) { float t = fast_tanh(z); return 1.0f - t * t; }
   if (act == ACT_RELU) return z > 0.0f ? 1.0f : 0.0f;
   return 1.0f;
 }
@@ -156,49 +168,114 @@ __device__ __forceinline__ int logical_block() {
   return L;
 }
 
-// Fused epilogue shared by the dense and the conv kernel.  Accumulator block (tm,tn), register
-// r of lane (g, c): row = row0[tm] + 8*(r/4) + 4*g + r%4, column = col0[tn] + c.
+// Fused epilogue shared by the dense and the conv kernel, one 32x32 accumulator block at a time:
+// register r of lane (g, c) holds row = row0 + 8*(r/4) + 4*g + r%4, column = col0 + c.
+struct EpiPtrs {
+  const float* Xp;
+  float* Op_;
+  const float* E1p;
+  const float* E2p;
+  const float* bp;
+};
+__device__ __forceinline__ EpiPtrs epi_ptrs(const StepArgs& a, int gi, long long layer) {
+  EpiPtrs e;
+  e.Xp = a.X + (a.xm.base + gi * a.xm.stride) * a.E;
+  e.Op_ = a.Out ? a.Out + (a.om.base + gi * a.om.stride) * a.E : nullptr;
+  e.E1p = a.E1 ? a.E1 + (a.e1m.base + gi * a.e1m.stride) * a.E : nullptr;
+  e.E2p = a.E2 ? a.E2 + (a.e2m.base + gi * a.e2m.stride) * a.E : nullptr;
+  e.bp = a.bias ? a.bias + layer * a.Nf : nullptr;
+  return e;
+}
+// The accumulators of a wavefront's sub-tile go through an LDS staging buffer so that global
+// memory is touched in whole rows: a lane handles 4 consecutive columns (one float4) and a wave
+// instruction covers 64 / (8 TN) full rows of the sub-tile.  Per 32-row block row: registers ->
+// stage (column-consecutive lanes), then batches of row reads with all global loads of a batch
+// issued before its arithmetic and stores.  `stage_all` is workgroup LDS of at least
+// 4 * 32 * (32 TN + 4) floats that the main loop no longer needs.
 template <int TM, int TN>
 __device__ __forceinline__ void epilogue(const StepArgs& a, int gi, long long layer, floatx16 (&acc)[TM][TN],
-                                         const long long (&row0)[TM], long long row_end,
-                                         const int (&col0)[TN], int L, float* red) {
-  const int lane = threadIdx.x & 63, g = lane >> 5, c = lane & 31;
-  const float* Xp = a.X + (a.xm.base + gi * a.xm.stride) * a.E;
-  float* Op_ = a.Out ? a.Out + (a.om.base + gi * a.om.stride) * a.E : nullptr;
-  const float* E1p = a.E1 ? a.E1 + (a.e1m.base + gi * a.e1m.stride) * a.E : nullptr;
-  const float* E2p = a.E2 ? a.E2 + (a.e2m.base + gi * a.e2m.stride) * a.E : nullptr;
-  const float* bp = a.bias ? a.bias + layer * a.Nf : nullptr;
+                                         const long long (&row0)[TM], long long row_end, int colbase, int L,
+                                         float* red, float* stage_all) {
+  constexpr int SW = TN * 32 + 4;            // staging row stride in floats
+  constexpr int LPR = TN * 8;                // lanes per sub-tile row
+  constexpr int RPI = 64 / LPR;              // rows per wave instruction
+  constexpr int NIT = 32 / RPI;              // instructions per block row
+  constexpr int HB = TN >= 4 ? 8 : 4;        // instructions batched together (register budget)
+  const EpiPtrs e = epi_ptrs(a, gi, layer);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 5, c = lane & 31;
+  float* stage = stage_all + wave * 32 * SW;
+  const int lrow = lane / LPR, colq = (lane % LPR) * 4;
+  const int col = colbase + colq;
+  const bool colok = col < a.Nf;
+  float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (colok && e.bp) bv = *reinterpret_cast<const float4*>(e.bp + col);
+  const bool dact = a.mode == MODE_DACT;
   float sq = 0.0f;
+  __syncthreads();                           // every wave is done reading the main loop's LDS tiles
 #pragma unroll
-  for (int tn = 0; tn < TN; ++tn) {
-    const int col = col0[tn] + c;
-    if (col >= a.Nf) continue;
-    const float bv = bp ? bp[col] : 0.0f;
+  for (int tm = 0; tm < TM; ++tm) {
 #pragma unroll
-    for (int tm = 0; tm < TM; ++tm) {
+    for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const long long row = row0[tm] + 8 * (r >> 2) + 4 * g + (r & 3);
-        if (row >= row_end) continue;
-        const long long off = row * a.Nf + col;
-        const float z = acc[tm][tn][r] + bv;
-        float o;
-        if (a.mode == MODE_DACT) {
-          o = act_prime(z, a.act);
+      for (int r = 0; r < 16; ++r) stage[(8 * (r >> 2) + 4 * g + (r & 3)) * SW + tn * 32 + c] = acc[tm][tn][r];
+#pragma unroll
+    for (int h0 = 0; h0 < NIT; h0 += HB) {
+      float4 z[HB], xv[HB], e1[HB], e2[HB];
+      unsigned off[HB];
+#pragma unroll
+      for (int i = 0; i < HB; ++i) {
+        const int rl = (h0 + i) * RPI + lrow;
+        const long long row = row0[tm] + rl;
+        const bool ok = colok && row < row_end;
+        off[i] = ok ? (unsigned)(row * a.Nf + col) : 0u;          // a state has fewer than 2^31 elements
+        z[i] = *reinterpret_cast<const float4*>(&stage[rl * SW + colq]);
+      }
+      const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+      // unconditional loads (rows / columns outside the tile read element 0 and are never stored)
+#pragma unroll
+      for (int i = 0; i < HB; ++i) xv[i] = dact ? zero : *reinterpret_cast<const float4*>(e.Xp + off[i]);
+      if (e.E1p) {
+#pragma unroll
+        for (int i = 0; i < HB; ++i) e1[i] = *reinterpret_cast<const float4*>(e.E1p + off[i]);
+      } else {
+#pragma unroll
+        for (int i = 0; i < HB; ++i) e1[i] = zero;
+      }
+      if (e.E2p) {
+#pragma unroll
+        for (int i = 0; i < HB; ++i) e2[i] = *reinterpret_cast<const float4*>(e.E2p + off[i]);
+      } else {
+#pragma unroll
+        for (int i = 0; i < HB; ++i) e2[i] = zero;
+      }
+#pragma unroll
+      for (int i = 0; i < HB; ++i) {
+        float4 o;
+        if (dact) {
+          o.x = act_prime(z[i].x + bv.x, a.act); o.y = act_prime(z[i].y + bv.y, a.act);
+          o.z = act_prime(z[i].z + bv.z, a.act); o.w = act_prime(z[i].w + bv.w, a.act);
         } else {
-          const float phi = Xp[off] + a.hs * act_fn(z, a.act);
-          o = a.sp * phi;
-          if (E1p) o += a.c1 * E1p[off];
-          if (E2p) o += a.c2 * E2p[off];
+          o.x = a.sp * (xv[i].x + a.hs * act_fn(z[i].x + bv.x, a.act)) + a.c1 * e1[i].x + a.c2 * e2[i].x;
+          o.y = a.sp * (xv[i].y + a.hs * act_fn(z[i].y + bv.y, a.act)) + a.c1 * e1[i].y + a.c2 * e2[i].y;
+          o.z = a.sp * (xv[i].z + a.hs * act_fn(z[i].z + bv.z, a.act)) + a.c1 * e1[i].z + a.c2 * e2[i].z;
+          o.w = a.sp * (xv[i].w + a.hs * act_fn(z[i].w + bv.w, a.act)) + a.c1 * e1[i].w + a.c2 * e2[i].w;
         }
-        if (Op_) Op_[off] = o;
-        sq += o * o;
+        xv[i] = o;
+      }
+#pragma unroll
+      for (int i = 0; i < HB; ++i) {
+        const int rl = (h0 + i) * RPI + lrow;
+        const long long row = row0[tm] + rl;
+        if (colok && row < row_end) {
+          if (e.Op_) *reinterpret_cast<float4*>(e.Op_ + (unsigned)(row * a.Nf + col)) = xv[i];
+          sq += (xv[i].x * xv[i].x + xv[i].y * xv[i].y) + (xv[i].z * xv[i].z + xv[i].w * xv[i].w);
+        }
       }
     }
   }
   if (a.norm_partial) {
     const float s = block_sum(sq, red);
-    if (threadIdx.x == 0) a.norm_partial[(long long)blockIdx.y * gridDim.x + L] = s;
+    if (threadIdx.x == 0) a.norm_partial[L] = s;
   }
 }
 
@@ -207,64 +284,71 @@ __device__ __forceinline__ void epilogue(const StepArgs& a, int gi, long long la
 // 4 wavefronts arranged WR x WC, each owning TM x TN blocks of 32x32.  Both operands are
 // staged through LDS in BK-wide slabs with a register prefetch of the next slab.
 // ------------------------------------------------------------------------------------------
-template <typename WT, int BM, int BN, int WR, int WC>
+template <typename WT, int BM, int BN, int WR, int WC, int BK, int PF>
 __global__ __launch_bounds__(NT) void dense_step_kernel(StepArgs a) {
-  constexpr int BK = Op<WT>::BK, ST = BK + Op<WT>::PAD, VEC = Op<WT>::VEC, KSTEP = Op<WT>::KSTEP;
+  constexpr int ST = BK + Op<WT>::PAD, VEC = Op<WT>::VEC, KSTEP = Op<WT>::KSTEP;
   constexpr int TM = BM / WR / 32, TN = BN / WC / 32;
   constexpr int AP = BM * BK / 4 / NT;      // float4 pieces of the state slab per thread
   constexpr int BP = BN * BK / VEC / NT;    // 16-byte pieces of the weight slab per thread
-  static_assert(AP >= 1 && BP >= 1 && WR * WC == 4, "tile too small for 256 threads");
-  __shared__ __attribute__((aligned(16))) WT As[BM * ST];
-  __shared__ __attribute__((aligned(16))) WT Bs[BN * ST];
+  static_assert(AP >= 1 && BP >= 1 && WR * WC == 4 && BK % KSTEP == 0, "tile does not fit 256 threads");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  WT* As = reinterpret_cast<WT*>(smem_raw);          // [BM][ST]
+  WT* Bs = As + BM * ST;                             // [BN][ST]
   __shared__ float red[4];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, c = lane & 31;
   const int tiles_n = (a.Nf + BN - 1) / BN;
   const int L = logical_block();
-  const int gi = blockIdx.y;
-  const int m0 = (L / tiles_n) * BM, n0 = (L % tiles_n) * BN;
+  const int gi = L / a.tiles, tile = L % a.tiles;
+  const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
   const long long layer = a.wm.base + gi * a.wm.stride;
   const float* Xp = a.X + (a.xm.base + gi * a.xm.stride) * a.E;
   const float* Dp = a.Dm ? a.Dm + (a.dm.base + gi * a.dm.stride) * a.E : nullptr;
   const WT* Wp = reinterpret_cast<const WT*>(a.W) + layer * a.wsize;
   const int K = a.K;
 
-  float4 areg[AP];
-  uint4 breg[BP];
-  auto load_slab = [&](int k0) {
+  // PF register sets hold the slabs in flight from global memory.  Loads are unconditional (a
+  // predicated load makes the compiler wait for it right away, which serialises the whole slab):
+  // out-of-range pieces read element 0 instead and are zeroed when the slab goes to LDS.
+  float4 areg[PF][AP], dreg[PF][AP];
+  uint4 breg[PF][BP];
+  unsigned amask[PF], bmask[PF];
+  auto load_slab = [&](float4 (&ar)[AP], float4 (&dr)[AP], uint4 (&br)[BP], unsigned& am, unsigned& bm, int k0) {
+    am = 0; bm = 0;
 #pragma unroll
     for (int i = 0; i < AP; ++i) {
       const int p = tid + NT * i, row = p / (BK / 4), kc = (p % (BK / 4)) * 4;
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (m0 + row < a.M && k0 + kc < K) {
-        const long long off = (long long)(m0 + row) * K + k0 + kc;
-        v = *reinterpret_cast<const float4*>(Xp + off);
-        if (Dp) {
-          const float4 d = *reinterpret_cast<const float4*>(Dp + off);
-          v.x *= d.x; v.y *= d.y; v.z *= d.z; v.w *= d.w;
-        }
-      }
-      areg[i] = v;
+      const bool ok = m0 + row < a.M && k0 + kc < K;
+      const unsigned off = ok ? (unsigned)((m0 + row) * K + k0 + kc) : 0u;
+      am |= ok ? (1u << i) : 0u;
+      ar[i] = *reinterpret_cast<const float4*>(Xp + off);
+      if (Dp) dr[i] = *reinterpret_cast<const float4*>(Dp + off);
     }
 #pragma unroll
     for (int i = 0; i < BP; ++i) {
       const int p = tid + NT * i, row = p / (BK / VEC), kc = (p % (BK / VEC)) * VEC;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (n0 + row < a.Nf && k0 + kc < K)
-        v = *reinterpret_cast<const uint4*>(Wp + (long long)(n0 + row) * K + k0 + kc);
-      breg[i] = v;
+      const bool ok = n0 + row < a.Nf && k0 + kc < K;
+      const unsigned off = ok ? (unsigned)((n0 + row) * K + k0 + kc) : 0u;
+      bm |= ok ? (1u << i) : 0u;
+      br[i] = *reinterpret_cast<const uint4*>(Wp + off);
     }
   };
-  auto store_slab = [&]() {
+  auto store_slab = [&](const float4 (&ar)[AP], const float4 (&dr)[AP], const uint4 (&br)[BP], unsigned am,
+                        unsigned bm) {
 #pragma unroll
     for (int i = 0; i < AP; ++i) {
       const int p = tid + NT * i, row = p / (BK / 4), kc = (p % (BK / 4)) * 4;
-      cvt_store4(&As[row * ST + kc], areg[i]);
+      float4 v = ar[i];
+      if (Dp) { v.x *= dr[i].x; v.y *= dr[i].y; v.z *= dr[i].z; v.w *= dr[i].w; }
+      if (!((am >> i) & 1u)) v = make_float4(0.f, 0.f, 0.f, 0.f);
+      cvt_store4(&As[row * ST + kc], v);
     }
 #pragma unroll
     for (int i = 0; i < BP; ++i) {
       const int p = tid + NT * i, row = p / (BK / VEC), kc = (p % (BK / VEC)) * VEC;
-      *reinterpret_cast<uint4*>(&Bs[row * ST + kc]) = breg[i];
+      uint4 v = br[i];
+      if (!((bm >> i) & 1u)) v = make_uint4(0, 0, 0, 0);
+      *reinterpret_cast<uint4*>(&Bs[row * ST + kc]) = v;
     }
   };
 
@@ -272,36 +356,59 @@ __global__ __launch_bounds__(NT) void dense_step_kernel(StepArgs a) {
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+    for (int j = 0; j < TN; ++j) acc[i][j] = zero16();
 
   const int wm0 = (wave / WC) * (BM / WR), wn0 = (wave % WC) * (BN / WC);
-  load_slab(0);
-  for (int k0 = 0; k0 < K; k0 += BK) {
-    __syncthreads();
-    store_slab();
-    __syncthreads();
-    if (k0 + BK < K) load_slab(k0 + BK);
+  // The k slabs are visited in a rotated order that depends on the group: with a power-of-two
+  // row pitch every workgroup would otherwise ask the same HBM channels for the same k at the
+  // same time.  Workgroups of one group keep a common order, so they still meet in L2.
+#ifdef MGRIT_TIMING
+  const long long t_start = __builtin_readcyclecounter();
+#endif
+  const int nk = (K + BK - 1) / BK;
+  const int rot = (int)(((long long)gi * 5) % nk);
+  auto slab_k0 = [&](int j) { int sl = rot + j; if (sl >= nk) sl -= nk; return sl * BK; };
 #pragma unroll
-    for (int ks = 0; ks < BK; ks += KSTEP) {
-      const WT* ap[TM];
-      const WT* bp[TN];
+  for (int sidx = 0; sidx < PF; ++sidx)
+    if (sidx < nk) load_slab(areg[sidx], dreg[sidx], breg[sidx], amask[sidx], bmask[sidx], slab_k0(sidx));
+  for (int it0 = 0; it0 < nk; it0 += PF) {
 #pragma unroll
-      for (int i = 0; i < TM; ++i) ap[i] = &As[(wm0 + i * 32 + c) * ST + ks];
+    for (int sidx = 0; sidx < PF; ++sidx) {
+      const int it = it0 + sidx;
+      if (it < nk) {
+        __syncthreads();
+        store_slab(areg[sidx], dreg[sidx], breg[sidx], amask[sidx], bmask[sidx]);
+        __syncthreads();
+        if (it + PF < nk) load_slab(areg[sidx], dreg[sidx], breg[sidx], amask[sidx], bmask[sidx], slab_k0(it + PF));
 #pragma unroll
-      for (int j = 0; j < TN; ++j) bp[j] = &Bs[(wn0 + j * 32 + c) * ST + ks];
-      mma_step<TM, TN>(ap, bp, acc, g);
+        for (int ks = 0; ks < BK; ks += KSTEP) {
+          const WT* ap[TM];
+          const WT* bp[TN];
+#pragma unroll
+          for (int i = 0; i < TM; ++i) ap[i] = &As[(wm0 + i * 32 + c) * ST + ks];
+#pragma unroll
+          for (int j = 0; j < TN; ++j) bp[j] = &Bs[(wn0 + j * 32 + c) * ST + ks];
+          mma_step<TM, TN>(ap, bp, acc, g);
+        }
+      }
     }
   }
 
   long long row0[TM];
-  int col0[TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i) row0[i] = m0 + wm0 + i * 32;
-#pragma unroll
-  for (int j = 0; j < TN; ++j) col0[j] = n0 + wn0 + j * 32;
-  epilogue<TM, TN>(a, gi, layer, acc, row0, (long long)a.M, col0, L, red);
+#ifdef MGRIT_TIMING
+  const long long t_loop = __builtin_readcyclecounter();
+#endif
+  static_assert((size_t)(BM + BN) * ST * sizeof(WT) >= (size_t)4 * 32 * (TN * 32 + 4) * 4, "LDS too small to stage the epilogue");
+  epilogue<TM, TN>(a, gi, layer, acc, row0, (long long)a.M, n0 + wn0, L, red, reinterpret_cast<float*>(smem_raw));
+#ifdef MGRIT_TIMING
+  // diagnostic build only: overwrite the norm partial with phase times in cycles
+  __syncthreads();
+  const long long t_end = __builtin_readcyclecounter();
+  if (a.norm_partial && threadIdx.x == 0)
+    a.norm_partial[L] = (L & 1) ? (float)(t_end - t_loop) : (float)(t_loop - t_start);
+#endif
 }
 
 // ------------------------------------------------------------------------------------------
@@ -329,31 +436,44 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
   WT* wts = patch + (TH + 2) * PW * CS;
 
   const int L = logical_block();
-  const int gi = blockIdx.y;
+  const int gi = L / a.tiles, tile = L % a.tiles;
   const int tiles_per_img = (H + TH - 1) / TH;
-  const int bimg = L / tiles_per_img, y0 = (L % tiles_per_img) * TH;
+  const int bimg = tile / tiles_per_img, y0 = (tile % tiles_per_img) * TH;
   const long long layer = a.wm.base + gi * a.wm.stride;
   const float* Xp = a.X + (a.xm.base + gi * a.xm.stride) * a.E;
   const float* Dp = a.Dm ? a.Dm + (a.dm.base + gi * a.dm.stride) * a.E : nullptr;
   const WT* Wp = reinterpret_cast<const WT*>(a.W) + layer * a.wsize;
 
-  // ---- input patch -> LDS (converted to the operand type)
+  // ---- input patch -> LDS (converted to the operand type), eight pieces per thread in flight;
+  // loads are unconditional (halo / padding pieces read element 0 and are zeroed afterwards)
   {
     const int cq = Cp / 4;
     const int total = (TH + 2) * PW * cq;
-    for (int p = tid; p < total; p += NT) {
-      const int pp = p / cq, c4 = (p % cq) * 4;
-      const int gy = y0 - 1 + pp / PW, gx = pp % PW - 1;
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (gy >= 0 && gy < H && gx >= 0 && gx < Wd && c4 < C) {
-        const long long off = (((long long)bimg * H + gy) * Wd + gx) * C + c4;
-        v = *reinterpret_cast<const float4*>(Xp + off);
-        if (Dp) {
-          const float4 d = *reinterpret_cast<const float4*>(Dp + off);
-          v.x *= d.x; v.y *= d.y; v.z *= d.z; v.w *= d.w;
+    constexpr int PU = 8;
+    for (int p0 = tid; p0 < total; p0 += NT * PU) {
+      float4 v[PU], d[PU];
+      unsigned okm = 0;
+#pragma unroll
+      for (int u = 0; u < PU; ++u) {
+        const int p = p0 + u * NT;
+        const int pp = p / cq, c4 = (p % cq) * 4;
+        const int gy = y0 - 1 + pp / PW, gx = pp % PW - 1;
+        const bool ok = p < total && gy >= 0 && gy < H && gx >= 0 && gx < Wd && c4 < C;
+        const unsigned off = ok ? (unsigned)(((bimg * H + gy) * Wd + gx) * C + c4) : 0u;
+        okm |= ok ? (1u << u) : 0u;
+        v[u] = *reinterpret_cast<const float4*>(Xp + off);
+        if (Dp) d[u] = *reinterpret_cast<const float4*>(Dp + off);
+      }
+#pragma unroll
+      for (int u = 0; u < PU; ++u) {
+        const int p = p0 + u * NT;
+        if (p < total) {
+          float4 w = v[u];
+          if (Dp) { w.x *= d[u].x; w.y *= d[u].y; w.z *= d[u].z; w.w *= d[u].w; }
+          if (!((okm >> u) & 1u)) w = make_float4(0.f, 0.f, 0.f, 0.f);
+          cvt_store4(&patch[(p / cq) * CS + (p % cq) * 4], w);
         }
       }
-      cvt_store4(&patch[pp * CS + c4], v);
     }
   }
 
@@ -361,16 +481,17 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
   const int wq = Cp / VEC;
   const int wtotal = 32 * TN * wq;
   uint4 wreg[WP];
+  unsigned wmask = 0;
   auto load_w = [&](int tap) {
+    wmask = 0;
 #pragma unroll
     for (int i = 0; i < WP; ++i) {
       const int p = tid + NT * i;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (p < wtotal) {
-        const int row = p / wq, kc = (p % wq) * VEC;
-        if (row < C && kc < C) v = *reinterpret_cast<const uint4*>(Wp + ((long long)row * 9 + tap) * C + kc);
-      }
-      wreg[i] = v;
+      const int row = p / wq, kc = (p % wq) * VEC;
+      const bool ok = p < wtotal && row < C && kc < C;
+      const unsigned off = ok ? (unsigned)((row * 9 + tap) * C + kc) : 0u;
+      wmask |= ok ? (1u << i) : 0u;
+      wreg[i] = *reinterpret_cast<const uint4*>(Wp + off);
     }
   };
   auto store_w = [&]() {
@@ -379,7 +500,9 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
       const int p = tid + NT * i;
       if (p < wtotal) {
         const int row = p / wq, kc = (p % wq) * VEC;
-        *reinterpret_cast<uint4*>(&wts[row * CS + kc]) = wreg[i];
+        uint4 v = wreg[i];
+        if (!((wmask >> i) & 1u)) v = make_uint4(0, 0, 0, 0);
+        *reinterpret_cast<uint4*>(&wts[row * CS + kc]) = v;
       }
     }
   };
@@ -397,9 +520,7 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+    for (int j = 0; j < TN; ++j) acc[i][j] = zero16();
 
   const bool wave_active = (wave * TM) * 32 < npx;
   load_w(0);
@@ -424,12 +545,9 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
 
   const long long img_row0 = ((long long)bimg * H + y0) * Wd;   // global pixel row of tile pixel 0
   long long row0[TM];
-  int col0[TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i) row0[i] = img_row0 + (wave * TM + i) * 32;
-#pragma unroll
-  for (int j = 0; j < TN; ++j) col0[j] = j * 32;
-  epilogue<TM, TN>(a, gi, layer, acc, row0, img_row0 + npx, col0, L, red);
+  epilogue<TM, TN>(a, gi, layer, acc, row0, img_row0 + npx, 0, L, red, reinterpret_cast<float*>(smem_raw));
 }
 
 // ------------------------------------------------------------------------------------------
@@ -451,32 +569,50 @@ static size_t conv_smem_bytes(const StepArgs& a, int dtype) {
   const int kstep = dtype == 0 ? 8 : 16, pad = dtype == 0 ? 4 : 8, es = dtype == 0 ? 4 : 2;
   const int Cp = (a.Nf + kstep - 1) / kstep * kstep, CS = Cp + pad;
   const int tn = a.Nf <= 32 ? 1 : 2;
-  return ((size_t)(a.TH + 2) * (a.Wimg + 2) + 32 * tn) * CS * es;
+  const size_t main_loop = ((size_t)(a.TH + 2) * (a.Wimg + 2) + 32 * tn) * CS * es;
+  const size_t staging = (size_t)4 * 32 * (tn * 32 + 4) * 4;       // epilogue staging buffer
+  return main_loop > staging ? main_loop : staging;
 }
 
-// dense tile choice: large tiles when they still fill the chip, else 64x64
-static bool dense_big_tile(const StepArgs& a, int groups) {
-  const long long big = (long long)((a.M + 127) / 128) * ((a.Nf + 127) / 128) * groups;
-  return big >= 512;
+// Dense tile choice: the largest tile that still gives every CU a workgroup, else the smallest.
+//   0: 64x64 (k slab 32 fp32 / 64 bf16)   1: 128x128   2: 256x256 (bf16 only)
+static int dense_tile_class(const StepArgs& a, int dtype, int groups) {
+  auto wgs = [&](int t) { return (long long)((a.M + t - 1) / t) * ((a.Nf + t - 1) / t) * groups; };
+  if (dtype != 0 && wgs(256) >= 256) return 2;
+  if (wgs(128) >= 256) return 1;
+  return 0;
 }
+static int dense_tile_edge(int cls) { return cls == 2 ? 256 : cls == 1 ? 128 : 64; }
 
 int step_grid_blocks(const StepArgs& a, int layer_kind, int dtype, int groups) {
-  (void)dtype;
   if (layer_kind == 1) {
     const int B = a.M / (a.Himg * a.Wimg);
     return B * ((a.Himg + a.TH - 1) / a.TH);
   }
-  if (dense_big_tile(a, groups)) return ((a.M + 127) / 128) * ((a.Nf + 127) / 128);
-  return ((a.M + 63) / 64) * ((a.Nf + 63) / 64);
+  const int t = dense_tile_edge(dense_tile_class(a, dtype, groups));
+  return ((a.M + t - 1) / t) * ((a.Nf + t - 1) / t);
 }
 
-hipError_t launch_step(const StepArgs& a, int layer_kind, int dtype, int groups, hipStream_t s) {
+template <typename WT, int BM, int BN, int BK, int PF>
+static void launch_dense(dim3 grid, hipStream_t s, const StepArgs& a) {
+  constexpr size_t smem = (size_t)(BM + BN) * (BK + Op<WT>::PAD) * sizeof(WT);
+  static bool raised = false;              // opt in once to more than 64 KB of dynamic LDS
+  if (smem > 64 * 1024 && !raised) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(dense_step_kernel<WT, BM, BN, 2, 2, BK, PF>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    raised = true;
+  }
+  hipLaunchKernelGGL((dense_step_kernel<WT, BM, BN, 2, 2, BK, PF>), grid, dim3(NT), smem, s, a);
+}
+
+hipError_t launch_step(const StepArgs& a_in, int layer_kind, int dtype, int groups, hipStream_t s) {
   if (groups <= 0) return hipSuccess;
+  StepArgs a = a_in;
+  a.tiles = step_grid_blocks(a, layer_kind, dtype, groups);
+  const dim3 grid((unsigned)a.tiles * (unsigned)groups);
   trace_before(s);
   int cls;
   if (layer_kind == 1) {
-    const int B = a.M / (a.Himg * a.Wimg);
-    dim3 grid(B * ((a.Himg + a.TH - 1) / a.TH), groups);
     const size_t smem = conv_smem_bytes(a, dtype);
     cls = dtype == 0 ? TRACE_CONV_F32 : TRACE_CONV_BF16;
     if (a.Nf <= 32) {
@@ -486,16 +622,20 @@ hipError_t launch_step(const StepArgs& a, int layer_kind, int dtype, int groups,
       if (dtype == 0) hipLaunchKernelGGL((conv_step_kernel<float, 2>), grid, dim3(NT), smem, s, a);
       else            hipLaunchKernelGGL((conv_step_kernel<__bf16, 2>), grid, dim3(NT), smem, s, a);
     }
-  } else if (dense_big_tile(a, groups)) {
-    dim3 grid(((a.M + 127) / 128) * ((a.Nf + 127) / 128), groups);
-    cls = dtype == 0 ? TRACE_DENSE_F32_128 : TRACE_DENSE_BF16_128;
-    if (dtype == 0) hipLaunchKernelGGL((dense_step_kernel<float, 128, 128, 2, 2>), grid, dim3(NT), 0, s, a);
-    else            hipLaunchKernelGGL((dense_step_kernel<__bf16, 128, 128, 2, 2>), grid, dim3(NT), 0, s, a);
   } else {
-    dim3 grid(((a.M + 63) / 64) * ((a.Nf + 63) / 64), groups);
-    cls = dtype == 0 ? TRACE_DENSE_F32_64 : TRACE_DENSE_BF16_64;
-    if (dtype == 0) hipLaunchKernelGGL((dense_step_kernel<float, 64, 64, 2, 2>), grid, dim3(NT), 0, s, a);
-    else            hipLaunchKernelGGL((dense_step_kernel<__bf16, 64, 64, 2, 2>), grid, dim3(NT), 0, s, a);
+    const int tc = dense_tile_class(a, dtype, groups);
+    if (tc == 2) {
+      cls = TRACE_DENSE_BF16_256;
+      launch_dense<__bf16, 256, 256, 64, 1>(grid, s, a);
+    } else if (tc == 1) {
+      cls = dtype == 0 ? TRACE_DENSE_F32_128 : TRACE_DENSE_BF16_128;
+      if (dtype == 0) launch_dense<float, 128, 128, 32, 2>(grid, s, a);
+      else            launch_dense<__bf16, 128, 128, 64, 1>(grid, s, a);
+    } else {
+      cls = dtype == 0 ? TRACE_DENSE_F32_64 : TRACE_DENSE_BF16_64;
+      if (dtype == 0) launch_dense<float, 64, 64, 64, 2>(grid, s, a);
+      else            launch_dense<__bf16, 64, 64, 128, 2>(grid, s, a);
+    }
   }
   const hipError_t e = hipGetLastError();
   trace_after(s, cls, groups);
@@ -651,7 +791,7 @@ hipError_t launch_transpose_weights(const void* W, void* Wt, int layer_kind, int
 // ------------------------------------------------------------------------------------------
 template <typename OT>
 __global__ __launch_bounds__(NT) void dense_grad_kernel(GradArgs a) {
-  constexpr int BK = Op<OT>::BK, ST = BK + Op<OT>::PAD, KSTEP = Op<OT>::KSTEP;
+  constexpr int BK = 2 * Op<OT>::KSTEP, ST = BK + Op<OT>::PAD, KSTEP = Op<OT>::KSTEP;
   constexpr int BM = 64, BN = 64;
   __shared__ __attribute__((aligned(16))) OT As[BM * ST];
   __shared__ __attribute__((aligned(16))) OT Bs[BN * ST];
@@ -659,8 +799,8 @@ __global__ __launch_bounds__(NT) void dense_grad_kernel(GradArgs a) {
   const int q = a.Nf;
   const int tiles_n = (q + BN - 1) / BN;
   const int L = logical_block();
-  const int gi = blockIdx.y;
-  const int m0 = (L / tiles_n) * BM, n0 = (L % tiles_n) * BN;
+  const int gi = L / a.tiles, tile = L % a.tiles;
+  const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
   const float* Up = a.U + (a.um.base + gi * a.um.stride) * a.E;
   const float* Lp = a.Lam + (a.lm.base + gi * a.lm.stride) * a.E;
   const float* Dp = a.Dm + (a.dm.base + gi * a.dm.stride) * a.E;
@@ -711,12 +851,14 @@ __global__ __launch_bounds__(NT) void bias_grad_kernel(GradArgs a) {
   a.db[(long long)gi * a.Nf + o] = a.hs * s;
 }
 
-hipError_t launch_grad(const GradArgs& a, int layer_kind, int dtype, int groups, hipStream_t s) {
+hipError_t launch_grad(const GradArgs& a_in, int layer_kind, int dtype, int groups, hipStream_t s) {
   if (groups <= 0) return hipSuccess;
   if (layer_kind != 0) return hipErrorNotSupported;
+  GradArgs a = a_in;
+  a.tiles = ((a.Nf + 63) / 64) * ((a.Nf + 63) / 64);
   trace_before(s);
   if (a.dW) {
-    dim3 grid(((a.Nf + 63) / 64) * ((a.Nf + 63) / 64), groups);
+    dim3 grid((unsigned)a.tiles * (unsigned)groups);
     if (dtype == 0) hipLaunchKernelGGL((dense_grad_kernel<float>), grid, dim3(NT), 0, s, a);
     else            hipLaunchKernelGGL((dense_grad_kernel<__bf16>), grid, dim3(NT), 0, s, a);
   }

@@ -56,7 +56,31 @@ DENSE_CASES = [
     I.reduced(I.cfg5(2), name="dense_bf16_q136_B50_N64_m4", q=136, B=50, N=64, m=4, head_classes=0),
     I.reduced(I.cfg5(2), name="dense_bf16_q256_B130_N256_m16", q=256, B=130, N=256, head_classes=0),
     I.reduced(I.cfg2(1), name="dense_fp32_serial_L1", q=40, B=9, N=13, max_levels=1),
+    # enough groups for the largest tiles (256x256 bf16, 128x128 fp32), ragged against them
+    I.reduced(I.cfg5(1), name="dense_bf16_q264_B260_N128_m2_bigtile", q=264, B=260, N=128, m=2, max_levels=2,
+              head_classes=0),
+    I.reduced(I.cfg2(1), name="dense_fp32_q136_B130_N128_m2_bigtile", q=136, B=130, N=128, m=2, max_levels=2),
 ]
+
+# widths the temporally fused chain kernels take (q a multiple of 128, at most 512); each case
+# also runs with the chain path switched off, i.e. through the lockstep kernels
+CHAIN_CASES = [
+    I.reduced(I.cfg2(3), name="chain_fp32_q128_B37_N64_L3_FCF", q=128, B=37, N=64),
+    I.reduced(I.cfg2(2), name="chain_fp32_q256_B70_N32_L2_F", q=256, B=70, N=32, max_levels=2, relax=I.RELAX_F,
+              bias_var=0.1, act=I.TANH),
+    I.reduced(I.cfg2(2), name="chain_fp32_q384_B33_N16_m2_L3", q=384, B=33, N=16, m=2, bias_var=0.1),
+    I.reduced(I.cfg5(2), name="chain_bf16_q512_B40_N64_m4", q=512, B=40, N=64, m=4, head_classes=0),
+    I.reduced(I.cfg5(2), name="chain_bf16_q128_B32_N32_m8_F", q=128, B=32, N=32, m=8, head_classes=0,
+              relax=I.RELAX_F, max_levels=2),
+    I.reduced(I.cfg2(1), name="chain_fp32_q512_serial_L1", q=512, B=20, N=9, max_levels=1),
+]
+
+
+@pytest.mark.parametrize("wl", CHAIN_CASES, ids=lambda w: w.name)
+def test_dense_forward_chain_widths(wl):
+    # The fused chain kernels are switched off in the library (their first GPU run faulted and the cause
+    # is not known yet), so these widths currently run through the lockstep kernels.
+    _check_forward(wl)
 
 
 @pytest.mark.parametrize("wl", DENSE_CASES, ids=lambda w: w.name)
@@ -81,11 +105,12 @@ def test_conv_forward(wl):
 
 # ------------------------------------------------------------------ options of the boundary
 def test_init_modes_and_user_guess():
-    wl = I.reduced(I.cfg2(2), name="dense_fp32_init", q=24, B=5, N=16, max_levels=2)
-    _check_forward(wl, init=0)
-    rng = np.random.default_rng(3)
-    Uinit = rng.standard_normal((wl.N + 1,) + wl.state_shape).astype(np.float32)
-    _check_forward(wl, init=2, U_init=Uinit)
+    for q in (24, 128):
+        wl = I.reduced(I.cfg2(2), name=f"dense_fp32_init_q{q}", q=q, B=5, N=16, max_levels=2)
+        _check_forward(wl, init=0)
+        rng = np.random.default_rng(3)
+        Uinit = rng.standard_normal((wl.N + 1,) + wl.state_shape).astype(np.float32)
+        _check_forward(wl, init=2, U_init=Uinit)
 
 
 def test_tolerance_stop_and_rms_norm():
@@ -138,14 +163,15 @@ def test_residual_norm_entry_point():
 
 
 def test_repeated_runs_are_bitwise_identical():
-    wl = I.reduced(I.cfg2(3), name="dense_fp32_determinism", q=72, B=37, N=64)
-    _announce(wl.name)
-    data = I.generate(wl)
-    gp = GpuProblem(wl, data)
-    _, U1, h1, _ = gp.forward()
-    _, U2, h2, _ = gp.forward()
-    same = bool(np.array_equal(U1, U2))
-    assert same and h1 == h2
+    for q in (72, 128):
+        wl = I.reduced(I.cfg2(3), name=f"dense_fp32_determinism_q{q}", q=q, B=37, N=64)
+        _announce(wl.name)
+        data = I.generate(wl)
+        gp = GpuProblem(wl, data)
+        _, U1, h1, _ = gp.forward()
+        _, U2, h2, _ = gp.forward()
+        same = bool(np.array_equal(U1, U2))
+        assert same and h1 == h2
 
 
 # ------------------------------------------------------------------ adjoint solve and parameter gradient
@@ -154,6 +180,12 @@ ADJ_CASES = [
     I.reduced(I.cfg5(2), name="adj_dense_bf16_q136_B50_N64_m4", q=136, B=50, N=64, m=4),
     I.reduced(I.cfg5(2), name="adj_dense_fp32_relu_F_L2", q=40, B=12, N=32, m=4, dtype=I.FP32, act=I.RELU,
               max_levels=2, relax=I.RELAX_F),
+    # chain-kernel widths
+    I.reduced(I.cfg5(3), name="adj_chain_fp32_q128_B37_N64_m4", q=128, B=37, N=64, m=4, dtype=I.FP32),
+    I.reduced(I.cfg5(2), name="adj_chain_bf16_q256_B50_N64_m4", q=256, B=50, N=64, m=4),
+    I.reduced(I.cfg5(2), name="adj_chain_fp32_q256_relu_F_L2", q=256, B=12, N=32, m=4, dtype=I.FP32, act=I.RELU,
+              max_levels=2, relax=I.RELAX_F),
+    I.reduced(I.cfg5(1), name="adj_fp32_q512_B8_N16_m4", q=512, B=8, N=16, m=4, dtype=I.FP32),
 ]
 
 
