@@ -122,7 +122,7 @@ hipError_t launch_chain(const ChainArgs& a, int dtype, hipStream_t s);
 // launch tracing (diagnostic): kernel classes, and begin / collect
 enum { TRACE_DENSE_F32_64 = 0, TRACE_DENSE_F32_128, TRACE_DENSE_BF16_64, TRACE_DENSE_BF16_128,
        TRACE_CONV_F32, TRACE_CONV_BF16, TRACE_GRAD, TRACE_CHAIN_F32, TRACE_CHAIN_BF16, TRACE_DENSE_BF16_256,
-       TRACE_NCLASS };
+       TRACE_DENSE_F32_KS, TRACE_DENSE_BF16_KS, TRACE_NCLASS };
 void trace_begin();
 int  trace_end(double* ms, long long* launches, long long* units, int ncls);
 void trace_before(hipStream_t s);

@@ -3,6 +3,8 @@
 // bandwidth-bound transfer kernels, the norm reduction and the parameter-gradient kernel.
 #include "mgrit_internal.h"
 
+#include <stdlib.h>
+
 #include <vector>
 
 namespace mgrit {
@@ -80,6 +82,14 @@ template <> struct Op<__bf16> {
   static constexpr int PAD = 8;
 };
 
+// 16-byte load of data that is used once per launch (layer weights): non-temporal, so that it does
+// not push the states, which the next launch reads again, out of the caches.
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+template <typename T>
+__device__ __forceinline__ uint4 ld_stream(const T* p) {
+  const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
 __device__ __forceinline__ void cvt_store4(float* dst, float4 v) { *reinterpret_cast<float4*>(dst) = v; }
 __device__ __forceinline__ void cvt_store4(__bf16* dst, float4 v) {
   bf16x4 o;
@@ -330,7 +340,7 @@ __global__ __launch_bounds__(NT) void dense_step_kernel(StepArgs a) {
       const bool ok = n0 + row < a.Nf && k0 + kc < K;
       const unsigned off = ok ? (unsigned)((n0 + row) * K + k0 + kc) : 0u;
       bm |= ok ? (1u << i) : 0u;
-      br[i] = *reinterpret_cast<const uint4*>(Wp + off);
+      br[i] = ld_stream(Wp + off);
     }
   };
   auto store_slab = [&](const float4 (&ar)[AP], const float4 (&dr)[AP], const uint4 (&br)[BP], unsigned am,
@@ -409,6 +419,142 @@ __global__ __launch_bounds__(NT) void dense_step_kernel(StepArgs a) {
   if (a.norm_partial && threadIdx.x == 0)
     a.norm_partial[L] = (L & 1) ? (float)(t_end - t_loop) : (float)(t_loop - t_start);
 #endif
+}
+
+// ------------------------------------------------------------------------------------------
+// Dense step for SMALL launches (coarse levels, narrow layers), built for latency instead of
+// reuse: a workgroup owns a 32-row x 32-column output tile and its four wavefronts split the
+// contraction (chunks of KC values of k, round robin).  Operand fragments go straight from
+// global memory into the MFMA source registers -- no LDS staging, no barrier in the k loop --
+// and the operands of the fused epilogue are requested before the k loop starts.  The four
+// partial tiles are summed through LDS in a fixed order.
+// ------------------------------------------------------------------------------------------
+template <typename WT> struct KsOp;
+template <> struct KsOp<float>  { static constexpr int KC = 64;  };   // 8 x (4 k per lane group) x 2 groups
+template <> struct KsOp<__bf16> { static constexpr int KC = 128; };   // 8 x (8 k per lane group) x 2 groups
+
+__device__ __forceinline__ void ks_mma(const float4 (&af)[8], const float4 (&)[8], const uint4 (&wf)[8], floatx16& acc,
+                                       float) {
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const float4 b = *reinterpret_cast<const float4*>(&wf[j]);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(af[j].x, b.x, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(af[j].y, b.y, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(af[j].z, b.z, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(af[j].w, b.w, acc, 0, 0, 0);
+  }
+}
+__device__ __forceinline__ void ks_mma(const float4 (&af)[8], const float4 (&ag)[8], const uint4 (&wf)[8], floatx16& acc,
+                                       __bf16) {
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    bf16x8 av;
+    av[0] = static_cast<__bf16>(af[j].x); av[1] = static_cast<__bf16>(af[j].y);
+    av[2] = static_cast<__bf16>(af[j].z); av[3] = static_cast<__bf16>(af[j].w);
+    av[4] = static_cast<__bf16>(ag[j].x); av[5] = static_cast<__bf16>(ag[j].y);
+    av[6] = static_cast<__bf16>(ag[j].z); av[7] = static_cast<__bf16>(ag[j].w);
+    const bf16x8 b = *reinterpret_cast<const bf16x8*>(&wf[j]);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, b, acc, 0, 0, 0);
+  }
+}
+
+template <typename WT>
+__global__ __launch_bounds__(NT) void dense_ksplit_kernel(StepArgs a) {
+  constexpr int KC = KsOp<WT>::KC;
+  constexpr bool BF = sizeof(WT) == 2;
+  constexpr int KL = BF ? 8 : 4;                    // consecutive k a lane feeds per piece
+  __shared__ __attribute__((aligned(16))) float part[4][32][36];
+  __shared__ float red[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, c = lane & 31;
+  const int tiles_n = (a.Nf + 31) / 32;
+  const int L = logical_block();
+  const int gi = L / a.tiles, tile = L % a.tiles;
+  const int m0 = (tile / tiles_n) * 32, n0 = (tile % tiles_n) * 32;
+  const long long layer = a.wm.base + gi * a.wm.stride;
+  const float* Xp = a.X + (a.xm.base + gi * a.xm.stride) * a.E;
+  const float* Dp = a.Dm ? a.Dm + (a.dm.base + gi * a.dm.stride) * a.E : nullptr;
+  const WT* Wp = reinterpret_cast<const WT*>(a.W) + layer * a.wsize;
+  const int K = a.K;
+  const EpiPtrs e = epi_ptrs(a, gi, layer);
+
+  // ---- epilogue operands first (one float4 per thread: row tid/8, columns 4*(tid%8)..+3)
+  const int erow = m0 + (tid >> 3), ecol = n0 + 4 * (tid & 7);
+  const bool eok = erow < a.M && ecol < a.Nf;
+  const unsigned eoff = eok ? (unsigned)(erow * a.Nf + ecol) : 0u;
+  const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+  const bool dact = a.mode == MODE_DACT;
+  float4 xv = zero, e1 = zero, e2 = zero, bv = zero;
+  if (!dact) xv = *reinterpret_cast<const float4*>(e.Xp + eoff);
+  if (e.E1p) e1 = *reinterpret_cast<const float4*>(e.E1p + eoff);
+  if (e.E2p) e2 = *reinterpret_cast<const float4*>(e.E2p + eoff);
+  if (e.bp && ecol < a.Nf) bv = *reinterpret_cast<const float4*>(e.bp + ecol);
+
+  // ---- k loop: this wavefront takes chunks wave, wave+4, ...; lane (c, g) feeds row m0+c of the
+  // state and row n0+c of the weights, pieces of KL consecutive k at k0 + 2*KL*j + KL*g
+  floatx16 acc = zero16();
+  const bool arow_ok = m0 + c < a.M, wrow_ok = n0 + c < a.Nf;
+  const unsigned abase = arow_ok ? (unsigned)((m0 + c) * K) : 0u;
+  const unsigned wbase = wrow_ok ? (unsigned)((n0 + c) * K) : 0u;
+  for (int k0 = wave * KC; k0 < K; k0 += 4 * KC) {
+    float4 af[8], ag[8], df[8], dg[8];
+    uint4 wf[8];
+    unsigned kmask = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int k = k0 + 2 * KL * j + KL * g;
+      const bool kok = k < K;                        // K % 8 == 0: a piece is in or out as a whole
+      kmask |= kok ? (1u << j) : 0u;
+      const unsigned ao = kok ? abase + k : 0u, wo = kok ? wbase + k : 0u;
+      af[j] = *reinterpret_cast<const float4*>(Xp + ao);
+      if (BF) ag[j] = *reinterpret_cast<const float4*>(Xp + ao + 4);
+      if (Dp) {
+        df[j] = *reinterpret_cast<const float4*>(Dp + ao);
+        if (BF) dg[j] = *reinterpret_cast<const float4*>(Dp + ao + 4);
+      }
+      wf[j] = ld_stream(Wp + wo);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      if (Dp) {
+        af[j].x *= df[j].x; af[j].y *= df[j].y; af[j].z *= df[j].z; af[j].w *= df[j].w;
+        if (BF) { ag[j].x *= dg[j].x; ag[j].y *= dg[j].y; ag[j].z *= dg[j].z; ag[j].w *= dg[j].w; }
+      }
+      if (!((kmask >> j) & 1u) || !arow_ok) { af[j] = zero; ag[j] = zero; }
+      if (!((kmask >> j) & 1u) || !wrow_ok) wf[j] = make_uint4(0, 0, 0, 0);
+    }
+    ks_mma(af, ag, wf, acc, WT());
+  }
+
+  // ---- sum the four partial tiles (fixed order) and apply the fused epilogue
+#pragma unroll
+  for (int r = 0; r < 16; ++r) part[wave][8 * (r >> 2) + 4 * g + (r & 3)][c] = acc[r];
+  __syncthreads();
+  const int pr = tid >> 3, pc = 4 * (tid & 7);
+  float4 z = *reinterpret_cast<const float4*>(&part[0][pr][pc]);
+#pragma unroll
+  for (int w = 1; w < 4; ++w) {
+    const float4 t = *reinterpret_cast<const float4*>(&part[w][pr][pc]);
+    z.x += t.x; z.y += t.y; z.z += t.z; z.w += t.w;
+  }
+  float4 o;
+  if (dact) {
+    o.x = act_prime(z.x + bv.x, a.act); o.y = act_prime(z.y + bv.y, a.act);
+    o.z = act_prime(z.z + bv.z, a.act); o.w = act_prime(z.w + bv.w, a.act);
+  } else {
+    o.x = a.sp * (xv.x + a.hs * act_fn(z.x + bv.x, a.act)) + a.c1 * e1.x + a.c2 * e2.x;
+    o.y = a.sp * (xv.y + a.hs * act_fn(z.y + bv.y, a.act)) + a.c1 * e1.y + a.c2 * e2.y;
+    o.z = a.sp * (xv.z + a.hs * act_fn(z.z + bv.z, a.act)) + a.c1 * e1.z + a.c2 * e2.z;
+    o.w = a.sp * (xv.w + a.hs * act_fn(z.w + bv.w, a.act)) + a.c1 * e1.w + a.c2 * e2.w;
+  }
+  float sq = 0.0f;
+  if (eok) {
+    if (e.Op_) *reinterpret_cast<float4*>(e.Op_ + eoff) = o;
+    sq = (o.x * o.x + o.y * o.y) + (o.z * o.z + o.w * o.w);
+  }
+  if (a.norm_partial) {
+    const float s = block_sum(sq, red);
+    if (threadIdx.x == 0) a.norm_partial[L] = s;
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -576,13 +722,16 @@ static size_t conv_smem_bytes(const StepArgs& a, int dtype) {
 
 // Dense tile choice: the largest tile that still gives every CU a workgroup, else the smallest.
 //   0: 64x64 (k slab 32 fp32 / 64 bf16)   1: 128x128   2: 256x256 (bf16 only)
+//  -1: 32x32 with the contraction split over the four wavefronts (latency-bound small launches)
 static int dense_tile_class(const StepArgs& a, int dtype, int groups) {
   auto wgs = [&](int t) { return (long long)((a.M + t - 1) / t) * ((a.Nf + t - 1) / t) * groups; };
   if (dtype != 0 && wgs(256) >= 256) return 2;
   if (wgs(128) >= 256) return 1;
+  static const long long ks_limit = getenv("MGRIT_KSPLIT_WGS") ? atoll(getenv("MGRIT_KSPLIT_WGS")) : 256;
+  if (wgs(64) < ks_limit) return -1;
   return 0;
 }
-static int dense_tile_edge(int cls) { return cls == 2 ? 256 : cls == 1 ? 128 : 64; }
+static int dense_tile_edge(int cls) { return cls == 2 ? 256 : cls == 1 ? 128 : cls == 0 ? 64 : 32; }
 
 int step_grid_blocks(const StepArgs& a, int layer_kind, int dtype, int groups) {
   if (layer_kind == 1) {
@@ -624,7 +773,11 @@ hipError_t launch_step(const StepArgs& a_in, int layer_kind, int dtype, int grou
     }
   } else {
     const int tc = dense_tile_class(a, dtype, groups);
-    if (tc == 2) {
+    if (tc == -1) {
+      cls = dtype == 0 ? TRACE_DENSE_F32_KS : TRACE_DENSE_BF16_KS;
+      if (dtype == 0) hipLaunchKernelGGL((dense_ksplit_kernel<float>), grid, dim3(NT), 0, s, a);
+      else            hipLaunchKernelGGL((dense_ksplit_kernel<__bf16>), grid, dim3(NT), 0, s, a);
+    } else if (tc == 2) {
       cls = TRACE_DENSE_BF16_256;
       launch_dense<__bf16, 256, 256, 64, 1>(grid, s, a);
     } else if (tc == 1) {
@@ -786,13 +939,16 @@ hipError_t launch_transpose_weights(const void* W, void* Wt, int layer_kind, int
 
 // ------------------------------------------------------------------------------------------
 // Parameter gradient (dense): dW[n] = hs * G^T U[n], G = Dm[n] .* Lam[n+1]; contraction over
-// the batch.  Output tile 64x64 per workgroup, operands transposed into LDS (k = batch row
-// fastest) so the same MFMA step applies.
+// the batch.  128x128 output tile per workgroup (2x2 wavefronts of 64x64).  Both operands are
+// stored batch-row-major in memory, i.e. with the contraction index slowest, so each thread
+// loads a 4 (rows) x 4 (columns) block with row-contiguous float4 loads, transposes it in
+// registers and writes 4 consecutive k per column to LDS, where the usual k-fastest fragments
+// are read.
 // ------------------------------------------------------------------------------------------
 template <typename OT>
 __global__ __launch_bounds__(NT) void dense_grad_kernel(GradArgs a) {
-  constexpr int BK = 2 * Op<OT>::KSTEP, ST = BK + Op<OT>::PAD, KSTEP = Op<OT>::KSTEP;
-  constexpr int BM = 64, BN = 64;
+  constexpr int BKR = 32, ST = BKR + Op<OT>::PAD, KSTEP = Op<OT>::KSTEP;
+  constexpr int BM = 128, BN = 128, TM = 2, TN = 2;
   __shared__ __attribute__((aligned(16))) OT As[BM * ST];
   __shared__ __attribute__((aligned(16))) OT Bs[BN * ST];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, c = lane & 31;
@@ -806,63 +962,115 @@ __global__ __launch_bounds__(NT) void dense_grad_kernel(GradArgs a) {
   const float* Dp = a.Dm + (a.dm.base + gi * a.dm.stride) * a.E;
   float* dWp = a.dW + (long long)gi * a.wsize;
 
-  floatx16 acc[1][1];
+  const int rb = tid & 7, cb = tid >> 3;             // 4 batch rows x 4 columns per thread
+  const bool aok = m0 + 4 * cb < q, bok = n0 + 4 * cb < q;      // q % 4 == 0: a float4 is in or out as a whole
+  float4 dv[4], lv[4], uv[4];
+  unsigned rmask = 0;
+  auto load_slab = [&](int r0) {
+    rmask = 0;
 #pragma unroll
-  for (int r = 0; r < 16; ++r) acc[0][0][r] = 0.0f;
-  // each thread moves BK*64/256 elements of each operand per slab: column = tid % 64
-  const int col = tid & 63, rsub = tid >> 6;
-  const int wm0 = (wave >> 1) * 32, wn0 = (wave & 1) * 32;
-  for (int k0 = 0; k0 < a.M; k0 += BK) {
+    for (int rr = 0; rr < 4; ++rr) {
+      const int row = r0 + 4 * rb + rr;
+      const bool rok = row < a.M;
+      rmask |= rok ? (1u << rr) : 0u;
+      const unsigned offa = (rok && aok) ? (unsigned)(row * q + m0 + 4 * cb) : 0u;
+      const unsigned offb = (rok && bok) ? (unsigned)(row * q + n0 + 4 * cb) : 0u;
+      dv[rr] = *reinterpret_cast<const float4*>(Dp + offa);
+      lv[rr] = *reinterpret_cast<const float4*>(Lp + offa);
+      uv[rr] = *reinterpret_cast<const float4*>(Up + offb);
+    }
+  };
+  auto store_slab = [&]() {
+    float gk[4][4], uk[4][4];                         // [column][k]
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+      const bool rok = (rmask >> rr) & 1u;
+      const float ga = (rok && aok) ? 1.0f : 0.0f, ub = (rok && bok) ? 1.0f : 0.0f;
+      gk[0][rr] = ga * dv[rr].x * lv[rr].x; gk[1][rr] = ga * dv[rr].y * lv[rr].y;
+      gk[2][rr] = ga * dv[rr].z * lv[rr].z; gk[3][rr] = ga * dv[rr].w * lv[rr].w;
+      uk[0][rr] = ub * uv[rr].x; uk[1][rr] = ub * uv[rr].y; uk[2][rr] = ub * uv[rr].z; uk[3][rr] = ub * uv[rr].w;
+    }
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc) {
+      cvt_store4(&As[(4 * cb + cc) * ST + 4 * rb], make_float4(gk[cc][0], gk[cc][1], gk[cc][2], gk[cc][3]));
+      cvt_store4(&Bs[(4 * cb + cc) * ST + 4 * rb], make_float4(uk[cc][0], uk[cc][1], uk[cc][2], uk[cc][3]));
+    }
+  };
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) acc[i][j] = zero16();
+  const int wm0 = (wave >> 1) * 64, wn0 = (wave & 1) * 64;
+  load_slab(0);
+  for (int r0 = 0; r0 < a.M; r0 += BKR) {
     __syncthreads();
+    store_slab();
+    __syncthreads();
+    if (r0 + BKR < a.M) load_slab(r0 + BKR);
 #pragma unroll
-    for (int r = rsub; r < BK; r += 4) {
-      float gv = 0.0f, uv = 0.0f;
-      const int row = k0 + r;
-      if (row < a.M) {
-        if (m0 + col < q) { const long long off = (long long)row * q + m0 + col; gv = Dp[off] * Lp[off]; }
-        if (n0 + col < q) uv = Up[(long long)row * q + n0 + col];
+    for (int ks = 0; ks < BKR; ks += KSTEP) {
+      const OT* ap[TM];
+      const OT* bp[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) ap[i] = &As[(wm0 + i * 32 + c) * ST + ks];
+#pragma unroll
+      for (int j = 0; j < TN; ++j) bp[j] = &Bs[(wn0 + j * 32 + c) * ST + ks];
+      mma_step<TM, TN>(ap, bp, acc, g);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int cc = n0 + wn0 + j * 32 + c;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = m0 + wm0 + i * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+        if (row < q && cc < q) dWp[(long long)row * q + cc] = a.hs * acc[i][j][r];
       }
-      As[col * ST + r] = static_cast<OT>(gv);
-      Bs[col * ST + r] = static_cast<OT>(uv);
     }
-    __syncthreads();
-#pragma unroll
-    for (int ks = 0; ks < BK; ks += KSTEP) {
-      const OT* ap[1] = {&As[(wm0 + c) * ST + ks]};
-      const OT* bp[1] = {&Bs[(wn0 + c) * ST + ks]};
-      mma_step<1, 1>(ap, bp, acc, g);
-    }
-  }
-#pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    const int row = m0 + wm0 + 8 * (r >> 2) + 4 * g + (r & 3), cc = n0 + wn0 + c;
-    if (row < q && cc < q) dWp[(long long)row * q + cc] = a.hs * acc[0][0][r];
-  }
 }
-// db[n][o] = hs * sum over rows of Dm .* Lam (fixed order); for conv, rows = batch * pixels
+// db[n][o] = hs * sum over rows of Dm .* Lam (fixed order).  64 columns per workgroup: 16 lanes of
+// float4 across, 16 row lanes down, then a fixed-order LDS reduction over the row lanes.
 __global__ __launch_bounds__(NT) void bias_grad_kernel(GradArgs a) {
+  __shared__ float4 part[16][17];
   const int gi = blockIdx.y;
   const float* Lp = a.Lam + (a.lm.base + gi * a.lm.stride) * a.E;
   const float* Dp = a.Dm + (a.dm.base + gi * a.dm.stride) * a.E;
-  const int o = blockIdx.x * NT + threadIdx.x;
-  if (o >= a.Nf) return;
-  float s = 0.0f;
-  for (int r = 0; r < a.M; ++r) { const long long off = (long long)r * a.Nf + o; s += Dp[off] * Lp[off]; }
-  a.db[(long long)gi * a.Nf + o] = a.hs * s;
+  const int cx = threadIdx.x & 15, ry = threadIdx.x >> 4;
+  const int col = blockIdx.x * 64 + 4 * cx;
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (col < a.Nf) {
+    for (int r = ry; r < a.M; r += 16) {
+      const unsigned off = (unsigned)(r * a.Nf + col);
+      const float4 d = *reinterpret_cast<const float4*>(Dp + off), l = *reinterpret_cast<const float4*>(Lp + off);
+      s.x += d.x * l.x; s.y += d.y * l.y; s.z += d.z * l.z; s.w += d.w * l.w;
+    }
+  }
+  part[ry][cx] = s;
+  __syncthreads();
+  if (ry == 0 && col < a.Nf) {
+    float4 t = part[0][cx];
+    for (int j = 1; j < 16; ++j) { t.x += part[j][cx].x; t.y += part[j][cx].y; t.z += part[j][cx].z; t.w += part[j][cx].w; }
+    t.x *= a.hs; t.y *= a.hs; t.z *= a.hs; t.w *= a.hs;
+    *reinterpret_cast<float4*>(a.db + (long long)gi * a.Nf + col) = t;
+  }
 }
 
 hipError_t launch_grad(const GradArgs& a_in, int layer_kind, int dtype, int groups, hipStream_t s) {
   if (groups <= 0) return hipSuccess;
   if (layer_kind != 0) return hipErrorNotSupported;
   GradArgs a = a_in;
-  a.tiles = ((a.Nf + 63) / 64) * ((a.Nf + 63) / 64);
+  a.tiles = ((a.Nf + 127) / 128) * ((a.Nf + 127) / 128);
   trace_before(s);
   if (a.dW) {
     dim3 grid((unsigned)a.tiles * (unsigned)groups);
     if (dtype == 0) hipLaunchKernelGGL((dense_grad_kernel<float>), grid, dim3(NT), 0, s, a);
     else            hipLaunchKernelGGL((dense_grad_kernel<__bf16>), grid, dim3(NT), 0, s, a);
   }
-  if (a.db) hipLaunchKernelGGL(bias_grad_kernel, dim3((a.Nf + NT - 1) / NT, groups), dim3(NT), 0, s, a);
+  if (a.db) hipLaunchKernelGGL(bias_grad_kernel, dim3((a.Nf + 63) / 64, groups), dim3(NT), 0, s, a);
   const hipError_t e = hipGetLastError();
   trace_after(s, TRACE_GRAD, groups);
   return e;
