@@ -20,6 +20,15 @@ sys.path.insert(0, ROOT)
 
 PEAK = {"fp32_mfma": 157.3, "bf16_mfma": 2500.0}       # TFLOP/s, published dense peaks of MI355X
 
+# Measured HBM bytes per launch of the dominant kernel (rocprofv3 --pmc FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0,
+# mean over the dispatches of the same bench command; summaries and the calibration of the two factors
+# are in profiles/<workload>_bench_hbm_traffic.md).  None where no counter run was made.
+TRAFFIC_BYTES = {
+    ("cfg2", "dense_ksplit_kernel<float>"): 5.16e6 + 0.97e6,
+    ("cfg2", "dense_step_kernel<float,64,64>"): 31.60e6 + 8.39e6,
+    ("cfg4", "conv_step_kernel<bf16>"): 529.72e6 + 241.59e6,
+}
+
 
 def layer_steps_per_solve(sizes, m, relax, iters):
     """Layer-step evaluations (one u + h F(u) for the whole batch at one point of one level) that
@@ -42,6 +51,10 @@ def layer_steps_per_solve(sizes, m, relax, iters):
         return n
 
     return sum(cyc(0, k == 0) for k in range(iters))
+
+
+def cyc_factor(adjoint):
+    return 3.0 if adjoint else 1.0
 
 
 def main():
@@ -140,7 +153,8 @@ def main():
     avg_us = ms_tot * 1e3 / launches
     achieved = units * flops_per_unit / (ms_tot * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 3), "peak": peak,
-                "unit": "TFLOP/s", "frac": round(achieved / peak, 5), "traffic": None,
+                "unit": "TFLOP/s", "frac": round(achieved / peak, 5),
+                "traffic": TRAFFIC_BYTES.get((args.workload, dom)),
                 "launches": launches, "avg_launch_us": round(avg_us, 3),
                 "flops_per_launch": units * flops_per_unit / launches,
                 "algorithmic_bytes_per_launch": units * bytes_per_unit / launches,
@@ -197,18 +211,28 @@ def main():
             cores = max([d.get("num_threads", 1) for d in threadpool_info()] or [1])
         except Exception:
             cores = os.cpu_count() or 1
-        small = wl.N * (2.0 * wl.E * (wl.q if wl.layer == I.DENSE else 9 * wl.C)) < 3e10
-        cyc = args.cycles if small else 1
+        # bounded sample: the same workload cut to its first Ns layers (same widths, batch, hierarchy
+        # rules and relaxation), with Ns chosen so that the oracle needs roughly 10-30 s
+        flop_step = 2.0 * wl.E * (wl.q if wl.layer == I.DENSE else 9 * wl.C)
+        budget_steps = max(64.0, 1.2e12 / flop_step if wl.layer == I.DENSE else 1.5e11 / flop_step)
+        per_layer = 3.2 * cyc_factor(adjoint)
+        Ns, unit = wl.N, wl.m ** (len(sizes) - 1)
+        while Ns > unit and Ns * per_layer * args.cycles > budget_steps:
+            Ns //= 2
+        Ns = max(unit, (Ns // unit) * unit)
+        sizes_s = O.level_sizes(Ns, wl.m, wl.max_levels, wl.min_coarse)
+        Ws, bs = data["W"][:Ns], data["b"][:Ns]
+        cyc = args.cycles
         a = time.perf_counter()
-        Uo, _, _ = O.fas_forward(data["W"], data["b"], data["u0"], wl.h, wl.m, wl.max_levels, wl.min_coarse,
+        Uo, _, _ = O.fas_forward(Ws, bs, data["u0"], wl.h, wl.m, wl.max_levels, wl.min_coarse,
                                  wl.relax, cyc, wl.layer, wl.act)
-        n_cpu = layer_steps_per_solve(sizes, wl.m, wl.relax, cyc) + (cyc - 1) * (wl.m - 1) * sizes[1]
-        sample = "forward solve of %d cycle(s)" % cyc
-        if adjoint and small:
+        n_cpu = layer_steps_per_solve(sizes_s, wl.m, wl.relax, cyc)   # counted as for the GPU
+        sample = "first %d of %d layers, forward solve of %d cycle(s)" % (Ns, wl.N, cyc)
+        if adjoint:
             lam_np = lamN.cpu().numpy()
-            O.fas_adjoint(data["W"], data["b"], Uo, lam_np, wl.h, wl.m, wl.max_levels, wl.min_coarse, wl.relax,
+            O.fas_adjoint(Ws, bs, Uo, lam_np, wl.h, wl.m, wl.max_levels, wl.min_coarse, wl.relax,
                           cyc, wl.layer, wl.act)
-            n_cpu = 2 * n_cpu + 2 * wl.N
+            n_cpu = 2 * n_cpu + 2 * Ns                        # + act' per layer + gradient per layer
             sample += " + adjoint solve + gradient"
         dt = time.perf_counter() - a
         out["cpu_baseline"] = {"value": round(n_cpu / dt, 1), "unit": "layer-steps/s", "cores": int(cores),
