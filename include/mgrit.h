@@ -122,7 +122,8 @@ int32_t mgrit_fas_forward(const mgrit_problem_t* p, const void* W, const float* 
  * db[n] = h sum G^n from the final Lam.
  *   U     device [(N+1)][state], read only      lamN  device [state], read only
  *   Lam   device [(N+1)][state]; out (in for init = MGRIT_INIT_USER)
- *   dW    device float, same shape as W, overwritten, or NULL;  db like b, or NULL
+ *   dW    device float, same shape as W (dense [N][q][q], conv [N][C][3][3][C]), overwritten, or NULL;
+ *         db like b, or NULL
  *   workspace_bytes >= mgrit_adjoint_workspace_bytes(p)
  * resnorm_hist / iters_done as above (residual of the adjoint system). */
 int32_t mgrit_fas_adjoint(const mgrit_problem_t* p, const void* W, const float* b, const float* U,

@@ -418,7 +418,6 @@ int32_t mgrit_fas_adjoint(const mgrit_problem_t* p, const void* W, const float* 
   Solver sv;
   int rc = make_plan(p, &sv.pl);
   if (rc != MGRIT_OK) return rc;
-  if (p->layer != MGRIT_LAYER_DENSE && (dW || db)) return MGRIT_ERR_UNSUPPORTED;
   if (workspace_bytes < sv.pl.bytes_adj) return MGRIT_ERR_WORKSPACE;
   const Plan& pl = sv.pl;
   sv.p = p; sv.s = static_cast<hipStream_t>(hip_stream); sv.adjoint = true;

@@ -626,32 +626,36 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
   // ---- weight slice of one tap: rows = output channel, k = input channel
   const int wq = Cp / VEC;
   const int wtotal = 32 * TN * wq;
-  uint4 wreg[WP];
-  unsigned wmask = 0;
-  auto load_w = [&](int tap) {
-    wmask = 0;
+  // two register sets and two LDS buffers: while tap t is multiplied out of one buffer, tap t+1
+  // goes from registers into the other and taps t+2, t+3 are in flight from global memory
+  uint4 wreg[2][WP];
+  unsigned wmask[2] = {0u, 0u};
+  auto load_w = [&](uint4 (&wr)[WP], unsigned& wm, int tap) {
+    wm = 0;
 #pragma unroll
     for (int i = 0; i < WP; ++i) {
       const int p = tid + NT * i;
       const int row = p / wq, kc = (p % wq) * VEC;
       const bool ok = p < wtotal && row < C && kc < C;
       const unsigned off = ok ? (unsigned)((row * 9 + tap) * C + kc) : 0u;
-      wmask |= ok ? (1u << i) : 0u;
-      wreg[i] = *reinterpret_cast<const uint4*>(Wp + off);
+      wm |= ok ? (1u << i) : 0u;
+      wr[i] = *reinterpret_cast<const uint4*>(Wp + off);
     }
   };
-  auto store_w = [&]() {
+  auto store_w = [&](const uint4 (&wr)[WP], unsigned wm, WT* dst) {
 #pragma unroll
     for (int i = 0; i < WP; ++i) {
       const int p = tid + NT * i;
       if (p < wtotal) {
         const int row = p / wq, kc = (p % wq) * VEC;
-        uint4 v = wreg[i];
-        if (!((wmask >> i) & 1u)) v = make_uint4(0, 0, 0, 0);
-        *reinterpret_cast<uint4*>(&wts[row * CS + kc]) = v;
+        uint4 v = wr[i];
+        if (!((wm >> i) & 1u)) v = make_uint4(0, 0, 0, 0);
+        *reinterpret_cast<uint4*>(&dst[row * CS + kc]) = v;
       }
     }
   };
+  load_w(wreg[0], wmask[0], 0);
+  load_w(wreg[1], wmask[1], 1);
 
   const int npx = min(TH, H - y0) * Wd;      // valid pixels of this tile
   int aoff[TM];
@@ -669,22 +673,32 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
     for (int j = 0; j < TN; ++j) acc[i][j] = zero16();
 
   const bool wave_active = (wave * TM) * 32 < npx;
-  load_w(0);
-  for (int tap = 0; tap < 9; ++tap) {
-    __syncthreads();
-    store_w();
-    __syncthreads();
-    if (tap + 1 < 9) load_w(tap + 1);
-    if (wave_active) {
-      const int toff = ((tap / 3) * PW + (tap % 3)) * CS;
-      for (int ks = 0; ks < Cp; ks += KSTEP) {
-        const WT* ap[TM];
-        const WT* bp[TN];
+  WT* wbuf[2] = {wts, wts + 32 * TN * CS};
+  store_w(wreg[0], wmask[0], wbuf[0]);
+  load_w(wreg[0], wmask[0], 2);
+  __syncthreads();                            // patch and tap 0 are in LDS
+  for (int tap0 = 0; tap0 < 9; tap0 += 2) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) ap[i] = patch + aoff[i] + toff + ks;
+    for (int sidx = 0; sidx < 2; ++sidx) {
+      const int tap = tap0 + sidx;
+      if (tap < 9) {
+        // buffer sidx holds tap; register set 1-sidx holds tap+1, set sidx has tap+2 in flight
+        if (tap + 1 < 9) store_w(wreg[1 - sidx], wmask[1 - sidx], wbuf[1 - sidx]);
+        if (tap + 3 < 9) load_w(wreg[1 - sidx], wmask[1 - sidx], tap + 3);
+        if (wave_active) {
+          const int toff = ((tap / 3) * PW + (tap % 3)) * CS;
+          const WT* wt = wbuf[sidx];
+          for (int ks = 0; ks < Cp; ks += KSTEP) {
+            const WT* ap[TM];
+            const WT* bp[TN];
 #pragma unroll
-        for (int j = 0; j < TN; ++j) bp[j] = wts + (j * 32 + c) * CS + ks;
-        mma_step<TM, TN>(ap, bp, acc, g);
+            for (int i = 0; i < TM; ++i) ap[i] = patch + aoff[i] + toff + ks;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) bp[j] = wt + (j * 32 + c) * CS + ks;
+            mma_step<TM, TN>(ap, bp, acc, g);
+          }
+        }
+        __syncthreads();                      // tap+1 visible; everyone is done with this buffer
       }
     }
   }
@@ -706,7 +720,7 @@ int conv_tile_rows(int Himg, int Wimg, int C, int dtype) {
   const int kstep = dtype == 0 ? 8 : 16, pad = dtype == 0 ? 4 : 8, es = dtype == 0 ? 4 : 2;
   const int Cp = (C + kstep - 1) / kstep * kstep, CS = Cp + pad;
   const int tn = C <= 32 ? 1 : 2;
-  while (thmax > 1 && ((size_t)(thmax + 2) * (Wimg + 2) + 32 * tn) * CS * es > 60 * 1024) --thmax;
+  while (thmax > 1 && ((size_t)(thmax + 2) * (Wimg + 2) + 2 * 32 * tn) * CS * es > 72 * 1024) --thmax;
   const int ntiles = (Himg + thmax - 1) / thmax;
   return (Himg + ntiles - 1) / ntiles;        // balanced tile height
 }
@@ -715,7 +729,7 @@ static size_t conv_smem_bytes(const StepArgs& a, int dtype) {
   const int kstep = dtype == 0 ? 8 : 16, pad = dtype == 0 ? 4 : 8, es = dtype == 0 ? 4 : 2;
   const int Cp = (a.Nf + kstep - 1) / kstep * kstep, CS = Cp + pad;
   const int tn = a.Nf <= 32 ? 1 : 2;
-  const size_t main_loop = ((size_t)(a.TH + 2) * (a.Wimg + 2) + 32 * tn) * CS * es;
+  const size_t main_loop = ((size_t)(a.TH + 2) * (a.Wimg + 2) + 2 * 32 * tn) * CS * es;   // patch + 2 tap buffers
   const size_t staging = (size_t)4 * 32 * (tn * 32 + 4) * 4;       // epilogue staging buffer
   return main_loop > staging ? main_loop : staging;
 }
@@ -754,6 +768,17 @@ static void launch_dense(dim3 grid, hipStream_t s, const StepArgs& a) {
   hipLaunchKernelGGL((dense_step_kernel<WT, BM, BN, 2, 2, BK, PF>), grid, dim3(NT), smem, s, a);
 }
 
+template <typename WT, int TN>
+static void launch_conv(dim3 grid, size_t smem, hipStream_t s, const StepArgs& a) {
+  static size_t raised = 64 * 1024;        // opt in to more than 64 KB of dynamic LDS when a shape needs it
+  if (smem > raised) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(conv_step_kernel<WT, TN>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    raised = smem;
+  }
+  hipLaunchKernelGGL((conv_step_kernel<WT, TN>), grid, dim3(NT), smem, s, a);
+}
+
 hipError_t launch_step(const StepArgs& a_in, int layer_kind, int dtype, int groups, hipStream_t s) {
   if (groups <= 0) return hipSuccess;
   StepArgs a = a_in;
@@ -765,11 +790,11 @@ hipError_t launch_step(const StepArgs& a_in, int layer_kind, int dtype, int grou
     const size_t smem = conv_smem_bytes(a, dtype);
     cls = dtype == 0 ? TRACE_CONV_F32 : TRACE_CONV_BF16;
     if (a.Nf <= 32) {
-      if (dtype == 0) hipLaunchKernelGGL((conv_step_kernel<float, 1>), grid, dim3(NT), smem, s, a);
-      else            hipLaunchKernelGGL((conv_step_kernel<__bf16, 1>), grid, dim3(NT), smem, s, a);
+      if (dtype == 0) launch_conv<float, 1>(grid, smem, s, a);
+      else            launch_conv<__bf16, 1>(grid, smem, s, a);
     } else {
-      if (dtype == 0) hipLaunchKernelGGL((conv_step_kernel<float, 2>), grid, dim3(NT), smem, s, a);
-      else            hipLaunchKernelGGL((conv_step_kernel<__bf16, 2>), grid, dim3(NT), smem, s, a);
+      if (dtype == 0) launch_conv<float, 2>(grid, smem, s, a);
+      else            launch_conv<__bf16, 2>(grid, smem, s, a);
     }
   } else {
     const int tc = dense_tile_class(a, dtype, groups);
@@ -1032,6 +1057,87 @@ __global__ __launch_bounds__(NT) void dense_grad_kernel(GradArgs a) {
       }
     }
 }
+// Parameter gradient (3x3 conv): dK[n][o][dy][dx][i] = hs * sum over pixels of G[b,y,x,o] *
+// U[b,y+dy-1,x+dx-1,i] (zero outside the image), G = Dm .* Lam.  One workgroup per (layer, tap):
+// a C x C output tile (C <= 64), contraction over all B*H*W pixels in slabs of 32, operands
+// transposed in registers as in the dense kernel.
+template <typename OT>
+__global__ __launch_bounds__(NT) void conv_grad_kernel(GradArgs a) {
+  constexpr int BKR = 32, ST = BKR + Op<OT>::PAD, KSTEP = Op<OT>::KSTEP;
+  __shared__ __attribute__((aligned(16))) OT As[64 * ST];
+  __shared__ __attribute__((aligned(16))) OT Bs[64 * ST];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, c = lane & 31;
+  const int C = a.Nf, H = a.Himg, Wd = a.Wimg;
+  const int L = logical_block();
+  const int gi = L / 9, tap = L % 9;
+  const int dy = tap / 3 - 1, dx = tap % 3 - 1;
+  const float* Up = a.U + (a.um.base + gi * a.um.stride) * a.E;
+  const float* Lp = a.Lam + (a.lm.base + gi * a.lm.stride) * a.E;
+  const float* Dp = a.Dm + (a.dm.base + gi * a.dm.stride) * a.E;
+  float* dKp = a.dW + (long long)gi * a.wsize;
+
+  const int rb = tid & 7, cb = (tid >> 3) & 15;      // 4 pixels x 4 channels per thread; threads 128.. idle
+  const bool cok = tid < 128 && 4 * cb < C;
+  float4 dv[4], lv[4], uv[4];
+  unsigned gmask = 0, umask = 0;
+  auto load_slab = [&](int r0) {
+    gmask = 0; umask = 0;
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+      const int px = r0 + 4 * rb + rr;
+      const bool pok = cok && px < a.M;
+      const int x = px % Wd, y = (px / Wd) % H;
+      const bool sok = pok && y + dy >= 0 && y + dy < H && x + dx >= 0 && x + dx < Wd;
+      gmask |= pok ? (1u << rr) : 0u;
+      umask |= sok ? (1u << rr) : 0u;
+      const unsigned og = pok ? (unsigned)(px * C + 4 * cb) : 0u;
+      const unsigned ou = sok ? (unsigned)((px + dy * Wd + dx) * C + 4 * cb) : 0u;
+      dv[rr] = *reinterpret_cast<const float4*>(Dp + og);
+      lv[rr] = *reinterpret_cast<const float4*>(Lp + og);
+      uv[rr] = *reinterpret_cast<const float4*>(Up + ou);
+    }
+  };
+  auto store_slab = [&]() {
+    if (tid >= 128) return;
+    float gk[4][4], uk[4][4];
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+      const float ga = ((gmask >> rr) & 1u) ? 1.0f : 0.0f, ub = ((umask >> rr) & 1u) ? 1.0f : 0.0f;
+      gk[0][rr] = ga * dv[rr].x * lv[rr].x; gk[1][rr] = ga * dv[rr].y * lv[rr].y;
+      gk[2][rr] = ga * dv[rr].z * lv[rr].z; gk[3][rr] = ga * dv[rr].w * lv[rr].w;
+      uk[0][rr] = ub * uv[rr].x; uk[1][rr] = ub * uv[rr].y; uk[2][rr] = ub * uv[rr].z; uk[3][rr] = ub * uv[rr].w;
+    }
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc) {
+      cvt_store4(&As[(4 * cb + cc) * ST + 4 * rb], make_float4(gk[cc][0], gk[cc][1], gk[cc][2], gk[cc][3]));
+      cvt_store4(&Bs[(4 * cb + cc) * ST + 4 * rb], make_float4(uk[cc][0], uk[cc][1], uk[cc][2], uk[cc][3]));
+    }
+  };
+
+  floatx16 acc[1][1];
+  acc[0][0] = zero16();
+  const int wm0 = (wave >> 1) * 32, wn0 = (wave & 1) * 32;
+  load_slab(0);
+  for (int r0 = 0; r0 < a.M; r0 += BKR) {
+    __syncthreads();
+    store_slab();
+    __syncthreads();
+    if (r0 + BKR < a.M) load_slab(r0 + BKR);
+#pragma unroll
+    for (int ks = 0; ks < BKR; ks += KSTEP) {
+      const OT* ap[1] = {&As[(wm0 + c) * ST + ks]};
+      const OT* bp[1] = {&Bs[(wn0 + c) * ST + ks]};
+      mma_step<1, 1>(ap, bp, acc, g);
+    }
+  }
+  const int ci = wn0 + c;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int co = wm0 + 8 * (r >> 2) + 4 * g + (r & 3);
+    if (co < C && ci < C) dKp[((long long)co * 9 + tap) * C + ci] = a.hs * acc[0][0][r];
+  }
+}
+
 // db[n][o] = hs * sum over rows of Dm .* Lam (fixed order).  64 columns per workgroup: 16 lanes of
 // float4 across, 16 row lanes down, then a fixed-order LDS reduction over the row lanes.
 __global__ __launch_bounds__(NT) void bias_grad_kernel(GradArgs a) {
@@ -1061,14 +1167,22 @@ __global__ __launch_bounds__(NT) void bias_grad_kernel(GradArgs a) {
 
 hipError_t launch_grad(const GradArgs& a_in, int layer_kind, int dtype, int groups, hipStream_t s) {
   if (groups <= 0) return hipSuccess;
-  if (layer_kind != 0) return hipErrorNotSupported;
   GradArgs a = a_in;
-  a.tiles = ((a.Nf + 127) / 128) * ((a.Nf + 127) / 128);
   trace_before(s);
-  if (a.dW) {
-    dim3 grid((unsigned)a.tiles * (unsigned)groups);
-    if (dtype == 0) hipLaunchKernelGGL((dense_grad_kernel<float>), grid, dim3(NT), 0, s, a);
-    else            hipLaunchKernelGGL((dense_grad_kernel<__bf16>), grid, dim3(NT), 0, s, a);
+  if (layer_kind == 0) {
+    a.tiles = ((a.Nf + 127) / 128) * ((a.Nf + 127) / 128);
+    if (a.dW) {
+      dim3 grid((unsigned)a.tiles * (unsigned)groups);
+      if (dtype == 0) hipLaunchKernelGGL((dense_grad_kernel<float>), grid, dim3(NT), 0, s, a);
+      else            hipLaunchKernelGGL((dense_grad_kernel<__bf16>), grid, dim3(NT), 0, s, a);
+    }
+  } else {
+    a.tiles = 9;
+    if (a.dW) {
+      dim3 grid(9u * (unsigned)groups);
+      if (dtype == 0) hipLaunchKernelGGL((conv_grad_kernel<float>), grid, dim3(NT), 0, s, a);
+      else            hipLaunchKernelGGL((conv_grad_kernel<__bf16>), grid, dim3(NT), 0, s, a);
+    }
   }
   if (a.db) hipLaunchKernelGGL(bias_grad_kernel, dim3((a.Nf + 63) / 64, groups), dim3(NT), 0, s, a);
   const hipError_t e = hipGetLastError();
