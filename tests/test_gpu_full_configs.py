@@ -146,3 +146,21 @@ def test_cfg5_full_training_step_sampled(cfg5_data):
         gW, gb = O.weight_grad(G, Un, wl.layer)
         eW, eb = _rel(dW[n], wl.h * gW), _rel(db[n], wl.h * gb)
         assert eW <= 2e-2 and eb <= 2e-2, (n, eW, eb)
+
+
+def test_cfg5_full_adjoint_elementwise(cfg5_data):
+    """Adjoint solve (1 cycle) and parameter gradient at full size, element by element, linearised about the
+    oracle's own one-cycle forward iterate."""
+    wl, data = cfg5_data
+    _say(wl.name + " adjoint + gradient, 1 cycle, element-wise")
+    Uo, _, _ = oracle_forward(wl, data)
+    U = Uo.astype(np.float32)
+    del Uo
+    lamN = I.terminal_adjoint(wl, data, U[-1])
+    gp = GpuProblem(wl, data)
+    Lam, dW, db, hist, it = gp.adjoint(U, lamN)
+    Lo, dWo, dbo, hist_o, _ = O.fas_adjoint(data["W"], data["b"], U, lamN, wl.h, wl.m, wl.max_levels, wl.min_coarse,
+                                            wl.relax, wl.max_iter, wl.layer, wl.act)
+    eL, eW, eb = rel_l2_per_state(Lam, Lo), rel_l2_per_state(dW, dWo), rel_l2_per_state(db, dbo)
+    print(f"cfg5 adjoint: Lam {eL:.3e}  dW {eW:.3e}  db {eb:.3e}  hist {hist} vs {hist_o}", flush=True)
+    assert eL <= 2e-2 and eW <= 2e-2 and eb <= 2e-2, (eL, eW, eb)

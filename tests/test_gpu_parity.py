@@ -234,3 +234,51 @@ def test_conv_adjoint_and_gradient(wl):
     tol = TOL[wl.dtype]
     eL, eW, eb = rel_l2_per_state(Lam, Lo), rel_l2_per_state(dW, dWo), rel_l2_per_state(db, dbo)
     assert eL <= tol and eW <= tol and eb <= tol, (eL, eW, eb)
+
+
+# ------------------------------------------------------------------ degenerate and edge cases
+EDGE_CASES = [
+    # a single coarse interval per level; the coarsest level has one step
+    I.reduced(I.cfg2(2), name="edge_one_interval_N4_m4", q=16, B=2, N=4, m=4, max_levels=3),
+    # batch of one, width 8 (smallest supported), m = 2, as many levels as fit
+    I.reduced(I.cfg2(2), name="edge_B1_q8_N16_m2_deep", q=8, B=1, N=16, m=2, max_levels=16, bias_var=0.1),
+    # N == 1: no coarsening possible, serial propagation of one step
+    I.reduced(I.cfg2(1), name="edge_N1", q=16, B=3, N=1, m=2, max_levels=4),
+    # one-pixel-high and one-pixel-wide images (every tap but the centre column/row is padding)
+    I.reduced(I.cfg3(2), name="edge_conv_1x9", B=2, C=8, Himg=1, Wimg=9, N=8, m=2, lifted_input=False),
+    I.reduced(I.cfg3(2), name="edge_conv_7x1", B=2, C=8, Himg=7, Wimg=1, N=8, m=2, lifted_input=False),
+    # widest supported image row
+    I.reduced(I.cfg3(1), name="edge_conv_2x256", B=1, C=8, Himg=2, Wimg=256, N=4, m=2, lifted_input=False),
+]
+
+
+@pytest.mark.parametrize("wl", EDGE_CASES, ids=lambda w: w.name)
+def test_edge_cases_forward(wl):
+    _check_forward(wl)
+
+
+def test_non_finite_input_is_reported():
+    """A NaN in the input makes the residual norm non-finite: the solve returns MGRIT_ERR_NONFINITE."""
+    from paper_2007_07336_amd import binding as Bd
+    wl = I.reduced(I.cfg2(2), name="nan_input", q=16, B=2, N=8, m=2, max_levels=2)
+    _announce(wl.name)
+    data = I.generate(wl)
+    data["u0"] = data["u0"].copy()
+    data["u0"][0, 0] = np.nan
+    gp = GpuProblem(wl, data)
+    rc, U, hist, it = gp.forward(check=False)
+    assert rc == Bd.MGRIT_ERR_NONFINITE
+    gp2 = GpuProblem(wl, data, tol=1e-3)
+    rc2, _, _, it2 = gp2.forward(check=False)
+    assert rc2 == Bd.MGRIT_ERR_NONFINITE and it2 == 1
+
+
+def test_conv_repeated_runs_are_bitwise_identical():
+    wl = I.reduced(I.cfg4(2), name="conv_bf16_determinism", B=2, Himg=12, Wimg=10, N=64)
+    _announce(wl.name)
+    data = I.generate(wl)
+    gp = GpuProblem(wl, data)
+    _, U1, h1, _ = gp.forward()
+    _, U2, h2, _ = gp.forward()
+    same = bool(np.array_equal(U1, U2))
+    assert same and h1 == h2
