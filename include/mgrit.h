@@ -57,7 +57,7 @@ enum { MGRIT_NORM_L2 = 0, MGRIT_NORM_RMS = 1 };            /* RMS = L2 / sqrt(#e
 enum { MGRIT_LAYER_DENSE = 0, MGRIT_LAYER_CONV3X3 = 1 };
 enum { MGRIT_ACT_TANH = 0, MGRIT_ACT_RELU = 1 };
 enum { MGRIT_FP32 = 0, MGRIT_BF16 = 1 };
-enum { MGRIT_INIT_ZERO = 0, MGRIT_INIT_COPY = 1, MGRIT_INIT_USER = 2 };
+enum { MGRIT_INIT_ZERO = 0, MGRIT_INIT_COPY = 1, MGRIT_INIT_USER = 2, MGRIT_INIT_NESTED = 3 };
 enum { MGRIT_MAX_LEVELS = 16 };
 
 typedef struct mgrit_problem {
@@ -80,8 +80,13 @@ typedef struct mgrit_problem {
   int32_t B, q;        /* dense: batch and width                                                 */
   int32_t C, Himg, Wimg; /* conv: channels, image height and width                               */
   int32_t init;        /* initial guess of the fine C-points: MGRIT_INIT_ZERO, MGRIT_INIT_COPY
-                          (every C-point := the known end value u^0, resp. lambda^N) or
-                          MGRIT_INIT_USER (take them from the in/out array)                      */
+                          (every C-point := the known end value u^0, resp. lambda^N),
+                          MGRIT_INIT_USER (take them from the in/out array) or MGRIT_INIT_NESTED
+                          (nested iteration: the coarsest level's equation L(V) = (u^0, 0, .., 0)
+                          with its own step size is solved in sequence; going up, the C-points of
+                          each level take the coarser level's values and its F-points follow by
+                          F-relaxation, Sec. III-A / III-C; the paper prints no start-up procedure.
+                          Costs N_coarsest + sum over the middle levels of N_l (m-1)/m layer steps) */
 } mgrit_problem_t;
 
 /* Level hierarchy (Sec. III-C: every m-th layer of a level is also a member of the next

@@ -20,6 +20,8 @@ What is computed, and where the paper defines it
 * the adjoint (backward) solve: the paper states that the same multigrid removes the
   serial backward propagation but prints no equations; here it is the exact reverse-mode
   derivative of Eq. (1), solved by the same cycle on the reversed layer axis.
+* the nested-iteration start (init = 3): the paper prints no start-up procedure; the coarsest
+  level's equation is solved first and handed up level by level                [Sec. III-A background]
 
 Index convention: N layer steps, N+1 states u^0..u^N, parameters theta^0..theta^{N-1}.
 Level l has N_l = N / c^l steps and step size h_l = c^l h; level-l point j is fine layer
@@ -29,7 +31,9 @@ interface of this project calls it m.)
 Pins (tests/test_oracle_pins.py): two-level exactness after N/c cycles, fixed point at the
 serial solution, linear-F closed forms and the dense two-grid operator, brute-force coarse
 equation check, layer steps against an independent float64 library routine, gradients
-against finite differences and automatic differentiation, level maps against enumeration.
+against finite differences and automatic differentiation, level maps against enumeration;
+the nested-iteration start against hand-written coarse forward-Euler loops, its exactness for a
+layer-independent constant F, and the unchanged fixed point.
 Parity unpinned: the value of a multilevel (3+ level) iterate at a fixed finite cycle count
 is pinned only through its limit, its fixed point and its agreement with the two-level case.
 """
@@ -253,6 +257,26 @@ def _cycle(l, sizes, U, g, m, relax, phi, hist):
     _f_relax(l, U, g, m, phi)
 
 
+def _nested_start(sizes, m, phi, first, shape):
+    """Nested-iteration start (the paper's multigrid background, Sec. III-A, solves coarse problems
+    first; the paper prints no start-up procedure for Alg. 1, so this is the plain one): every level
+    carries the equation L(V) = (first, 0, .., 0) with its own step size.  The coarsest level is
+    solved in sequence; going up, the C-points of a level take the values of the next coarser level
+    (injection the other way round) and its F-points follow by F-relaxation.  Returns the values of
+    the points of level 1, i.e. the start values of the fine C-points."""
+    L = len(sizes)
+    V = np.zeros((sizes[L - 1] + 1,) + shape)
+    V[0] = first
+    for j in range(1, sizes[L - 1] + 1):
+        V[j] = phi(L - 1, j - 1, V[j - 1])
+    for l in range(L - 2, 0, -1):
+        Ul = np.zeros((sizes[l] + 1,) + shape)
+        Ul[::m] = V
+        _f_relax(l, Ul, np.zeros_like(Ul), m, phi)
+        V = Ul
+    return V
+
+
 def _solve(sizes, m, relax, phi, first, shape, init, X_init, max_iter, tol, norm_kind):
     N = sizes[0]
     L = len(sizes)
@@ -261,6 +285,8 @@ def _solve(sizes, m, relax, phi, first, shape, init, X_init, max_iter, tol, norm
         U[::m] = first
     elif init == 2:
         U[:] = X_init
+    elif init == 3 and L > 1:
+        U[::m] = _nested_start(sizes, m, phi, first, shape)
     U[0] = first
     g = np.zeros_like(U)
     g[0] = first

@@ -16,6 +16,7 @@ MGRIT_OK = 0
 MGRIT_ERR_POINTER, MGRIT_ERR_PROBLEM, MGRIT_ERR_WORKSPACE = -1, -2, -3
 MGRIT_ERR_UNSUPPORTED, MGRIT_ERR_NONFINITE, MGRIT_ERR_HIP = -4, -5, -6
 MGRIT_MAX_LEVELS = 16
+MGRIT_INIT_ZERO, MGRIT_INIT_COPY, MGRIT_INIT_USER, MGRIT_INIT_NESTED = 0, 1, 2, 3
 ERROR_NAMES = {0: "MGRIT_OK", -1: "MGRIT_ERR_POINTER", -2: "MGRIT_ERR_PROBLEM", -3: "MGRIT_ERR_WORKSPACE",
                -4: "MGRIT_ERR_UNSUPPORTED", -5: "MGRIT_ERR_NONFINITE", -6: "MGRIT_ERR_HIP"}
 

@@ -64,7 +64,7 @@ int make_plan(const mgrit_problem_t* p, Plan* pl) {
   if (p->layer != MGRIT_LAYER_DENSE && p->layer != MGRIT_LAYER_CONV3X3) return MGRIT_ERR_PROBLEM;
   if (p->act != MGRIT_ACT_TANH && p->act != MGRIT_ACT_RELU) return MGRIT_ERR_PROBLEM;
   if (p->dtype != MGRIT_FP32 && p->dtype != MGRIT_BF16) return MGRIT_ERR_PROBLEM;
-  if (p->init < MGRIT_INIT_ZERO || p->init > MGRIT_INIT_USER) return MGRIT_ERR_PROBLEM;
+  if (p->init < MGRIT_INIT_ZERO || p->init > MGRIT_INIT_NESTED) return MGRIT_ERR_PROBLEM;
   if (p->layer == MGRIT_LAYER_DENSE) {
     if (p->B < 1 || p->q < 1) return MGRIT_ERR_PROBLEM;
     if (p->q % 8 != 0) return MGRIT_ERR_UNSUPPORTED;       // 16-byte operand pieces
@@ -97,7 +97,7 @@ int make_plan(const mgrit_problem_t* p, Plan* pl) {
   for (int l = 0; l + 1 < pl->L; ++l) {
     pl->off_R[l] = off; off = align_up(off + (size_t)(pl->Nl[l + 1] + 1) * pl->E * 4);
     pl->off_C[l] = off;                // C-relaxation results of the fused dense sweeps
-    if (p->layer == MGRIT_LAYER_DENSE) off = align_up(off + (size_t)(pl->Nl[l + 1] + 1) * pl->E * 4);
+    if (p->layer == MGRIT_LAYER_DENSE && chain_enabled()) off = align_up(off + (size_t)(pl->Nl[l + 1] + 1) * pl->E * 4);
   }
   pl->chain_fwd = p->layer == MGRIT_LAYER_DENSE && chain_supported(p->q, p->dtype, false);
   pl->chain_adj = p->layer == MGRIT_LAYER_DENSE && chain_supported(p->q, p->dtype, true);
@@ -137,6 +137,7 @@ struct Solver {
   float* R[MGRIT_MAX_LEVELS];
   float* Cb[MGRIT_MAX_LEVELS];
   bool use_chain = false;
+  bool plain_rhs = false;              // nested start: every level carries the right-hand side (first, 0, .., 0)
   const void* W;
   const float* bias;
   const float* Dm;
@@ -174,7 +175,7 @@ struct Solver {
     StepArgs a = base_args(l, js0, jstride);
     a.X = X[l]; a.xm = pm(l, js0 - 1, jstride);
     a.Out = X[l]; a.om = pm(l, js0, jstride);
-    if (g[l]) { a.E1 = g[l]; a.e1m = PtMap{js0, jstride}; a.c1 = 1.0f; }
+    if (g[l] && !plain_rhs) { a.E1 = g[l]; a.e1m = PtMap{js0, jstride}; a.c1 = 1.0f; }
     launch(a, groups);
   }
   void f_relax(int l) {                                        // Sec. III-C, Fig. 3
@@ -246,6 +247,23 @@ struct Solver {
     if (l > 0) chain_f_relax(l);                          // on the fine level the next sweep does it
   }
 
+  // Nested-iteration start: the coarsest level's own equation is solved in sequence from the known
+  // value; going up, the C-points of a level take the coarser level's values and (on the middle
+  // levels) the F-points follow by F-relaxation.  The fine level's F-points are left to the opening
+  // relaxation of the first cycle.
+  void nested_start(const float* first) {
+    const int m = p->m;
+    plain_rhs = true;
+    const int lc = pl.L - 1;
+    chk(launch_copy_points(X[lc], pm(lc, 0, 0), first, PtMap{0, 0}, pl.E, 1, s));
+    for (int j = 1; j <= pl.Nl[lc]; ++j) propagate(lc, j, 1, 1);
+    for (int l = lc - 1; l >= 0; --l) {
+      chk(launch_copy_points(X[l], pm(l, 0, m), X[l + 1], PtMap{0, 1}, pl.E, pl.Nl[l + 1] + 1, s));
+      if (l > 0) f_relax(l);
+    }
+    plain_rhs = false;
+  }
+
   void cycle(int l, int iter, bool skip_opening_relax) {
     const int m = p->m;
     if (l == pl.L - 1) {                                        // coarsest level: serial solve
@@ -306,6 +324,7 @@ int run_solver(Solver& sv, const float* first, double* resnorm_hist, int32_t* it
   if (pl.L > 1 && p->init == MGRIT_INIT_COPY)
     sv.chk(launch_copy_points(sv.X[0], sv.pm(0, m, m), first, PtMap{0, 0}, pl.E, pl.Nl[1], sv.s));
   sv.chk(launch_copy_points(sv.X[0], sv.pm(0, 0, 0), first, PtMap{0, 0}, pl.E, 1, sv.s));
+  if (pl.L > 1 && p->init == MGRIT_INIT_NESTED) sv.nested_start(first);
 
   int iters = 0;
   int rc = MGRIT_OK;

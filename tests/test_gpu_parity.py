@@ -113,6 +113,45 @@ def test_init_modes_and_user_guess():
         _check_forward(wl, init=2, U_init=Uinit)
 
 
+NESTED_CASES = [
+    I.reduced(I.cfg2(2), name="nested_dense_fp32_q72_B37_N64_L3_FCF", q=72, B=37, N=64, bias_var=0.1),
+    I.reduced(I.cfg2(1), name="nested_dense_fp32_q40_B9_N32_L2_F", q=40, B=9, N=32, max_levels=2, relax=I.RELAX_F),
+    I.reduced(I.cfg5(2), name="nested_dense_bf16_q136_B50_N64_m4", q=136, B=50, N=64, m=4),
+    I.reduced(I.cfg2(1), name="nested_dense_fp32_q16_N16_m2_deep", q=16, B=3, N=16, m=2, max_levels=16, bias_var=0.1),
+    I.reduced(I.cfg3(1), name="nested_conv_fp32_c16_10x9_B2_N16_L3", B=2, Himg=10, Wimg=9, N=16, m=2, max_levels=3),
+    I.reduced(I.cfg4(1), name="nested_conv_bf16_c64_8x8_B3_N16_m4", B=3, Himg=8, Wimg=8, N=16, m=4, max_levels=2),
+]
+
+
+@pytest.mark.parametrize("wl", NESTED_CASES, ids=lambda w: w.name)
+def test_nested_iteration_start_forward(wl):
+    """init = MGRIT_INIT_NESTED: coarsest level first, handed up level by level, then the cycles."""
+    _check_forward(wl, init=3)
+
+
+@pytest.mark.parametrize("wl", [
+    I.reduced(I.cfg5(2), name="nested_adj_dense_fp32_q72_B37_N64_m4", q=72, B=37, N=64, m=4, dtype=I.FP32),
+    I.reduced(I.cfg5(1), name="nested_adj_dense_bf16_q136_B50_N64_m4", q=136, B=50, N=64, m=4),
+    I.reduced(I.cfg3(1), name="nested_adj_conv_fp32_c16_10x9_B2_N16", B=2, Himg=10, Wimg=9, N=16, act=I.TANH),
+], ids=lambda w: w.name)
+def test_nested_iteration_start_adjoint(wl):
+    _announce(wl.name)
+    data = I.generate(wl)
+    Uo, _, _ = oracle_forward(wl, data, max_iter=2, init=3)
+    U = Uo.astype(np.float32)
+    rng = np.random.default_rng(19)
+    lamN = rng.standard_normal(wl.state_shape).astype(np.float32)
+    gp = GpuProblem(wl, data, init=3)
+    Lam, dW, db, hist, it = gp.adjoint(U, lamN)
+    Lo, dWo, dbo, hist_o, it_o = oracle_adjoint(wl, data, U, lamN, init=3)
+    tol = TOL[wl.dtype]
+    eL, eW, eb = rel_l2_per_state(Lam, Lo), rel_l2_per_state(dW, dWo), rel_l2_per_state(db, dbo)
+    assert eL <= tol and eW <= tol and eb <= tol, (eL, eW, eb)
+    assert it == it_o
+    for a, b in zip(hist, hist_o):
+        assert abs(a - b) <= 5e-2 * b + 1e-7
+
+
 def test_tolerance_stop_and_rms_norm():
     wl = I.reduced(I.cfg2(30), name="dense_fp32_tol", q=32, B=8, N=64, tol=1e-4, norm_kind=1)
     _announce(wl.name)

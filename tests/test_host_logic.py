@@ -95,13 +95,15 @@ def test_forward_argument_validation():
     assert _fwd(p) == Bd.MGRIT_ERR_WORKSPACE
     assert _fwd(p, ws_bytes=M.mgrit_workspace_bytes(p) - 1) == Bd.MGRIT_ERR_WORKSPACE
     for bad in (dict(N=0), dict(m=1), dict(max_levels=0), dict(max_levels=17), dict(relax=2), dict(cycle=1),
-                dict(max_iter=0), dict(norm_kind=2), dict(layer=2), dict(act=5), dict(dtype=3), dict(init=3),
+                dict(max_iter=0), dict(norm_kind=2), dict(layer=2), dict(act=5), dict(dtype=3), dict(init=4), dict(init=-1),
                 dict(h=0.0), dict(B=0), dict(q=0), dict(N=18, m=4), dict(N=24, m=4, max_levels=3)):
         assert _fwd(_problem(**bad)) == Bd.MGRIT_ERR_PROBLEM, bad
     for uns in (dict(q=12), dict(layer=1, C=12, Himg=4, Wimg=4), dict(layer=1, C=128, Himg=4, Wimg=4),
                 dict(layer=1, C=16, Himg=4, Wimg=300)):
         assert _fwd(_problem(**uns)) == Bd.MGRIT_ERR_UNSUPPORTED, uns
     assert _fwd(_problem(layer=1, C=0, Himg=4, Wimg=4)) == Bd.MGRIT_ERR_PROBLEM
+    for ok_init in (Bd.MGRIT_INIT_ZERO, Bd.MGRIT_INIT_COPY, Bd.MGRIT_INIT_USER, Bd.MGRIT_INIT_NESTED):
+        assert _fwd(_problem(init=ok_init)) == Bd.MGRIT_ERR_WORKSPACE     # valid problem: stops at the size check
 
 
 def test_adjoint_and_norm_argument_validation():

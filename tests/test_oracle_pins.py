@@ -474,3 +474,116 @@ def test_convergence_history_similar_across_depths():
         _, hist, it = O.fas_forward(W, b, u0, 1.0 / N, 4, 2, 1, O.RELAX_FCF, 20, DENSE, TANH, tol=1e-9)
         its.append(it)
     assert max(its) - min(its) <= 1, its
+
+
+# ---------------------------------------------------------------------------------------
+# Nested-iteration start (init = 3): coarse problems first, handed up level by level
+# ---------------------------------------------------------------------------------------
+def _euler_dense(v, Wn, bn, step_size, kind):
+    z = v @ Wn.T + bn
+    return v + step_size * (np.tanh(z) if kind == TANH else np.maximum(z, 0.0))
+
+
+@pytest.mark.parametrize("kind", [TANH, RELU])
+def test_nested_start_two_level_is_coarse_forward_euler(kind):
+    """Two levels: the start values of the C-points are forward Euler with step c*h through every
+    c-th layer's parameters (Sec. III-C, Eq. (25)), written out here without the oracle's helpers."""
+    rng = np.random.default_rng(31)
+    N, m, q = 12, 3, 5
+    W, b, u0 = _dense_problem(rng, N, q, 2, scale=1.5)
+    h = 0.4
+    U, hist, it = O.fas_forward(W, b, u0, h, m, 2, 1, O.RELAX_F, 0, DENSE, kind, init=3)
+    assert it == 0 and hist == []
+    v = u0.copy()
+    for i in range(1, N // m + 1):
+        n = (i - 1) * m
+        v = _euler_dense(v, W[n], b[n], m * h, kind)
+        assert np.abs(U[i * m] - v).max() < 1e-14
+    assert np.array_equal(U[0], u0)
+
+
+def test_nested_start_three_level_brute_force():
+    rng = np.random.default_rng(32)
+    N, m, q = 16, 2, 4
+    W, b, u0 = _dense_problem(rng, N, q, 3, scale=1.5)
+    h = 0.3
+    U, _, _ = O.fas_forward(W, b, u0, h, m, 3, 1, O.RELAX_FCF, 0, DENSE, TANH, init=3)
+    # level 2: points at fine layers 0, 4, 8, 12, 16, step 4h
+    lvl2 = [u0.copy()]
+    for j in range(1, N // 4 + 1):
+        n = (j - 1) * 4
+        lvl2.append(_euler_dense(lvl2[-1], W[n], b[n], 4 * h, TANH))
+    # level 1: points at fine layers 0, 2, .., 16, step 2h; even points from level 2, odd ones by one step
+    for j2 in range(N // 4 + 1):
+        assert np.abs(U[4 * j2] - lvl2[j2]).max() < 1e-14
+    for j2 in range(N // 4):
+        n = 4 * j2
+        f_point = _euler_dense(lvl2[j2], W[n], b[n], 2 * h, TANH)
+        assert np.abs(U[n + 2] - f_point).max() < 1e-14
+
+
+def test_nested_start_exact_for_layer_independent_constant_F():
+    """W = 0 and the same bias in every layer: F is one constant, every step size integrates it
+    exactly, so the start is already the solution and the first residual vanishes."""
+    rng = np.random.default_rng(33)
+    N, m, q = 32, 4, 3
+    W = np.zeros((N, q, q))
+    b = np.tile(rng.standard_normal((1, q)), (N, 1))
+    u0 = rng.standard_normal((2, q))
+    Us = O.serial_forward(W, b, u0, 0.1, DENSE, TANH)
+    U, hist, _ = O.fas_forward(W, b, u0, 0.1, m, 3, 1, O.RELAX_F, 1, DENSE, TANH, init=3)
+    assert hist[0] < 1e-13 and np.abs(U - Us).max() < 1e-13
+    # the copy start is not exact here (guards against the test passing vacuously)
+    _, hist_c, _ = O.fas_forward(W, b, u0, 0.1, m, 3, 1, O.RELAX_F, 1, DENSE, TANH, init=1)
+    assert hist_c[0] > 1e-3
+
+
+def test_nested_start_same_limit_and_smaller_first_residual():
+    """Parameters that vary smoothly with depth (the regime of Sec. II, Eq. (2), where a coarse step
+    approximates c fine ones): same limit as any other start, smaller residuals on the way."""
+    rng = np.random.default_rng(34)
+    N, m, q = 64, 4, 6
+    Wa, Wb = rng.standard_normal((2, q, q)) / math.sqrt(q)
+    t = np.arange(N) / N
+    W = np.cos(2 * t)[:, None, None] * Wa + np.sin(2 * t)[:, None, None] * Wb
+    b = np.outer(np.cos(t), rng.standard_normal(q)) * 0.3
+    u0 = rng.standard_normal((3, q))
+    h = 1 / N
+    Us = O.serial_forward(W, b, u0, h, DENSE, TANH)
+    U, hist, it = O.fas_forward(W, b, u0, h, m, 3, 1, O.RELAX_FCF, 30, DENSE, TANH, tol=1e-12, init=3)
+    assert it < 30 and np.abs(U - Us).max() < 1e-10
+    _, hist_c, it_c = O.fas_forward(W, b, u0, h, m, 3, 1, O.RELAX_FCF, 30, DENSE, TANH, tol=1e-12, init=1)
+    assert hist[0] < 0.6 * hist_c[0] and hist[1] < 0.6 * hist_c[1] and it <= it_c
+
+
+@pytest.mark.parametrize("layer", [DENSE, CONV])
+def test_nested_start_same_limit_random_layers(layer):
+    rng = np.random.default_rng(36)
+    N, m = 32, 2
+    if layer == DENSE:
+        W, b, u0 = _dense_problem(rng, N, 6, 3)
+    else:
+        W, b, u0 = _conv_problem(rng, N, 2, 1, 4, 4)
+    Us = O.serial_forward(W, b, u0, 1 / N, layer, TANH)
+    U, hist, it = O.fas_forward(W, b, u0, 1 / N, m, 3, 1, O.RELAX_FCF, 30, layer, TANH, tol=1e-13, init=3)
+    assert it < 30 and np.abs(U - Us).max() < 1e-11
+
+
+def test_nested_start_adjoint_two_level_brute_force():
+    """Adjoint solve: the start values of the C-points are the coarse adjoint recursion from the top,
+    each coarse step using the state and parameters of the first layer of its interval."""
+    rng = np.random.default_rng(35)
+    N, m, q = 8, 4, 4
+    W, b, u0 = _dense_problem(rng, N, q, 2, scale=1.5)
+    h = 0.25
+    Us = O.serial_forward(W, b, u0, h, DENSE, TANH)
+    lamN = rng.standard_normal(u0.shape)
+    Lam, dW, db, hist, it = O.fas_adjoint(W, b, Us, lamN, h, m, 2, 1, O.RELAX_F, 0, DENSE, TANH, init=3)
+    lam = lamN.copy()
+    assert np.array_equal(Lam[N], lamN)
+    for i in range(N // m - 1, -1, -1):
+        n = i * m
+        z = Us[n] @ W[n].T + b[n]
+        G = (1.0 - np.tanh(z) ** 2) * lam
+        lam = lam + (m * h) * (G @ W[n])
+        assert np.abs(Lam[n] - lam).max() < 1e-14
