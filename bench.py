@@ -81,7 +81,7 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     wl = I.ALL[args.workload](args.cycles)
-    adjoint = wl.layer == I.DENSE          # parameter gradient kernels exist for dense layers
+    adjoint = True
     data = I.generate(wl)
     p = M.problem_from_workload(wl)
     sizes, _ = M.mgrit_level_map(p)
@@ -196,8 +196,27 @@ def main():
         p_one = M.problem_from_workload(wl, max_iter=1)
         t_one = timed(lambda: M.mgrit_fas_forward(p_one, W, b, u0, U, ws, want_hist=False))
         t_two = timed(lambda: M.mgrit_fas_forward(p, W, b, u0, U, ws, want_hist=False))
+        # nested-iteration start against the copy start, on this workload's independent random layers
+        # and on the same shapes with parameters that vary smoothly with depth
+        nested = {}
+        wl_s = I.reduced(wl, smooth_depth=True)
+        W_s = torch.from_numpy(I.generate(wl_s)["W"]).to(dev)
+        if wl.dtype == I.BF16:
+            W_s = W_s.to(torch.bfloat16)
+        b_s = torch.from_numpy(I.generate(wl_s)["b"]).to(dev)
+        for tag, Wx, bx in (("random_layers", W, b), ("smooth_depth", W_s, b_s)):
+            for init, iname in ((1, "copy"), (3, "nested")):
+                p_i = M.problem_from_workload(wl, max_iter=40, tol=1e-6, norm_kind=1, init=init)
+                r = {}
+
+                def run():
+                    r["r"] = M.mgrit_fas_forward(p_i, Wx, bx, u0, U, ws_tol)
+                t_i = timed(run, 3)
+                nested["%s_%s" % (tag, iname)] = {"cycles": r["r"][2], "ms": round(t_i, 3),
+                                                  "first_rms_residual": r["r"][1][0]}
+        del W_s, b_s
         out["extras"] = {"time_to_rms_1e-6_ms": round(t_tol, 3), "cycles_to_rms_1e-6": res["r"][2],
-                         "final_rms_residual": res["r"][1][-1],
+                         "final_rms_residual": res["r"][1][-1], "start_comparison_to_rms_1e-6": nested,
                          "serial_forward_gpu_ms": round(t_ser, 3),
                          "forward_1_cycle_ms": round(t_one, 3), "forward_%d_cycles_ms" % args.cycles: round(t_two, 3),
                          "forward_cycle_layer_steps_per_s":
@@ -211,30 +230,38 @@ def main():
             cores = max([d.get("num_threads", 1) for d in threadpool_info()] or [1])
         except Exception:
             cores = os.cpu_count() or 1
-        # bounded sample: the same workload cut to its first Ns layers (same widths, batch, hierarchy
-        # rules and relaxation), with Ns chosen so that the oracle needs roughly 10-30 s
-        flop_step = 2.0 * wl.E * (wl.q if wl.layer == I.DENSE else 9 * wl.C)
-        budget_steps = max(64.0, 1.2e12 / flop_step if wl.layer == I.DENSE else 1.5e11 / flop_step)
-        per_layer = 3.2 * cyc_factor(adjoint)
-        Ns, unit = wl.N, wl.m ** (len(sizes) - 1)
-        while Ns > unit and Ns * per_layer * args.cycles > budget_steps:
+        # bounded sample of about 10-30 s of CPU work: the same workload (widths, hierarchy rules, relaxation,
+        # cycle count) cut to its first Ns layers and, if one pass is still too long, to its first Bs samples;
+        # if one pass is short it is repeated.  Layer steps are counted as for the GPU, scaled by Bs / B.
+        flop_step = 2.0 * wl.E * (wl.q if wl.layer == I.DENSE else 9 * wl.C)       # one layer step, whole batch
+        budget = 1.4e12 if wl.layer == I.DENSE else 3.5e11                          # flops of oracle work aimed at
+        per_layer = 3.2 * cyc_factor(adjoint) * args.cycles
+        Ns, unit, Bs = wl.N, wl.m ** (len(sizes) - 1), wl.B
+        while Ns > unit and Ns * per_layer * flop_step > budget:
             Ns //= 2
         Ns = max(unit, (Ns // unit) * unit)
+        while Bs > 1 and Ns * per_layer * flop_step * Bs / wl.B > budget:
+            Bs //= 2
+        reps = int(min(50, max(1, budget // (Ns * per_layer * flop_step * Bs / wl.B))))
         sizes_s = O.level_sizes(Ns, wl.m, wl.max_levels, wl.min_coarse)
-        Ws, bs = data["W"][:Ns], data["b"][:Ns]
+        Ws, bs, u0s = data["W"][:Ns], data["b"][:Ns], data["u0"][:Bs]
         cyc = args.cycles
-        a = time.perf_counter()
-        Uo, _, _ = O.fas_forward(Ws, bs, data["u0"], wl.h, wl.m, wl.max_levels, wl.min_coarse,
-                                 wl.relax, cyc, wl.layer, wl.act)
         n_cpu = layer_steps_per_solve(sizes_s, wl.m, wl.relax, cyc)   # counted as for the GPU
-        sample = "first %d of %d layers, forward solve of %d cycle(s)" % (Ns, wl.N, cyc)
+        sample = "first %d of %d layers, first %d of %d samples, forward solve of %d cycle(s)" % (Ns, wl.N, Bs, wl.B, cyc)
         if adjoint:
-            lam_np = lamN.cpu().numpy()
-            O.fas_adjoint(Ws, bs, Uo, lam_np, wl.h, wl.m, wl.max_levels, wl.min_coarse, wl.relax,
-                          cyc, wl.layer, wl.act)
-            n_cpu = 2 * n_cpu + 2 * Ns                        # + act' per layer + gradient per layer
+            n_cpu = 2 * n_cpu + 2 * Ns                            # + act' per layer + gradient per layer
             sample += " + adjoint solve + gradient"
+        lam_np = lamN.cpu().numpy()[:Bs] if adjoint else None
+        a = time.perf_counter()
+        for _ in range(reps):
+            Uo, _, _ = O.fas_forward(Ws, bs, u0s, wl.h, wl.m, wl.max_levels, wl.min_coarse,
+                                     wl.relax, cyc, wl.layer, wl.act)
+            if adjoint:
+                O.fas_adjoint(Ws, bs, Uo, lam_np, wl.h, wl.m, wl.max_levels, wl.min_coarse, wl.relax,
+                              cyc, wl.layer, wl.act)
         dt = time.perf_counter() - a
+        n_cpu = n_cpu * reps * (Bs / wl.B)
+        sample += ", %d pass(es)" % reps
         out["cpu_baseline"] = {"value": round(n_cpu / dt, 1), "unit": "layer-steps/s", "cores": int(cores),
                                "kind": "oracle", "sample": sample + " of %s (fp64 numpy, %.1f s)" % (wl.name, dt)}
     print(json.dumps(out))

@@ -54,6 +54,8 @@ class Workload:
     seed: int = 0
     tol: float = 0.0
     norm_kind: int = 0
+    smooth_depth: bool = False  # True: parameters vary smoothly with depth (a quarter turn between two
+                                # random draws) instead of being independent from layer to layer
 
     @property
     def h(self) -> float:
@@ -112,6 +114,12 @@ def generate(wl: Workload) -> dict:
         else:
             u0 = rng.standard_normal((wl.B, wl.Himg, wl.Wimg, wl.C))
         feat = wl.C * wl.Himg * wl.Wimg
+    if wl.smooth_depth:
+        # theta(t) = cos(pi t / 2) theta_a + sin(pi t / 2) theta_b, t = n / N: same variance at every depth
+        t = (np.arange(wl.N) / wl.N) * (np.pi / 2)
+        ex = (slice(None),) + (None,) * (W.ndim - 1)
+        W = np.cos(t)[ex] * W[0] + np.sin(t)[ex] * W[wl.N // 2]
+        b = np.cos(t)[:, None] * b[0] + np.sin(t)[:, None] * b[wl.N // 2]
     W = W.astype(np.float32)
     if wl.dtype == BF16:
         W = round_to_bf16(W)
