@@ -234,7 +234,7 @@ def main():
         # cycle count) cut to its first Ns layers and, if one pass is still too long, to its first Bs samples;
         # if one pass is short it is repeated.  Layer steps are counted as for the GPU, scaled by Bs / B.
         flop_step = 2.0 * wl.E * (wl.q if wl.layer == I.DENSE else 9 * wl.C)       # one layer step, whole batch
-        budget = 1.4e12 if wl.layer == I.DENSE else 3.5e11                          # flops of oracle work aimed at
+        budget = 1.4e12 if wl.layer == I.DENSE else 5.0e11                          # flops of oracle work aimed at
         per_layer = 3.2 * cyc_factor(adjoint) * args.cycles
         Ns, unit, Bs = wl.N, wl.m ** (len(sizes) - 1), wl.B
         while Ns > unit and Ns * per_layer * flop_step > budget:

@@ -32,7 +32,7 @@ struct Plan {
   size_t esize;                        // bytes per weight element
   size_t off_X[MGRIT_MAX_LEVELS], off_g[MGRIT_MAX_LEVELS], off_R[MGRIT_MAX_LEVELS], off_C[MGRIT_MAX_LEVELS];
   bool chain_fwd, chain_adj;           // dense layers: temporally fused chain kernels usable
-  size_t off_partial, n_partial, off_hist, off_Wt, off_D;
+  size_t off_partial, n_partial, off_hist, off_Wt, off_D, off_gpart;
   size_t bytes_fwd, bytes_adj;
 };
 
@@ -119,6 +119,9 @@ int make_plan(const mgrit_problem_t* p, Plan* pl) {
   pl->bytes_fwd = off;
   pl->off_Wt = off; off = align_up(off + (size_t)p->N * pl->wsize * pl->esize);
   pl->off_D = off; off = align_up(off + (size_t)p->N * pl->E * 4);
+  pl->off_gpart = off;                 // partial sums of the conv parameter gradient when layers are split
+  if (p->layer == MGRIT_LAYER_CONV3X3)
+    off = align_up(off + conv_grad_partial_bytes(p->B, p->Himg, p->Wimg, p->C, p->dtype, p->N));
   pl->bytes_adj = off;
   return MGRIT_OK;
 }
@@ -470,6 +473,7 @@ int32_t mgrit_fas_adjoint(const mgrit_problem_t* p, const void* W, const float* 
     ga.dW = dW; ga.db = db; ga.hs = p->h;
     ga.M = pl.M; ga.Nf = pl.Nf; ga.K = pl.K; ga.Himg = p->Himg; ga.Wimg = p->Wimg; ga.B = p->B;
     ga.E = pl.E; ga.wsize = pl.wsize;
+    ga.partial = reinterpret_cast<float*>(ws + pl.off_gpart);
     if (launch_grad(ga, p->layer, p->dtype, p->N, sv.s) != hipSuccess) return MGRIT_ERR_HIP;
     if (resnorm_hist || iters_done)
       if (hipStreamSynchronize(sv.s) != hipSuccess) return MGRIT_ERR_HIP;

@@ -59,7 +59,21 @@ struct GradArgs {
   int M, Nf, K, Himg, Wimg, B;
   int tiles;                        // workgroups per layer (filled in by the launch wrapper)
   long long E, wsize;
+  // conv, all taps in one workgroup (filled in by the launch wrapper from conv_grad_geom)
+  float* partial;                   // [chunks][layers][wsize] partial sums when a layer is split into chunks
+  int layers;
+  int gWp, gR, gKL, gPU, gPG, gspi, gslabs, gchunks, gspc;
 };
+// Geometry of the conv gradient kernel that forms all nine taps in one workgroup: a slab is gR image rows
+// of one image (row pitch gWp, a multiple of 8), the contraction over a slab runs over gKL pixel slots,
+// the layer's slabs are split into `chunks` workgroups whose partial sums a second kernel adds in a fixed order.
+struct ConvGradGeom {
+  int Wp, R, KL, PU, PG, spi, slabs, chunks, spc;
+  size_t smem;
+  bool ok;                          // false: image row too wide for this kernel (one workgroup per tap is used)
+};
+ConvGradGeom conv_grad_geom(int B, int Himg, int Wimg, int C, int dtype, int layers);
+size_t     conv_grad_partial_bytes(int B, int Himg, int Wimg, int C, int dtype, int layers);
 
 // ---- launch wrappers (defined in mgrit_kernels.hip); all enqueue on `s` and return the HIP status
 hipError_t launch_step(const StepArgs& a, int layer_kind, int dtype, int groups, hipStream_t s);

@@ -1060,9 +1060,10 @@ __global__ __launch_bounds__(NT) void dense_grad_kernel(GradArgs a) {
 // Parameter gradient (3x3 conv): dK[n][o][dy][dx][i] = hs * sum over pixels of G[b,y,x,o] *
 // U[b,y+dy-1,x+dx-1,i] (zero outside the image), G = Dm .* Lam.  One workgroup per (layer, tap):
 // a C x C output tile (C <= 64), contraction over all B*H*W pixels in slabs of 32, operands
-// transposed in registers as in the dense kernel.
+// transposed in registers as in the dense kernel.  Every tap re-reads the whole layer, so this form is
+// kept only for image rows too wide for the all-taps kernel below.
 template <typename OT>
-__global__ __launch_bounds__(NT) void conv_grad_kernel(GradArgs a) {
+__global__ __launch_bounds__(NT) void conv_grad_tap_kernel(GradArgs a) {
   constexpr int BKR = 32, ST = BKR + Op<OT>::PAD, KSTEP = Op<OT>::KSTEP;
   __shared__ __attribute__((aligned(16))) OT As[64 * ST];
   __shared__ __attribute__((aligned(16))) OT Bs[64 * ST];
@@ -1138,6 +1139,193 @@ __global__ __launch_bounds__(NT) void conv_grad_kernel(GradArgs a) {
   }
 }
 
+// Parameter gradient (3x3 conv), all nine taps in one workgroup.  Written as one product per layer,
+//   dK[o][n] = sum over pixels p of G[p][o] * S[p][n],   n = tap * C + i,   S[p][tap*C+i] = U[p + tap][i],
+// which is exactly the row-major [C][9C] layout of dK[o][dy][dx][i].  A workgroup walks over slabs of gR
+// image rows of one image.  Per slab the 4 (pixels) x 4 (channels) register transposes of the dense
+// gradient kernel put G as [o][pixel] and U as [i][patch pixel] into LDS, the latter three times, shifted
+// by dx = -1, 0, +1, so that every 16-byte fragment read of a tap is aligned; dy is a whole-row offset.
+// A lane's B-operand row is fixed by its column n (tap and input channel), so the k loop is a plain
+// GEMM loop over the slab's pixel slots.  The wavefront w owns the 32-column blocks w, w+4, w+8, ...
+// LDS is cleared once; slots that are never written (row padding, the column left of x = 0 in the
+// dx = -1 copy, ...) stay zero, rows outside the image are written as zeros every slab.
+// With few layers the slabs of a layer are split over `gchunks` workgroups that write partial sums.
+template <typename OT, int TM, int TN>
+__global__ __launch_bounds__(NT) void conv_grad_kernel(GradArgs a) {
+  constexpr int KSTEP = Op<OT>::KSTEP;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, c = lane & 31;
+  const int C = a.Nf, H = a.Himg, Wd = a.Wimg;
+  const int Wp = a.gWp, R = a.gR, PU = a.gPU, PG = a.gPG, KL = a.gKL;
+  OT* Ut = reinterpret_cast<OT*>(smem_raw);             // [3][C][PU]
+  OT* Gt = Ut + 3 * C * PU;                             // [C][PG]
+  const int L = logical_block();
+  const int gi = L / a.gchunks, ch = L % a.gchunks;
+  const float* Up = a.U + (a.um.base + gi * a.um.stride) * a.E;
+  const float* Lp = a.Lam + (a.lm.base + gi * a.lm.stride) * a.E;
+  const float* Dp = a.Dm + (a.dm.base + gi * a.dm.stride) * a.E;
+
+  {
+    const int n16 = (int)(((size_t)3 * C * PU + (size_t)C * PG) * sizeof(OT) / 16);
+    for (int p = tid; p < n16; p += NT) reinterpret_cast<uint4*>(smem_raw)[p] = make_uint4(0u, 0u, 0u, 0u);
+  }
+
+  // this thread's 4x4 blocks: one of G, up to three of the U patch (channel group fastest, then x, then row)
+  const int CG = C >> 2, XG = (Wd + 3) >> 2;
+  const int nGb = R * XG * CG, nUb = (R + 2) * XG * CG;
+  const bool gact = tid < nGb;
+  const int gb = gact ? tid : 0;
+  const int g_cg = gb % CG, g_xg = (gb / CG) % XG, g_r = gb / (CG * XG);
+  bool uact[3];
+  int u_cg[3], u_xg[3], u_r[3];
+#pragma unroll
+  for (int t = 0; t < 3; ++t) {
+    const int blk = tid + NT * t;
+    uact[t] = blk < nUb;
+    const int ub = uact[t] ? blk : 0;
+    u_cg[t] = ub % CG; u_xg[t] = (ub / CG) % XG; u_r[t] = ub / (CG * XG);
+  }
+  float4 dv[4], lv[4], uv[3][4];
+  unsigned gmask = 0, umask[3] = {0, 0, 0};
+  auto load_slab = [&](int sl) {
+    const int b = sl / a.gspi, y0 = (sl % a.gspi) * R;
+    {
+      const int y = y0 + g_r;
+      const bool rok = gact && y < H;
+      gmask = 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int x = 4 * g_xg + j;
+        const bool ok = rok && x < Wd;
+        gmask |= ok ? (1u << j) : 0u;
+        const unsigned off = ok ? (unsigned)((((long long)b * H + y) * Wd + x) * C + 4 * g_cg) : 0u;
+        dv[j] = *reinterpret_cast<const float4*>(Dp + off);
+        lv[j] = *reinterpret_cast<const float4*>(Lp + off);
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < 3; ++t) {
+      if (NT * t >= nUb) break;                        // uniform
+      const int y = y0 - 1 + u_r[t];
+      const bool rok = uact[t] && y >= 0 && y < H;
+      umask[t] = 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int x = 4 * u_xg[t] + j;
+        const bool ok = rok && x < Wd;
+        umask[t] |= ok ? (1u << j) : 0u;
+        const unsigned off = ok ? (unsigned)((((long long)b * H + y) * Wd + x) * C + 4 * u_cg[t]) : 0u;
+        uv[t][j] = *reinterpret_cast<const float4*>(Up + off);
+      }
+    }
+  };
+  auto store_slab = [&]() {
+    if (gact) {
+      float gk[4][4];                                   // [channel][pixel]
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const bool ok = (gmask >> j) & 1u;
+        gk[0][j] = ok ? dv[j].x * lv[j].x : 0.0f; gk[1][j] = ok ? dv[j].y * lv[j].y : 0.0f;
+        gk[2][j] = ok ? dv[j].z * lv[j].z : 0.0f; gk[3][j] = ok ? dv[j].w * lv[j].w : 0.0f;
+      }
+#pragma unroll
+      for (int cc = 0; cc < 4; ++cc)
+        cvt_store4(&Gt[(4 * g_cg + cc) * PG + g_r * Wp + 4 * g_xg], make_float4(gk[cc][0], gk[cc][1], gk[cc][2], gk[cc][3]));
+    }
+#pragma unroll
+    for (int t = 0; t < 3; ++t) {
+      if (NT * t >= nUb) break;                        // uniform
+      if (!uact[t]) continue;
+      float uk[4][4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const bool ok = (umask[t] >> j) & 1u;
+        uk[0][j] = ok ? uv[t][j].x : 0.0f; uk[1][j] = ok ? uv[t][j].y : 0.0f;
+        uk[2][j] = ok ? uv[t][j].z : 0.0f; uk[3][j] = ok ? uv[t][j].w : 0.0f;
+      }
+      const int col = 4 * u_xg[t];
+#pragma unroll
+      for (int cc = 0; cc < 4; ++cc) {
+        const int i = 4 * u_cg[t] + cc;
+        OT* rowm = Ut + (0 * C + i) * PU + u_r[t] * Wp;   // dx = -1: slot xx holds U[x = xx - 1]
+        OT* row0 = Ut + (1 * C + i) * PU + u_r[t] * Wp;   // dx =  0
+        OT* rowp = Ut + (2 * C + i) * PU + u_r[t] * Wp;   // dx = +1: slot xx holds U[x = xx + 1]
+        cvt_store4(row0 + col, make_float4(uk[cc][0], uk[cc][1], uk[cc][2], uk[cc][3]));
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          if (col + j + 1 < Wp) rowm[col + j + 1] = static_cast<OT>(uk[cc][j]);
+          if (col + j - 1 >= 0) rowp[col + j - 1] = static_cast<OT>(uk[cc][j]);
+        }
+      }
+    }
+  };
+
+  // this lane's operand rows: output channel o for A, column n = tap * C + i for B (clamped: the blocks
+  // past the end compute values that are never stored)
+  const OT* arow[TM];
+  const OT* brow[TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) arow[i] = Gt + min(32 * i + c, C - 1) * PG;
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int n = min(32 * (wave + 4 * j) + c, 9 * C - 1);
+    const int tap = n / C, ii = n % C;
+    brow[j] = Ut + ((tap % 3) * C + ii) * PU + (tap / 3) * Wp;
+  }
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) acc[i][j] = zero16();
+
+  const int s_begin = ch * a.gspc, s_end = min(s_begin + a.gspc, a.gslabs);
+  if (s_begin < s_end) load_slab(s_begin);
+  for (int sl = s_begin; sl < s_end; ++sl) {
+    __syncthreads();
+    store_slab();
+    __syncthreads();
+    if (sl + 1 < s_end) load_slab(sl + 1);
+    for (int ks = 0; ks < KL; ks += KSTEP) {
+      const OT* ap[TM];
+      const OT* bp[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) ap[i] = arow[i] + ks;
+#pragma unroll
+      for (int j = 0; j < TN; ++j) bp[j] = brow[j] + ks;
+      mma_step<TM, TN>(ap, bp, acc, g);
+    }
+  }
+  const bool direct = a.gchunks == 1;
+  float* dst = direct ? a.dW + (long long)gi * a.wsize : a.partial + ((long long)ch * a.layers + gi) * a.wsize;
+  const float scale = direct ? a.hs : 1.0f;
+  const int NC = 9 * C;
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int n = 32 * (wave + 4 * j) + c;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int o = 32 * i + 8 * (r >> 2) + 4 * g + (r & 3);
+        if (o < C && n < NC) dst[(long long)o * NC + n] = scale * acc[i][j][r];
+      }
+    }
+}
+// dK = hs * (sum of the chunk partial sums, in chunk order)
+__global__ __launch_bounds__(NT) void conv_grad_reduce_kernel(const float* partial, float* dW, long long total4,
+                                                              int chunks, float hs) {
+  const float4* src = reinterpret_cast<const float4*>(partial);
+  float4* dst = reinterpret_cast<float4*>(dW);
+  for (long long i = (long long)blockIdx.x * NT + threadIdx.x; i < total4; i += (long long)gridDim.x * NT) {
+    float4 s = src[i];
+    for (int k = 1; k < chunks; ++k) {
+      const float4 v = src[(long long)k * total4 + i];
+      s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    }
+    dst[i] = make_float4(hs * s.x, hs * s.y, hs * s.z, hs * s.w);
+  }
+}
+
 // db[n][o] = hs * sum over rows of Dm .* Lam (fixed order).  64 columns per workgroup: 16 lanes of
 // float4 across, 16 row lanes down, then a fixed-order LDS reduction over the row lanes.
 __global__ __launch_bounds__(NT) void bias_grad_kernel(GradArgs a) {
@@ -1165,6 +1353,46 @@ __global__ __launch_bounds__(NT) void bias_grad_kernel(GradArgs a) {
   }
 }
 
+ConvGradGeom conv_grad_geom(int B, int Himg, int Wimg, int C, int dtype, int layers) {
+  ConvGradGeom gm = {};
+  const int es = dtype == 0 ? 4 : 2, pad = dtype == 0 ? Op<float>::PAD : Op<__bf16>::PAD;
+  const int kstep = dtype == 0 ? Op<float>::KSTEP : Op<__bf16>::KSTEP;
+  gm.Wp = (Wimg + 7) & ~7;
+  gm.R = 64 / gm.Wp;
+  if (gm.R < 1) gm.R = 1;
+  if (gm.R > Himg) gm.R = Himg;
+  const int KP = gm.R * gm.Wp;
+  gm.KL = (KP + kstep - 1) / kstep * kstep;
+  gm.PU = (gm.R + 2) * gm.Wp + pad;                     // reads reach slot 2*Wp + KL - 1 <= (R+2)*Wp + pad - 1
+  gm.PG = gm.KL + pad;
+  gm.spi = (Himg + gm.R - 1) / gm.R;
+  gm.slabs = B * gm.spi;
+  gm.smem = ((size_t)3 * C * gm.PU + (size_t)C * gm.PG) * es;
+  gm.ok = Wimg <= 64 && gm.smem <= (size_t)150 * 1024;
+  int ch = (512 + layers - 1) / (layers > 0 ? layers : 1);  // aim at two workgroups per compute unit
+  if (ch > 64) ch = 64;
+  if (ch > gm.slabs) ch = gm.slabs;
+  if (ch < 1) ch = 1;
+  gm.spc = (gm.slabs + ch - 1) / ch;
+  gm.chunks = (gm.slabs + gm.spc - 1) / gm.spc;
+  return gm;
+}
+size_t conv_grad_partial_bytes(int B, int Himg, int Wimg, int C, int dtype, int layers) {
+  const ConvGradGeom gm = conv_grad_geom(B, Himg, Wimg, C, dtype, layers);
+  if (!gm.ok || gm.chunks <= 1) return 0;
+  return (size_t)gm.chunks * layers * 9 * C * C * sizeof(float);
+}
+template <typename OT, int TM, int TN>
+static hipError_t launch_conv_grad(const GradArgs& a, unsigned blocks, size_t smem, hipStream_t s) {
+  if (smem > 64 * 1024) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_grad_kernel<OT, TM, TN>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL((conv_grad_kernel<OT, TM, TN>), dim3(blocks), dim3(NT), smem, s, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_grad(const GradArgs& a_in, int layer_kind, int dtype, int groups, hipStream_t s) {
   if (groups <= 0) return hipSuccess;
   GradArgs a = a_in;
@@ -1176,12 +1404,36 @@ hipError_t launch_grad(const GradArgs& a_in, int layer_kind, int dtype, int grou
       if (dtype == 0) hipLaunchKernelGGL((dense_grad_kernel<float>), grid, dim3(NT), 0, s, a);
       else            hipLaunchKernelGGL((dense_grad_kernel<__bf16>), grid, dim3(NT), 0, s, a);
     }
-  } else {
-    a.tiles = 9;
-    if (a.dW) {
+  } else if (a.dW) {
+    const ConvGradGeom gm = conv_grad_geom(a.B, a.Himg, a.Wimg, a.Nf, dtype, groups);
+    if (!gm.ok) {
+      a.tiles = 9;
       dim3 grid(9u * (unsigned)groups);
-      if (dtype == 0) hipLaunchKernelGGL((conv_grad_kernel<float>), grid, dim3(NT), 0, s, a);
-      else            hipLaunchKernelGGL((conv_grad_kernel<__bf16>), grid, dim3(NT), 0, s, a);
+      if (dtype == 0) hipLaunchKernelGGL((conv_grad_tap_kernel<float>), grid, dim3(NT), 0, s, a);
+      else            hipLaunchKernelGGL((conv_grad_tap_kernel<__bf16>), grid, dim3(NT), 0, s, a);
+    } else {
+      a.layers = groups;
+      a.gWp = gm.Wp; a.gR = gm.R; a.gKL = gm.KL; a.gPU = gm.PU; a.gPG = gm.PG;
+      a.gspi = gm.spi; a.gslabs = gm.slabs; a.gchunks = gm.chunks; a.gspc = gm.spc;
+      a.tiles = gm.chunks;
+      const int tm = a.Nf > 32 ? 2 : 1, tn = ((9 * a.Nf + 31) / 32 + 3) / 4;
+      hipError_t e = hipErrorInvalidValue;                 // also the result if the partial-sum buffer is missing
+      const unsigned blocks = (unsigned)gm.chunks * (unsigned)groups;
+      const bool have_buf = gm.chunks == 1 || a.partial != nullptr;
+#define MGRIT_CG(TM_, TN_)                                                                                     \
+      if (have_buf && tm == TM_ && tn == TN_)                                                                   \
+        e = dtype == 0 ? launch_conv_grad<float, TM_, TN_>(a, blocks, gm.smem, s)                               \
+                       : launch_conv_grad<__bf16, TM_, TN_>(a, blocks, gm.smem, s);
+      MGRIT_CG(1, 1) MGRIT_CG(1, 2) MGRIT_CG(1, 3) MGRIT_CG(2, 3) MGRIT_CG(2, 4) MGRIT_CG(2, 5)
+#undef MGRIT_CG
+      if (e != hipSuccess) { trace_after(s, TRACE_GRAD, groups); return e; }
+      if (gm.chunks > 1) {
+        const long long total4 = (long long)groups * a.wsize / 4;
+        long long nb = (total4 + NT - 1) / NT;
+        if (nb > 4096) nb = 4096;
+        hipLaunchKernelGGL(conv_grad_reduce_kernel, dim3((unsigned)nb), dim3(NT), 0, s, a.partial, a.dW, total4,
+                           gm.chunks, a.hs);
+      }
     }
   }
   if (a.db) hipLaunchKernelGGL(bias_grad_kernel, dim3((a.Nf + 63) / 64, groups), dim3(NT), 0, s, a);

@@ -61,6 +61,33 @@ def test_cfg3_full_elementwise():
     assert abs(hist[0] - hist_o[0]) <= 1e-3 * hist_o[0], (hist, hist_o)
 
 
+def test_cfg3_full_adjoint_elementwise():
+    """Adjoint solve and parameter gradient (layers split into partial sums) at full size, element by element.
+
+    ReLU' is a 0/1 decision on the sign of z = A u + b, and one flipped decision changes a gradient entry by
+    O(1), so both sides must take every decision identically.  The weights, biases and the states to linearise
+    about are therefore put on coarse binary grids (weights in steps of 2^-7 below 1/2, states in steps of 2^-5
+    below 2, biases in steps of 2^-12): every product and every partial sum of the 144 terms of z is then exact
+    in float32 in any summation order, so z is the same number on both sides."""
+    wl = I.cfg3(1)
+    _say(wl.name + " adjoint + gradient")
+    data = dict(I.generate(wl))
+    data["W"] = (np.clip(np.round(data["W"] * 128.0), -63, 63) / 128.0).astype(np.float32)
+    data["b"] = (np.round(data["b"] * 4096.0) / 4096.0).astype(np.float32)
+    Uo, _, _ = oracle_forward(wl, data)
+    U = (np.clip(np.round(Uo * 32.0), -63, 63) / 32.0).astype(np.float32)
+    del Uo
+    rng = np.random.default_rng(21)
+    lamN = (rng.standard_normal(wl.state_shape) / wl.B).astype(np.float32)
+    gp = GpuProblem(wl, data)
+    Lam, dW, db, hist, it = gp.adjoint(U, lamN)
+    Lo, dWo, dbo, hist_o, _ = O.fas_adjoint(data["W"], data["b"], U, lamN, wl.h, wl.m, wl.max_levels, wl.min_coarse,
+                                            wl.relax, wl.max_iter, wl.layer, wl.act)
+    eL, eW, eb = rel_l2_per_state(Lam, Lo), rel_l2_per_state(dW, dWo), rel_l2_per_state(db, dbo)
+    print(f"cfg3 adjoint: Lam {eL:.3e}  dW {eW:.3e}  db {eb:.3e}", flush=True)
+    assert eL <= 1e-5 and eW <= 1e-5 and eb <= 1e-5, (eL, eW, eb)
+
+
 def _sampled_f_point_checks(wl, data, U, rng, n_samples):
     """Every F-point j (j % m != 0) equals one layer step of point j-1 after the closing F-relaxation."""
     W64 = data["W"]
@@ -93,6 +120,38 @@ def test_cfg4_full_sampled():
     inc = rel_l2_per_state(U[1:wl.m + 1] - U[0], Us[1:] - Us[0])
     assert inc <= 2e-2, inc
     del U
+
+
+def test_cfg4_full_adjoint_gradient_sampled():
+    """Adjoint solve and parameter gradient of the large conv workload (one workgroup per layer, no partial
+    sums): sampled adjoint F-points and sampled layer gradients, recomputed by the oracle from the GPU's own
+    neighbouring values."""
+    wl = I.cfg4(2)
+    _say(wl.name + " adjoint + gradient")
+    data = I.generate(wl)
+    gp = GpuProblem(wl, data)
+    _, U, _, _ = gp.forward()
+    # ReLU' is a 0/1 decision on the sign of z: both sides take it from the same bf16-representable states
+    U = I.round_to_bf16(U)
+    rng = np.random.default_rng(22)
+    lamN = (rng.standard_normal(wl.state_shape) / wl.B).astype(np.float32)
+    Lam, dW, db, hist, it = gp.adjoint(U, lamN)
+    assert it == 2 and hist[1] < hist[0]
+    same = bool(np.array_equal(Lam[wl.N], lamN))
+    assert same
+    W, b = data["W"], data["b"]
+    for n in rng.choice(np.arange(wl.N), size=4, replace=False):
+        Wn, bn, Un = W[n].astype(np.float64), b[n].astype(np.float64), U[n].astype(np.float64)
+        if n % wl.m != 0:
+            ref = O.adjoint_step(Lam[n + 1].astype(np.float64), Un, Wn, bn, wl.h, wl.layer, wl.act)
+            e = _rel(Lam[n].astype(np.float64) - Lam[n + 1], ref - Lam[n + 1])
+            assert e <= 2e-2, (n, e)
+        G = O.act_prime(O.affine(Un, Wn, bn, wl.layer), wl.act) * Lam[n + 1].astype(np.float64)
+        gW, gb = O.weight_grad(G, Un, wl.layer)
+        eW, eb = _rel(dW[n], wl.h * gW), _rel(db[n], wl.h * gb)
+        print(f"cfg4 layer {n}: dW {eW:.3e} db {eb:.3e}", flush=True)
+        assert eW <= 2e-2 and eb <= 2e-2, (n, eW, eb)
+    del U, Lam, dW
 
 
 @pytest.fixture(scope="module")

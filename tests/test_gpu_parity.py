@@ -250,6 +250,26 @@ CONV_ADJ_CASES = [
     I.reduced(I.cfg4(1), name="adj_conv_bf16_c64_8x8_B3_N16_m4", B=3, Himg=8, Wimg=8, N=16, m=4, max_levels=2),
     I.reduced(I.cfg3(1), name="adj_conv_fp32_c24_7x5_B2_N8_m2", B=2, C=24, Himg=7, Wimg=5, N=8, m=2,
               lifted_input=False),
+    # shapes of the all-taps gradient kernel: every (row blocks, column blocks per wavefront) arrangement,
+    # one slab per layer (no partial sums), ragged last slab, widest row it takes, and the per-tap
+    # kernel that wider rows fall back to
+    I.reduced(I.cfg4(1), name="adj_conv_bf16_c64_32x32_B2_N8", B=2, N=8, m=2, max_levels=2, act=I.TANH),
+    I.reduced(I.cfg3(1), name="adj_conv_fp32_c8_2x32_B1_N4_one_slab", B=1, C=8, Himg=2, Wimg=32, N=4, m=2,
+              lifted_input=False, act=I.TANH),
+    I.reduced(I.cfg3(1), name="adj_conv_fp32_c32_7x28_B2_N4", B=2, C=32, Himg=7, Wimg=28, N=4, m=2,
+              lifted_input=False, act=I.TANH),
+    I.reduced(I.cfg4(1), name="adj_conv_bf16_c40_5x40_B2_N4", B=2, C=40, Himg=5, Wimg=40, N=4, m=2, max_levels=2,
+              act=I.TANH),
+    I.reduced(I.cfg4(1), name="adj_conv_bf16_c48_9x12_B3_N4", B=3, C=48, Himg=9, Wimg=12, N=4, m=2, max_levels=2,
+              act=I.TANH),
+    I.reduced(I.cfg4(1), name="adj_conv_bf16_c56_3x64_B2_N4", B=2, C=56, Himg=3, Wimg=64, N=4, m=2, max_levels=2,
+              act=I.TANH),
+    I.reduced(I.cfg3(1), name="adj_conv_fp32_c8_2x256_B1_N4_wide", B=1, C=8, Himg=2, Wimg=256, N=4, m=2,
+              lifted_input=False, act=I.TANH),
+    I.reduced(I.cfg3(1), name="adj_conv_fp32_c16_1x9_B2_N4", B=2, C=16, Himg=1, Wimg=9, N=4, m=2,
+              lifted_input=False, act=I.TANH),
+    I.reduced(I.cfg3(1), name="adj_conv_fp32_c16_7x1_B2_N4", B=2, C=16, Himg=7, Wimg=1, N=4, m=2,
+              lifted_input=False, act=I.TANH),
 ]
 
 
