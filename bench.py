@@ -18,7 +18,8 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-PEAK = {"fp32_mfma": 157.3, "bf16_mfma": 2500.0}       # TFLOP/s, published dense peaks of MI355X
+PEAK = {"fp32_mfma": 157.3, "bf16_mfma": 2500.0,       # TFLOP/s, published dense peaks of MI355X
+        "hbm_GBps": 8000.0}
 
 # Measured HBM bytes per launch of the dominant kernel (rocprofv3 --pmc FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0,
 # mean over the dispatches of the same bench command; summaries and the calibration of the two factors
@@ -149,16 +150,23 @@ def main():
     else:
         flops_per_unit = 2.0 * wl.B * wl.Himg * wl.Wimg * wl.C * 9 * wl.C
         bytes_per_unit = 9 * wl.C * wl.C * (4 if wl.dtype == I.FP32 else 2) + 2 * wl.E * 4
-    peak = PEAK["fp32_mfma"] if wl.dtype == I.FP32 else PEAK["bf16_mfma"]
+    peak_mfma = PEAK["fp32_mfma"] if wl.dtype == I.FP32 else PEAK["bf16_mfma"]
     avg_us = ms_tot * 1e3 / launches
-    achieved = units * flops_per_unit / (ms_tot * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 3), "peak": peak,
-                "unit": "TFLOP/s", "frac": round(achieved / peak, 5),
+    tflops = units * flops_per_unit / (ms_tot * 1e-3) / 1e12
+    gbps = units * bytes_per_unit / (ms_tot * 1e-3) / 1e9
+    # the roof that binds is the one that takes longer for this kernel's flops and algorithmic bytes
+    hbm_bound = bytes_per_unit / (PEAK["hbm_GBps"] * 1e9) > flops_per_unit / (peak_mfma * 1e12)
+    roofline = {"bound": "hbm" if hbm_bound else "mfma", "kernel": dom,
+                "achieved": round(gbps if hbm_bound else tflops, 3),
+                "peak": PEAK["hbm_GBps"] if hbm_bound else peak_mfma,
+                "unit": "GB/s" if hbm_bound else "TFLOP/s",
+                "frac": round(gbps / PEAK["hbm_GBps"] if hbm_bound else tflops / peak_mfma, 5),
                 "traffic": TRAFFIC_BYTES.get((args.workload, dom)),
                 "launches": launches, "avg_launch_us": round(avg_us, 3),
                 "flops_per_launch": units * flops_per_unit / launches,
                 "algorithmic_bytes_per_launch": units * bytes_per_unit / launches,
-                "hbm_GBps_algorithmic": round(units * bytes_per_unit / (ms_tot * 1e-3) / 1e9, 1),
+                "mfma_TFLOPs": round(tflops, 3), "mfma_frac": round(tflops / peak_mfma, 5),
+                "hbm_GBps_algorithmic": round(gbps, 1), "hbm_frac": round(gbps / PEAK["hbm_GBps"], 5),
                 "all_kernels_ms": {k: round(v[0] / args.steps, 4) for k, v in tr.items()}}
 
     out = {"metric": "layer-steps/sec per FAS cycle (forward + adjoint + gradient), 1xMI355X",

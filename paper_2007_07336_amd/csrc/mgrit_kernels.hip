@@ -410,7 +410,7 @@ __global__ __launch_bounds__(NT) void dense_step_kernel(StepArgs a) {
 #ifdef MGRIT_TIMING
   const long long t_loop = __builtin_readcyclecounter();
 #endif
-  static_assert((size_t)(BM + BN) * ST * sizeof(WT) >= (size_t)4 * 32 * (TN * 32 + 4) * 4, "LDS too small to stage the epilogue");
+  static_assert(WC == 2, "the launch wrapper sizes the epilogue staging for two wavefront columns");
   epilogue<TM, TN>(a, gi, layer, acc, row0, (long long)a.M, n0 + wn0, L, red, reinterpret_cast<float*>(smem_raw));
 #ifdef MGRIT_TIMING
   // diagnostic build only: overwrite the norm partial with phase times in cycles
@@ -735,17 +735,18 @@ static size_t conv_smem_bytes(const StepArgs& a, int dtype) {
 }
 
 // Dense tile choice: the largest tile that still gives every CU a workgroup, else the smallest.
-//   0: 64x64 (k slab 32 fp32 / 64 bf16)   1: 128x128   2: 256x256 (bf16 only)
+//   0: 64x64   1: 128x128 (two workgroups per CU; a 256x256 bf16 tile with one workgroup per CU halves the
+//   L2 traffic but measured 8-19 % slower at every group count, its single wavefront per SIMD cannot keep
+//   enough loads in flight)
 //  -1: 32x32 with the contraction split over the four wavefronts (latency-bound small launches)
 static int dense_tile_class(const StepArgs& a, int dtype, int groups) {
   auto wgs = [&](int t) { return (long long)((a.M + t - 1) / t) * ((a.Nf + t - 1) / t) * groups; };
-  if (dtype != 0 && wgs(256) >= 256) return 2;
   if (wgs(128) >= 256) return 1;
   static const long long ks_limit = getenv("MGRIT_KSPLIT_WGS") ? atoll(getenv("MGRIT_KSPLIT_WGS")) : 256;
   if (wgs(64) < ks_limit) return -1;
   return 0;
 }
-static int dense_tile_edge(int cls) { return cls == 2 ? 256 : cls == 1 ? 128 : cls == 0 ? 64 : 32; }
+static int dense_tile_edge(int cls) { return cls == 1 ? 128 : cls == 0 ? 64 : 32; }
 
 int step_grid_blocks(const StepArgs& a, int layer_kind, int dtype, int groups) {
   if (layer_kind == 1) {
@@ -758,7 +759,9 @@ int step_grid_blocks(const StepArgs& a, int layer_kind, int dtype, int groups) {
 
 template <typename WT, int BM, int BN, int BK, int PF>
 static void launch_dense(dim3 grid, hipStream_t s, const StepArgs& a) {
-  constexpr size_t smem = (size_t)(BM + BN) * (BK + Op<WT>::PAD) * sizeof(WT);
+  constexpr size_t tiles_b = (size_t)(BM + BN) * (BK + Op<WT>::PAD) * sizeof(WT);
+  constexpr size_t stage_b = (size_t)4 * 32 * (BN / 2 + 4) * sizeof(float);   // epilogue staging, 2 wavefront columns
+  constexpr size_t smem = tiles_b > stage_b ? tiles_b : stage_b;
   static bool raised = false;              // opt in once to more than 64 KB of dynamic LDS
   if (smem > 64 * 1024 && !raised) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(dense_step_kernel<WT, BM, BN, 2, 2, BK, PF>),
@@ -802,9 +805,6 @@ hipError_t launch_step(const StepArgs& a_in, int layer_kind, int dtype, int grou
       cls = dtype == 0 ? TRACE_DENSE_F32_KS : TRACE_DENSE_BF16_KS;
       if (dtype == 0) hipLaunchKernelGGL((dense_ksplit_kernel<float>), grid, dim3(NT), 0, s, a);
       else            hipLaunchKernelGGL((dense_ksplit_kernel<__bf16>), grid, dim3(NT), 0, s, a);
-    } else if (tc == 2) {
-      cls = TRACE_DENSE_BF16_256;
-      launch_dense<__bf16, 256, 256, 64, 1>(grid, s, a);
     } else if (tc == 1) {
       cls = dtype == 0 ? TRACE_DENSE_F32_128 : TRACE_DENSE_BF16_128;
       if (dtype == 0) launch_dense<float, 128, 128, 32, 2>(grid, s, a);
@@ -921,17 +921,32 @@ hipError_t launch_norm_final(const float* partial, int n, double scale, double* 
 // ------------------------------------------------------------------------------------------
 template <typename WT>
 __global__ __launch_bounds__(NT) void transpose_dense_kernel(const WT* W, WT* Wt, int q) {
-  __shared__ WT tile[32][33];
+  // 64x64 tile per workgroup; a thread moves 4 consecutive elements, so a row segment of the tile is
+  // 128 (2-byte elements) or 256 contiguous bytes on both the reading and the writing side.  q % 8 == 0,
+  // hence a group of 4 is inside the matrix or outside it as a whole.
+  __shared__ WT tile[64][64 + 4];
   const long long layer = blockIdx.z;
   const WT* src = W + layer * (long long)q * q;
   WT* dst = Wt + layer * (long long)q * q;
-  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;     // 32 x 8
-  const int x0 = blockIdx.x * 32, y0 = blockIdx.y * 32;
-  for (int j = ty; j < 32; j += 8)
-    if (y0 + j < q && x0 + tx < q) tile[j][tx] = src[(long long)(y0 + j) * q + x0 + tx];
+  const int tx = (threadIdx.x & 15) * 4, ty = threadIdx.x >> 4;   // 16 groups of 4 across, 16 rows down
+  const int x0 = blockIdx.x * 64, y0 = blockIdx.y * 64;
+#pragma unroll
+  for (int j = 0; j < 64; j += 16) {
+    const int y = y0 + ty + j;
+    if (y < q && x0 + tx < q) {
+      const WT* p = src + (long long)y * q + x0 + tx;
+      tile[ty + j][tx] = p[0]; tile[ty + j][tx + 1] = p[1]; tile[ty + j][tx + 2] = p[2]; tile[ty + j][tx + 3] = p[3];
+    }
+  }
   __syncthreads();
-  for (int j = ty; j < 32; j += 8)
-    if (x0 + j < q && y0 + tx < q) dst[(long long)(x0 + j) * q + y0 + tx] = tile[tx][j];
+#pragma unroll
+  for (int j = 0; j < 64; j += 16) {
+    const int x = x0 + ty + j;                     // row of the transposed matrix
+    if (x < q && y0 + tx < q) {
+      WT* p = dst + (long long)x * q + y0 + tx;
+      p[0] = tile[tx][ty + j]; p[1] = tile[tx + 1][ty + j]; p[2] = tile[tx + 2][ty + j]; p[3] = tile[tx + 3][ty + j];
+    }
+  }
 }
 template <typename WT>
 __global__ __launch_bounds__(NT) void transpose_conv_kernel(const WT* K, WT* Kt, int C, long long total) {
@@ -949,7 +964,7 @@ __global__ __launch_bounds__(NT) void transpose_conv_kernel(const WT* K, WT* Kt,
 hipError_t launch_transpose_weights(const void* W, void* Wt, int layer_kind, int dtype, int layers, int Nf,
                                     hipStream_t s) {
   if (layer_kind == 0) {
-    dim3 grid((Nf + 31) / 32, (Nf + 31) / 32, layers);
+    dim3 grid((Nf + 63) / 64, (Nf + 63) / 64, layers);
     if (dtype == 0) hipLaunchKernelGGL((transpose_dense_kernel<float>), grid, dim3(NT), 0, s, (const float*)W, (float*)Wt, Nf);
     else hipLaunchKernelGGL((transpose_dense_kernel<uint16_t>), grid, dim3(NT), 0, s, (const uint16_t*)W, (uint16_t*)Wt, Nf);
   } else {
