@@ -242,7 +242,7 @@ def main():
         # cycle count) cut to its first Ns layers and, if one pass is still too long, to its first Bs samples;
         # if one pass is short it is repeated.  Layer steps are counted as for the GPU, scaled by Bs / B.
         flop_step = 2.0 * wl.E * (wl.q if wl.layer == I.DENSE else 9 * wl.C)       # one layer step, whole batch
-        budget = 1.4e12 if wl.layer == I.DENSE else 5.0e11                          # flops of oracle work aimed at
+        budget = 4.0e12 if wl.layer == I.DENSE else 5.0e11                          # flops of oracle work aimed at
         per_layer = 3.2 * cyc_factor(adjoint) * args.cycles
         Ns, unit, Bs = wl.N, wl.m ** (len(sizes) - 1), wl.B
         while Ns > unit and Ns * per_layer * flop_step > budget:
@@ -250,7 +250,6 @@ def main():
         Ns = max(unit, (Ns // unit) * unit)
         while Bs > 1 and Ns * per_layer * flop_step * Bs / wl.B > budget:
             Bs //= 2
-        reps = int(min(50, max(1, budget // (Ns * per_layer * flop_step * Bs / wl.B))))
         sizes_s = O.level_sizes(Ns, wl.m, wl.max_levels, wl.min_coarse)
         Ws, bs, u0s = data["W"][:Ns], data["b"][:Ns], data["u0"][:Bs]
         cyc = args.cycles
@@ -261,12 +260,16 @@ def main():
             sample += " + adjoint solve + gradient"
         lam_np = lamN.cpu().numpy()[:Bs] if adjoint else None
         a = time.perf_counter()
-        for _ in range(reps):
+        reps, want = 0, 1
+        while reps < want:
             Uo, _, _ = O.fas_forward(Ws, bs, u0s, wl.h, wl.m, wl.max_levels, wl.min_coarse,
                                      wl.relax, cyc, wl.layer, wl.act)
             if adjoint:
                 O.fas_adjoint(Ws, bs, Uo, lam_np, wl.h, wl.m, wl.max_levels, wl.min_coarse, wl.relax,
                               cyc, wl.layer, wl.act)
+            reps += 1
+            if reps == 1:                                          # short pass: repeat it up to about 12 s in all
+                want = int(min(50, max(1, 12.0 // max(time.perf_counter() - a, 1e-3))))
         dt = time.perf_counter() - a
         n_cpu = n_cpu * reps * (Bs / wl.B)
         sample += ", %d pass(es)" % reps

@@ -24,8 +24,9 @@
  *          z[b,y,x,o] = sum_{dy,dx,i} W[o][dy][dx][i] u[b,y+dy-1,x+dx-1,i] + b[o]
  *   W is float when dtype = MGRIT_FP32 and bf16 (upper 16 bits of a float, 2 bytes) when
  *   dtype = MGRIT_BF16.  With MGRIT_BF16 the matrix-core operands (weights and the state
- *   operand of the affine map) are bf16 and everything else -- accumulation, bias,
- *   activation, the skip add, states, residuals, corrections -- is float.
+ *   operand of the affine map; in the parameter gradient G = act' * Lam and U, and for conv
+ *   layers also the G that is summed into db) are rounded to bf16 and everything else --
+ *   accumulation, bias, activation, the skip add, states, residuals, corrections -- is float.
  *   State arrays over points are [N+1][state].
  *
  * Return value of every int32_t function: MGRIT_OK or one of the negative codes below.

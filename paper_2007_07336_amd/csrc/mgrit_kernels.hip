@@ -1174,6 +1174,7 @@ __global__ __launch_bounds__(NT) void conv_grad_kernel(GradArgs a) {
   const int Wp = a.gWp, R = a.gR, PU = a.gPU, PG = a.gPG, KL = a.gKL;
   OT* Ut = reinterpret_cast<OT*>(smem_raw);             // [3][C][PU]
   OT* Gt = Ut + 3 * C * PU;                             // [C][PG]
+  OT* ones = Gt + C * PG;                               // [PU] of 1: the operand row of column 9C, the bias gradient
   const int L = logical_block();
   const int gi = L / a.gchunks, ch = L % a.gchunks;
   const float* Up = a.U + (a.um.base + gi * a.um.stride) * a.E;
@@ -1183,6 +1184,7 @@ __global__ __launch_bounds__(NT) void conv_grad_kernel(GradArgs a) {
   {
     const int n16 = (int)(((size_t)3 * C * PU + (size_t)C * PG) * sizeof(OT) / 16);
     for (int p = tid; p < n16; p += NT) reinterpret_cast<uint4*>(smem_raw)[p] = make_uint4(0u, 0u, 0u, 0u);
+    for (int p = tid; p < PU; p += NT) ones[p] = static_cast<OT>(1.0f);
   }
 
   // this thread's 4x4 blocks: one of G, up to three of the U patch (channel group fastest, then x, then row)
@@ -1275,17 +1277,18 @@ __global__ __launch_bounds__(NT) void conv_grad_kernel(GradArgs a) {
     }
   };
 
-  // this lane's operand rows: output channel o for A, column n = tap * C + i for B (clamped: the blocks
-  // past the end compute values that are never stored)
+  // this lane's operand rows: output channel o for A, column n = tap * C + i for B; column 9C multiplies G by
+  // ones, which sums it over the pixels (the bias gradient).  Clamped: blocks past the end compute values
+  // that are never stored.
   const OT* arow[TM];
   const OT* brow[TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i) arow[i] = Gt + min(32 * i + c, C - 1) * PG;
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
-    const int n = min(32 * (wave + 4 * j) + c, 9 * C - 1);
+    const int n = min(32 * (wave + 4 * j) + c, 9 * C);
     const int tap = n / C, ii = n % C;
-    brow[j] = Ut + ((tap % 3) * C + ii) * PU + (tap / 3) * Wp;
+    brow[j] = n == 9 * C ? ones : Ut + ((tap % 3) * C + ii) * PU + (tap / 3) * Wp;
   }
   floatx16 acc[TM][TN];
 #pragma unroll
@@ -1311,9 +1314,13 @@ __global__ __launch_bounds__(NT) void conv_grad_kernel(GradArgs a) {
     }
   }
   const bool direct = a.gchunks == 1;
-  float* dst = direct ? a.dW + (long long)gi * a.wsize : a.partial + ((long long)ch * a.layers + gi) * a.wsize;
-  const float scale = direct ? a.hs : 1.0f;
   const int NC = 9 * C;
+  const long long pstride = a.wsize + C;                // a partial-sum record: dK of the layer, then db
+  float* dKd = direct ? (a.dW ? a.dW + (long long)gi * a.wsize : nullptr)
+                      : a.partial + ((long long)ch * a.layers + gi) * pstride;
+  float* dbd = direct ? (a.db ? a.db + (long long)gi * C : nullptr)
+                      : a.partial + ((long long)ch * a.layers + gi) * pstride + a.wsize;
+  const float scale = direct ? a.hs : 1.0f;
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -1322,22 +1329,28 @@ __global__ __launch_bounds__(NT) void conv_grad_kernel(GradArgs a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int o = 32 * i + 8 * (r >> 2) + 4 * g + (r & 3);
-        if (o < C && n < NC) dst[(long long)o * NC + n] = scale * acc[i][j][r];
+        if (o < C) {
+          if (n < NC) { if (dKd) dKd[(long long)o * NC + n] = scale * acc[i][j][r]; }
+          else if (n == NC) { if (dbd) dbd[o] = scale * acc[i][j][r]; }
+        }
       }
     }
 }
-// dK = hs * (sum of the chunk partial sums, in chunk order)
-__global__ __launch_bounds__(NT) void conv_grad_reduce_kernel(const float* partial, float* dW, long long total4,
-                                                              int chunks, float hs) {
+// dK and db = hs * (sum of the chunk partial sums, in chunk order).  A record holds wsize values of dK and C of db.
+__global__ __launch_bounds__(NT) void conv_grad_reduce_kernel(const float* partial, float* dW, float* db, int layers,
+                                                              long long wsize, int C, int chunks, float hs) {
+  const long long rec4 = (wsize + C) / 4, total4 = rec4 * layers;
   const float4* src = reinterpret_cast<const float4*>(partial);
-  float4* dst = reinterpret_cast<float4*>(dW);
   for (long long i = (long long)blockIdx.x * NT + threadIdx.x; i < total4; i += (long long)gridDim.x * NT) {
     float4 s = src[i];
     for (int k = 1; k < chunks; ++k) {
       const float4 v = src[(long long)k * total4 + i];
       s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
     }
-    dst[i] = make_float4(hs * s.x, hs * s.y, hs * s.z, hs * s.w);
+    const float4 o = make_float4(hs * s.x, hs * s.y, hs * s.z, hs * s.w);
+    const long long layer = i / rec4, e = (i % rec4) * 4;
+    if (e < wsize) { if (dW) *reinterpret_cast<float4*>(dW + layer * wsize + e) = o; }
+    else if (db) *reinterpret_cast<float4*>(db + layer * C + (e - wsize)) = o;
   }
 }
 
@@ -1382,7 +1395,7 @@ ConvGradGeom conv_grad_geom(int B, int Himg, int Wimg, int C, int dtype, int lay
   gm.PG = gm.KL + pad;
   gm.spi = (Himg + gm.R - 1) / gm.R;
   gm.slabs = B * gm.spi;
-  gm.smem = ((size_t)3 * C * gm.PU + (size_t)C * gm.PG) * es;
+  gm.smem = ((size_t)3 * C * gm.PU + (size_t)C * gm.PG + gm.PU) * es;      // U copies, G, the row of ones
   gm.ok = Wimg <= 64 && gm.smem <= (size_t)150 * 1024;
   int ch = (512 + layers - 1) / (layers > 0 ? layers : 1);  // aim at two workgroups per compute unit
   if (ch > 64) ch = 64;
@@ -1395,7 +1408,7 @@ ConvGradGeom conv_grad_geom(int B, int Himg, int Wimg, int C, int dtype, int lay
 size_t conv_grad_partial_bytes(int B, int Himg, int Wimg, int C, int dtype, int layers) {
   const ConvGradGeom gm = conv_grad_geom(B, Himg, Wimg, C, dtype, layers);
   if (!gm.ok || gm.chunks <= 1) return 0;
-  return (size_t)gm.chunks * layers * 9 * C * C * sizeof(float);
+  return (size_t)gm.chunks * layers * (9 * C * C + C) * sizeof(float);
 }
 template <typename OT, int TM, int TN>
 static hipError_t launch_conv_grad(const GradArgs& a, unsigned blocks, size_t smem, hipStream_t s) {
@@ -1419,19 +1432,22 @@ hipError_t launch_grad(const GradArgs& a_in, int layer_kind, int dtype, int grou
       if (dtype == 0) hipLaunchKernelGGL((dense_grad_kernel<float>), grid, dim3(NT), 0, s, a);
       else            hipLaunchKernelGGL((dense_grad_kernel<__bf16>), grid, dim3(NT), 0, s, a);
     }
-  } else if (a.dW) {
+  } else if (a.dW || a.db) {
     const ConvGradGeom gm = conv_grad_geom(a.B, a.Himg, a.Wimg, a.Nf, dtype, groups);
-    if (!gm.ok) {
+    if (!gm.ok) {                                          // wide image rows: one workgroup per (layer, tap)
       a.tiles = 9;
-      dim3 grid(9u * (unsigned)groups);
-      if (dtype == 0) hipLaunchKernelGGL((conv_grad_tap_kernel<float>), grid, dim3(NT), 0, s, a);
-      else            hipLaunchKernelGGL((conv_grad_tap_kernel<__bf16>), grid, dim3(NT), 0, s, a);
-    } else {
+      if (a.dW) {
+        dim3 grid(9u * (unsigned)groups);
+        if (dtype == 0) hipLaunchKernelGGL((conv_grad_tap_kernel<float>), grid, dim3(NT), 0, s, a);
+        else            hipLaunchKernelGGL((conv_grad_tap_kernel<__bf16>), grid, dim3(NT), 0, s, a);
+      }
+      if (a.db) hipLaunchKernelGGL(bias_grad_kernel, dim3((a.Nf + 63) / 64, groups), dim3(NT), 0, s, a);
+    } else {                                               // all taps and the bias gradient in one kernel
       a.layers = groups;
       a.gWp = gm.Wp; a.gR = gm.R; a.gKL = gm.KL; a.gPU = gm.PU; a.gPG = gm.PG;
       a.gspi = gm.spi; a.gslabs = gm.slabs; a.gchunks = gm.chunks; a.gspc = gm.spc;
       a.tiles = gm.chunks;
-      const int tm = a.Nf > 32 ? 2 : 1, tn = ((9 * a.Nf + 31) / 32 + 3) / 4;
+      const int tm = a.Nf > 32 ? 2 : 1, tn = ((9 * a.Nf + 1 + 31) / 32 + 3) / 4;
       hipError_t e = hipErrorInvalidValue;                 // also the result if the partial-sum buffer is missing
       const unsigned blocks = (unsigned)gm.chunks * (unsigned)groups;
       const bool have_buf = gm.chunks == 1 || a.partial != nullptr;
@@ -1443,15 +1459,15 @@ hipError_t launch_grad(const GradArgs& a_in, int layer_kind, int dtype, int grou
 #undef MGRIT_CG
       if (e != hipSuccess) { trace_after(s, TRACE_GRAD, groups); return e; }
       if (gm.chunks > 1) {
-        const long long total4 = (long long)groups * a.wsize / 4;
+        const long long total4 = (long long)groups * (a.wsize + a.Nf) / 4;
         long long nb = (total4 + NT - 1) / NT;
         if (nb > 4096) nb = 4096;
-        hipLaunchKernelGGL(conv_grad_reduce_kernel, dim3((unsigned)nb), dim3(NT), 0, s, a.partial, a.dW, total4,
-                           gm.chunks, a.hs);
+        hipLaunchKernelGGL(conv_grad_reduce_kernel, dim3((unsigned)nb), dim3(NT), 0, s, a.partial, a.dW, a.db, groups,
+                           a.wsize, a.Nf, gm.chunks, a.hs);
       }
     }
   }
-  if (a.db) hipLaunchKernelGGL(bias_grad_kernel, dim3((a.Nf + 63) / 64, groups), dim3(NT), 0, s, a);
+  if (a.db && layer_kind == 0) hipLaunchKernelGGL(bias_grad_kernel, dim3((a.Nf + 63) / 64, groups), dim3(NT), 0, s, a);
   const hipError_t e = hipGetLastError();
   trace_after(s, TRACE_GRAD, groups);
   return e;
