@@ -202,14 +202,18 @@ __device__ __forceinline__ EpiPtrs epi_ptrs(const StepArgs& a, int gi, long long
 // stage (column-consecutive lanes), then batches of row reads with all global loads of a batch
 // issued before its arithmetic and stores.  `stage_all` is workgroup LDS of at least
 // 4 * 32 * (32 TN + 4) floats that the main loop no longer needs.
-template <int TM, int TN>
+// With XREG the skip-connection operand x is not read from memory: the caller hands it over in registers,
+// xreg[tm * NIT + h] = the float4 this lane handles in instruction h of block row tm (the conv kernel
+// loads its input tile in exactly this arrangement).
+template <int TM, int TN, bool XREG = false, int NX = 1>
 __device__ __forceinline__ void epilogue(const StepArgs& a, int gi, long long layer, floatx16 (&acc)[TM][TN],
                                          const long long (&row0)[TM], long long row_end, int colbase, int L,
-                                         float* red, float* stage_all) {
+                                         float* red, float* stage_all, const float4 (&xreg)[NX]) {
   constexpr int SW = TN * 32 + 4;            // staging row stride in floats
   constexpr int LPR = TN * 8;                // lanes per sub-tile row
   constexpr int RPI = 64 / LPR;              // rows per wave instruction
   constexpr int NIT = 32 / RPI;              // instructions per block row
+  static_assert(!XREG || NX == TM * NIT, "one register operand per lane and row instruction");
   constexpr int HB = TN >= 4 ? 8 : 4;        // instructions batched together (register budget)
   const EpiPtrs e = epi_ptrs(a, gi, layer);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 5, c = lane & 31;
@@ -243,7 +247,10 @@ __device__ __forceinline__ void epilogue(const StepArgs& a, int gi, long long la
       const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
       // unconditional loads (rows / columns outside the tile read element 0 and are never stored)
 #pragma unroll
-      for (int i = 0; i < HB; ++i) xv[i] = dact ? zero : *reinterpret_cast<const float4*>(e.Xp + off[i]);
+      for (int i = 0; i < HB; ++i) {
+        if (XREG) xv[i] = xreg[XREG ? tm * NIT + h0 + i : 0];
+        else xv[i] = dact ? zero : *reinterpret_cast<const float4*>(e.Xp + off[i]);
+      }
       if (e.E1p) {
 #pragma unroll
         for (int i = 0; i < HB; ++i) e1[i] = *reinterpret_cast<const float4*>(e.E1p + off[i]);
@@ -287,6 +294,14 @@ __device__ __forceinline__ void epilogue(const StepArgs& a, int gi, long long la
     const float s = block_sum(sq, red);
     if (threadIdx.x == 0) a.norm_partial[L] = s;
   }
+}
+
+template <int TM, int TN>
+__device__ __forceinline__ void epilogue(const StepArgs& a, int gi, long long layer, floatx16 (&acc)[TM][TN],
+                                         const long long (&row0)[TM], long long row_end, int colbase, int L,
+                                         float* red, float* stage_all) {
+  const float4 none[1] = {make_float4(0.f, 0.f, 0.f, 0.f)};
+  epilogue<TM, TN, false, 1>(a, gi, layer, acc, row0, row_end, colbase, L, red, stage_all, none);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -590,34 +605,87 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
   const float* Dp = a.Dm ? a.Dm + (a.dm.base + gi * a.dm.stride) * a.E : nullptr;
   const WT* Wp = reinterpret_cast<const WT*>(a.W) + layer * a.wsize;
 
-  // ---- input patch -> LDS (converted to the operand type), eight pieces per thread in flight;
-  // loads are unconditional (halo / padding pieces read element 0 and are zeroed afterwards)
+  // ---- input patch -> LDS (converted to the operand type).  The tile's own pixels are loaded in the
+  // arrangement of the epilogue (lane -> 4 channels of a pixel row, NIT rows per 32-pixel block), so the
+  // float values stay in registers as the skip-connection operand and the state is read from memory once;
+  // the halo rows above and below come in the same batch.  Loads are unconditional (pieces outside the
+  // image or the tile read element 0 and are zeroed afterwards); the side columns of the patch are the
+  // zero padding of the image.
+  constexpr int LPR = TN * 8, RPI = 64 / LPR, NIT = 32 / RPI, NX = TM * NIT;
+  const int npx = min(TH, H - y0) * Wd;      // valid pixels of this tile
+  const int lrow = lane / LPR, colq = (lane % LPR) * 4;
+  float4 xreg[NX];
   {
-    const int cq = Cp / 4;
-    const int total = (TH + 2) * PW * cq;
-    constexpr int PU = 8;
-    for (int p0 = tid; p0 < total; p0 += NT * PU) {
-      float4 v[PU], d[PU];
-      unsigned okm = 0;
+    unsigned okm = 0;
 #pragma unroll
-      for (int u = 0; u < PU; ++u) {
+    for (int i = 0; i < NX; ++i) {
+      const int p = (wave * TM + i / NIT) * 32 + (i % NIT) * RPI + lrow;      // tile pixel
+      const bool ok = p < npx && colq < C;
+      const unsigned off = ok ? (unsigned)((((long long)bimg * H + y0) * Wd + p) * C + colq) : 0u;
+      okm |= ok ? (1u << i) : 0u;
+      xreg[i] = *reinterpret_cast<const float4*>(Xp + off);
+    }
+    // halo: patch rows 0 and TH+1 (image rows y0-1 and y0+TH), interior columns only
+    const int cq = Cp / 4;
+    const int htotal = 2 * Wd * cq;
+    constexpr int HU = 4;
+    for (int p0 = tid; p0 < htotal; p0 += NT * HU) {
+      float4 v[HU], d[HU];
+      unsigned hm = 0;
+#pragma unroll
+      for (int u = 0; u < HU; ++u) {
         const int p = p0 + u * NT;
         const int pp = p / cq, c4 = (p % cq) * 4;
-        const int gy = y0 - 1 + pp / PW, gx = pp % PW - 1;
-        const bool ok = p < total && gy >= 0 && gy < H && gx >= 0 && gx < Wd && c4 < C;
-        const unsigned off = ok ? (unsigned)(((bimg * H + gy) * Wd + gx) * C + c4) : 0u;
-        okm |= ok ? (1u << u) : 0u;
+        const int prow = pp < Wd ? 0 : TH + 1, gx = pp < Wd ? pp : pp - Wd;
+        const int gy = y0 - 1 + prow;
+        const bool ok = p < htotal && gy >= 0 && gy < H && c4 < C;
+        const unsigned off = ok ? (unsigned)((((long long)bimg * H + gy) * Wd + gx) * C + c4) : 0u;
+        hm |= ok ? (1u << u) : 0u;
         v[u] = *reinterpret_cast<const float4*>(Xp + off);
         if (Dp) d[u] = *reinterpret_cast<const float4*>(Dp + off);
       }
 #pragma unroll
-      for (int u = 0; u < PU; ++u) {
+      for (int u = 0; u < HU; ++u) {
         const int p = p0 + u * NT;
-        if (p < total) {
+        if (p < htotal) {
+          const int pp = p / cq, c4 = (p % cq) * 4;
+          const int prow = pp < Wd ? 0 : TH + 1, gx = pp < Wd ? pp : pp - Wd;
           float4 w = v[u];
           if (Dp) { w.x *= d[u].x; w.y *= d[u].y; w.z *= d[u].z; w.w *= d[u].w; }
-          if (!((okm >> u) & 1u)) w = make_float4(0.f, 0.f, 0.f, 0.f);
-          cvt_store4(&patch[(p / cq) * CS + (p % cq) * 4], w);
+          if (!((hm >> u) & 1u)) w = make_float4(0.f, 0.f, 0.f, 0.f);
+          cvt_store4(&patch[(prow * PW + gx + 1) * CS + c4], w);
+        }
+      }
+    }
+    // side columns (x = -1 and x = Wd) of every patch row: zero
+    for (int p = tid; p < 2 * (TH + 2) * cq; p += NT) {
+      const int pp = p / cq, c4 = (p % cq) * 4;
+      const int prow = pp >> 1, pcol = (pp & 1) ? PW - 1 : 0;
+      cvt_store4(&patch[(prow * PW + pcol) * CS + c4], make_float4(0.f, 0.f, 0.f, 0.f));
+    }
+    // the tile's own pixels: operand copy to LDS (zero below the last valid row and for padded channels);
+    // the act' factors of the adjoint sweep are fetched one block row at a time to bound the registers
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+      float4 dreg[NIT];
+      if (Dp) {
+#pragma unroll
+        for (int h = 0; h < NIT; ++h) {
+          const int p = (wave * TM + tm) * 32 + h * RPI + lrow;
+          const bool ok = (okm >> (tm * NIT + h)) & 1u;
+          const unsigned off = ok ? (unsigned)((((long long)bimg * H + y0) * Wd + p) * C + colq) : 0u;
+          dreg[h] = *reinterpret_cast<const float4*>(Dp + off);
+        }
+      }
+#pragma unroll
+      for (int h = 0; h < NIT; ++h) {
+        const int i = tm * NIT + h;
+        const int p = (wave * TM + tm) * 32 + h * RPI + lrow;
+        if (p < TH * Wd && colq < Cp) {
+          float4 w = xreg[i];
+          if (Dp) { w.x *= dreg[h].x; w.y *= dreg[h].y; w.z *= dreg[h].z; w.w *= dreg[h].w; }
+          if (!((okm >> i) & 1u)) w = make_float4(0.f, 0.f, 0.f, 0.f);
+          cvt_store4(&patch[((p / Wd + 1) * PW + p % Wd + 1) * CS + colq], w);
         }
       }
     }
@@ -657,7 +725,6 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
   load_w(wreg[0], wmask[0], 0);
   load_w(wreg[1], wmask[1], 1);
 
-  const int npx = min(TH, H - y0) * Wd;      // valid pixels of this tile
   int aoff[TM];
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
@@ -707,7 +774,7 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
   long long row0[TM];
 #pragma unroll
   for (int i = 0; i < TM; ++i) row0[i] = img_row0 + (wave * TM + i) * 32;
-  epilogue<TM, TN>(a, gi, layer, acc, row0, img_row0 + npx, 0, L, red, reinterpret_cast<float*>(smem_raw));
+  epilogue<TM, TN, true, NX>(a, gi, layer, acc, row0, img_row0 + npx, 0, L, red, reinterpret_cast<float*>(smem_raw), xreg);
 }
 
 // ------------------------------------------------------------------------------------------
