@@ -205,18 +205,20 @@ __device__ __forceinline__ EpiPtrs epi_ptrs(const StepArgs& a, int gi, long long
 // With XREG the skip-connection operand x is not read from memory: the caller hands it over in registers,
 // xreg[tm * NIT + h] = the float4 this lane handles in instruction h of block row tm (the conv kernel
 // loads its input tile in exactly this arrangement).
-template <int TM, int TN, bool XREG = false, int NX = 1>
-__device__ __forceinline__ void epilogue(const StepArgs& a, int gi, long long layer, floatx16 (&acc)[TM][TN],
-                                         const long long (&row0)[TM], long long row_end, int colbase, int L,
-                                         float* red, float* stage_all, const float4 (&xreg)[NX]) {
-  constexpr int SW = TN * 32 + 4;            // staging row stride in floats
-  constexpr int LPR = TN * 8;                // lanes per sub-tile row
+// `stage_block(tm, stage)` writes the wavefront's accumulators of block row tm (32 rows x CW columns) to
+// `stage` with row stride CW + 4; it is the only part that depends on the MFMA shape.
+template <int TM, int CW, bool XREG, int NX, typename StageFn>
+__device__ __forceinline__ void epilogue_rows(const StepArgs& a, int gi, long long layer, StageFn stage_block,
+                                              const long long (&row0)[TM], long long row_end, int colbase, int L,
+                                              float* red, float* stage_all, const float4 (&xreg)[NX]) {
+  constexpr int SW = CW + 4;                 // staging row stride in floats
+  constexpr int LPR = CW / 4;                // lanes per sub-tile row
   constexpr int RPI = 64 / LPR;              // rows per wave instruction
   constexpr int NIT = 32 / RPI;              // instructions per block row
   static_assert(!XREG || NX == TM * NIT, "one register operand per lane and row instruction");
-  constexpr int HB = TN >= 4 ? 8 : 4;        // instructions batched together (register budget)
+  constexpr int HB = NIT < 4 ? NIT : (CW >= 128 ? 8 : 4);   // instructions batched together (register budget)
   const EpiPtrs e = epi_ptrs(a, gi, layer);
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 5, c = lane & 31;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   float* stage = stage_all + wave * 32 * SW;
   const int lrow = lane / LPR, colq = (lane % LPR) * 4;
   const int col = colbase + colq;
@@ -228,10 +230,7 @@ __device__ __forceinline__ void epilogue(const StepArgs& a, int gi, long long la
   __syncthreads();                           // every wave is done reading the main loop's LDS tiles
 #pragma unroll
   for (int tm = 0; tm < TM; ++tm) {
-#pragma unroll
-    for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) stage[(8 * (r >> 2) + 4 * g + (r & 3)) * SW + tn * 32 + c] = acc[tm][tn][r];
+    stage_block(tm, stage);
 #pragma unroll
     for (int h0 = 0; h0 < NIT; h0 += HB) {
       float4 z[HB], xv[HB], e1[HB], e2[HB];
@@ -296,6 +295,20 @@ __device__ __forceinline__ void epilogue(const StepArgs& a, int gi, long long la
   }
 }
 
+// 32x32 MFMA blocks: register r of a lane holds row 8 (r / 4) + 4 g + r % 4, column c of the block
+template <int TM, int TN, bool XREG = false, int NX = 1>
+__device__ __forceinline__ void epilogue(const StepArgs& a, int gi, long long layer, floatx16 (&acc)[TM][TN],
+                                         const long long (&row0)[TM], long long row_end, int colbase, int L,
+                                         float* red, float* stage_all, const float4 (&xreg)[NX]) {
+  const int lane = threadIdx.x & 63, g = lane >> 5, c = lane & 31;
+  auto stage_block = [&](int tm, float* stage) {
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) stage[(8 * (r >> 2) + 4 * g + (r & 3)) * (TN * 32 + 4) + tn * 32 + c] = acc[tm][tn][r];
+  };
+  epilogue_rows<TM, TN * 32, XREG, NX>(a, gi, layer, stage_block, row0, row_end, colbase, L, red, stage_all, xreg);
+}
 template <int TM, int TN>
 __device__ __forceinline__ void epilogue(const StepArgs& a, int gi, long long layer, floatx16 (&acc)[TM][TN],
                                          const long long (&row0)[TM], long long row_end, int colbase, int L,
@@ -579,12 +592,17 @@ __global__ __launch_bounds__(NT) void dense_ksplit_kernel(StepArgs a) {
 // loaded to LDS once (zero padding materialised there) and the nine taps read it at shifted
 // offsets, while the [C_out][C_in] weight slice of each tap streams through LDS.
 // ------------------------------------------------------------------------------------------
-template <typename WT, int TN>
+// N16 (float only, at most 16 channels): the output-channel side uses 16x16x4 MFMA blocks, so none of the
+// matrix-core work is spent on padding columns; a wavefront then owns 4 blocks of 16 pixels.
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+template <typename WT, int TN, bool N16 = false>
 __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
-  constexpr int VEC = Op<WT>::VEC, KSTEP = Op<WT>::KSTEP, PAD = Op<WT>::PAD;
+  static_assert(!N16 || (sizeof(WT) == 4 && TN == 1), "the 16-wide variant is float only");
+  constexpr int VEC = Op<WT>::VEC, KSTEP = N16 ? 16 : Op<WT>::KSTEP, PAD = Op<WT>::PAD;
   constexpr int TM = 2;
-  constexpr int CPMAX = 32 * TN;
-  constexpr int WP = (32 * TN * CPMAX / VEC + NT - 1) / NT;   // weight pieces per thread per tap
+  constexpr int CW = N16 ? 16 : 32 * TN;    // output channels a workgroup covers
+  constexpr int CPMAX = CW;
+  constexpr int WP = (CW * CPMAX / VEC + NT - 1) / NT;        // weight pieces per thread per tap
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   __shared__ float red[4];
 
@@ -611,7 +629,7 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
   // the halo rows above and below come in the same batch.  Loads are unconditional (pieces outside the
   // image or the tile read element 0 and are zeroed afterwards); the side columns of the patch are the
   // zero padding of the image.
-  constexpr int LPR = TN * 8, RPI = 64 / LPR, NIT = 32 / RPI, NX = TM * NIT;
+  constexpr int LPR = CW / 4, RPI = 64 / LPR, NIT = 32 / RPI, NX = TM * NIT;
   const int npx = min(TH, H - y0) * Wd;      // valid pixels of this tile
   const int lrow = lane / LPR, colq = (lane % LPR) * 4;
   float4 xreg[NX];
@@ -693,7 +711,7 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
 
   // ---- weight slice of one tap: rows = output channel, k = input channel
   const int wq = Cp / VEC;
-  const int wtotal = 32 * TN * wq;
+  const int wtotal = CW * wq;
   // two register sets and two LDS buffers: while tap t is multiplied out of one buffer, tap t+1
   // goes from registers into the other and taps t+2, t+3 are in flight from global memory
   uint4 wreg[2][WP];
@@ -725,22 +743,29 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
   load_w(wreg[0], wmask[0], 0);
   load_w(wreg[1], wmask[1], 1);
 
-  int aoff[TM];
+  // A-operand rows of this lane: 32x32 blocks -> pixel (wave*TM + i)*32 + lane%32;
+  // 16x16 blocks -> pixel wave*64 + 16*b + lane%16 (k group lane/16)
+  constexpr int NA = N16 ? 4 : TM;
+  const int r16 = lane & 15, kq = lane >> 4;
+  int aoff[NA];
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    int p = (wave * TM + i) * 32 + c;
+  for (int i = 0; i < NA; ++i) {
+    int p = N16 ? wave * 64 + 16 * i + r16 : (wave * TM + i) * 32 + c;
     if (p >= npx) p = 0;                      // masked rows compute on pixel 0 and are dropped
     aoff[i] = ((p / Wd) * PW + (p % Wd)) * CS;
   }
 
   floatx16 acc[TM][TN];
+  floatx4 acc16[4];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int j = 0; j < TN; ++j) acc[i][j] = zero16();
+#pragma unroll
+  for (int i = 0; i < 4; ++i) acc16[i] = floatx4{0.f, 0.f, 0.f, 0.f};
 
   const bool wave_active = (wave * TM) * 32 < npx;
-  WT* wbuf[2] = {wts, wts + 32 * TN * CS};
+  WT* wbuf[2] = {wts, wts + CW * CS};
   store_w(wreg[0], wmask[0], wbuf[0]);
   load_w(wreg[0], wmask[0], 2);
   __syncthreads();                            // patch and tap 0 are in LDS
@@ -756,13 +781,27 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
           const int toff = ((tap / 3) * PW + (tap % 3)) * CS;
           const WT* wt = wbuf[sidx];
           for (int ks = 0; ks < Cp; ks += KSTEP) {
-            const WT* ap[TM];
-            const WT* bp[TN];
+            if constexpr (N16) {
+              // lane (r16, kq) feeds k = ks + 4 kq .. + 3, one value per instruction (any fixed pairing of
+              // the lanes' k values is a valid order of the sum)
+              const float4 bf = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(wt) + r16 * CS + ks + 4 * kq);
 #pragma unroll
-            for (int i = 0; i < TM; ++i) ap[i] = patch + aoff[i] + toff + ks;
+              for (int i = 0; i < 4; ++i) {
+                const float4 af = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(patch) + aoff[i] + toff + ks + 4 * kq);
+                acc16[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.x, bf.x, acc16[i], 0, 0, 0);
+                acc16[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.y, bf.y, acc16[i], 0, 0, 0);
+                acc16[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.z, bf.z, acc16[i], 0, 0, 0);
+                acc16[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.w, bf.w, acc16[i], 0, 0, 0);
+              }
+            } else {
+              const WT* ap[TM];
+              const WT* bp[TN];
 #pragma unroll
-            for (int j = 0; j < TN; ++j) bp[j] = wt + (j * 32 + c) * CS + ks;
-            mma_step<TM, TN>(ap, bp, acc, g);
+              for (int i = 0; i < TM; ++i) ap[i] = patch + aoff[i] + toff + ks;
+#pragma unroll
+              for (int j = 0; j < TN; ++j) bp[j] = wt + (j * 32 + c) * CS + ks;
+              mma_step<TM, TN>(ap, bp, acc, g);
+            }
           }
         }
         __syncthreads();                      // tap+1 visible; everyone is done with this buffer
@@ -774,7 +813,20 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
   long long row0[TM];
 #pragma unroll
   for (int i = 0; i < TM; ++i) row0[i] = img_row0 + (wave * TM + i) * 32;
-  epilogue<TM, TN, true, NX>(a, gi, layer, acc, row0, img_row0 + npx, 0, L, red, reinterpret_cast<float*>(smem_raw), xreg);
+  if constexpr (N16) {
+    // 16x16 blocks: register v of a lane holds row 4 (lane / 16) + v, column lane % 16 of the block;
+    // block row tm of the epilogue is the pair of blocks 2 tm, 2 tm + 1
+    auto stage_block = [&](int tm, float* stage) {
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) stage[(16 * b + 4 * kq + v) * (CW + 4) + r16] = acc16[2 * tm + b][v];
+    };
+    epilogue_rows<TM, CW, true, NX>(a, gi, layer, stage_block, row0, img_row0 + npx, 0, L, red,
+                                    reinterpret_cast<float*>(smem_raw), xreg);
+  } else {
+    epilogue<TM, TN, true, NX>(a, gi, layer, acc, row0, img_row0 + npx, 0, L, red, reinterpret_cast<float*>(smem_raw), xreg);
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -784,20 +836,23 @@ int conv_tile_rows(int Himg, int Wimg, int C, int dtype) {
   if (Wimg > 256 || Wimg < 1 || Himg < 1 || C < 1 || C > 64) return 0;
   int thmax = 256 / Wimg;
   if (thmax > Himg) thmax = Himg;
-  const int kstep = dtype == 0 ? 8 : 16, pad = dtype == 0 ? 4 : 8, es = dtype == 0 ? 4 : 2;
+  const bool n16 = dtype == 0 && C <= 16;       // as conv_uses_n16
+  const int kstep = n16 ? 16 : dtype == 0 ? 8 : 16, pad = dtype == 0 ? 4 : 8, es = dtype == 0 ? 4 : 2;
   const int Cp = (C + kstep - 1) / kstep * kstep, CS = Cp + pad;
-  const int tn = C <= 32 ? 1 : 2;
-  while (thmax > 1 && ((size_t)(thmax + 2) * (Wimg + 2) + 2 * 32 * tn) * CS * es > 72 * 1024) --thmax;
+  const int cw = n16 ? 16 : C <= 32 ? 32 : 64;
+  while (thmax > 1 && ((size_t)(thmax + 2) * (Wimg + 2) + 2 * cw) * CS * es > 72 * 1024) --thmax;
   const int ntiles = (Himg + thmax - 1) / thmax;
   return (Himg + ntiles - 1) / ntiles;        // balanced tile height
 }
 
+static bool conv_uses_n16(const StepArgs& a, int dtype) { return dtype == 0 && a.Nf <= 16; }
 static size_t conv_smem_bytes(const StepArgs& a, int dtype) {
-  const int kstep = dtype == 0 ? 8 : 16, pad = dtype == 0 ? 4 : 8, es = dtype == 0 ? 4 : 2;
+  const bool n16 = conv_uses_n16(a, dtype);
+  const int kstep = n16 ? 16 : dtype == 0 ? 8 : 16, pad = dtype == 0 ? 4 : 8, es = dtype == 0 ? 4 : 2;
   const int Cp = (a.Nf + kstep - 1) / kstep * kstep, CS = Cp + pad;
-  const int tn = a.Nf <= 32 ? 1 : 2;
-  const size_t main_loop = ((size_t)(a.TH + 2) * (a.Wimg + 2) + 2 * 32 * tn) * CS * es;   // patch + 2 tap buffers
-  const size_t staging = (size_t)4 * 32 * (tn * 32 + 4) * 4;       // epilogue staging buffer
+  const int cw = n16 ? 16 : a.Nf <= 32 ? 32 : 64;
+  const size_t main_loop = ((size_t)(a.TH + 2) * (a.Wimg + 2) + 2 * cw) * CS * es;   // patch + 2 tap buffers
+  const size_t staging = (size_t)4 * 32 * (cw + 4) * 4;             // epilogue staging buffer
   return main_loop > staging ? main_loop : staging;
 }
 
@@ -838,15 +893,15 @@ static void launch_dense(dim3 grid, hipStream_t s, const StepArgs& a) {
   hipLaunchKernelGGL((dense_step_kernel<WT, BM, BN, 2, 2, BK, PF>), grid, dim3(NT), smem, s, a);
 }
 
-template <typename WT, int TN>
+template <typename WT, int TN, bool N16 = false>
 static void launch_conv(dim3 grid, size_t smem, hipStream_t s, const StepArgs& a) {
   static size_t raised = 64 * 1024;        // opt in to more than 64 KB of dynamic LDS when a shape needs it
   if (smem > raised) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(conv_step_kernel<WT, TN>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(conv_step_kernel<WT, TN, N16>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     raised = smem;
   }
-  hipLaunchKernelGGL((conv_step_kernel<WT, TN>), grid, dim3(NT), smem, s, a);
+  hipLaunchKernelGGL((conv_step_kernel<WT, TN, N16>), grid, dim3(NT), smem, s, a);
 }
 
 hipError_t launch_step(const StepArgs& a_in, int layer_kind, int dtype, int groups, hipStream_t s) {
@@ -859,7 +914,9 @@ hipError_t launch_step(const StepArgs& a_in, int layer_kind, int dtype, int grou
   if (layer_kind == 1) {
     const size_t smem = conv_smem_bytes(a, dtype);
     cls = dtype == 0 ? TRACE_CONV_F32 : TRACE_CONV_BF16;
-    if (a.Nf <= 32) {
+    if (conv_uses_n16(a, dtype)) {
+      launch_conv<float, 1, true>(grid, smem, s, a);
+    } else if (a.Nf <= 32) {
       if (dtype == 0) launch_conv<float, 1>(grid, smem, s, a);
       else            launch_conv<__bf16, 1>(grid, smem, s, a);
     } else {
