@@ -223,7 +223,28 @@ def main():
                 nested["%s_%s" % (tag, iname)] = {"cycles": r["r"][2], "ms": round(t_i, 3),
                                                   "first_rms_residual": r["r"][1][0]}
         del W_s, b_s
-        out["extras"] = {"time_to_rms_1e-6_ms": round(t_tol, 3), "cycles_to_rms_1e-6": res["r"][2],
+        # gradient of the early-stopped solves against the exact one (Sec. IV-A: two cycles suffice for
+        # training): k forward cycles, k adjoint cycles about those states, gradient; the reference is
+        # max_levels = 1, i.e. serial forward and backward propagation through the same kernels
+        grad_err = {}
+        if adjoint:
+            p_ser_a = M.problem_from_workload(wl, max_levels=1)
+            M.mgrit_fas_forward(p_ser_a, W, b, u0, U, ws, want_hist=False)
+            M.mgrit_fas_adjoint(p_ser_a, W, b, U, lamN, Lam, dW, db, ws, want_hist=False)
+            torch.cuda.synchronize()
+            ref_n = float(torch.linalg.vector_norm(dW.double()))
+            dW_ref = dW.clone()
+            t_ser_train = timed(lambda: (M.mgrit_fas_forward(p_ser_a, W, b, u0, U, ws, want_hist=False),
+                                         M.mgrit_fas_adjoint(p_ser_a, W, b, U, lamN, Lam, dW, db, ws, want_hist=False)), 3)
+            for k in (1, 2, 3, 4):
+                p_k = M.problem_from_workload(wl, max_iter=k)
+                M.mgrit_fas_forward(p_k, W, b, u0, U, ws, want_hist=False)
+                M.mgrit_fas_adjoint(p_k, W, b, U, lamN, Lam, dW, db, ws, want_hist=False)
+                torch.cuda.synchronize()
+                grad_err[str(k)] = float(torch.linalg.vector_norm((dW - dW_ref).double())) / ref_n
+            del dW_ref
+            grad_err["serial_forward_backward_gradient_gpu_ms"] = round(t_ser_train, 3)
+        out["extras"] = {"gradient_rel_error_vs_cycles": grad_err, "time_to_rms_1e-6_ms": round(t_tol, 3), "cycles_to_rms_1e-6": res["r"][2],
                          "final_rms_residual": res["r"][1][-1], "start_comparison_to_rms_1e-6": nested,
                          "serial_forward_gpu_ms": round(t_ser, 3),
                          "forward_1_cycle_ms": round(t_one, 3), "forward_%d_cycles_ms" % args.cycles: round(t_two, 3),
