@@ -26,8 +26,9 @@ PEAK = {"fp32_mfma": 157.3, "bf16_mfma": 2500.0,       # TFLOP/s, published dens
 # are in profiles/<workload>_bench_hbm_traffic.md).  None where no counter run was made.
 TRAFFIC_BYTES = {
     ("cfg2", "dense_ksplit_kernel<float>"): 5.16e6 + 0.97e6,
-    ("cfg2", "dense_step_kernel<float,64,64>"): 31.60e6 + 8.39e6,
-    ("cfg4", "conv_step_kernel<bf16>"): 529.72e6 + 241.59e6,
+    ("cfg2", "dense_step_kernel<float,64,64>"): 31.52e6 + 8.39e6,
+    ("cfg4", "conv_step_kernel<bf16>"): 451.76e6 + 260.80e6,
+    ("cfg5", "dense_step_kernel<bf16,128,128>"): 328.61e6 + 72.41e6,
 }
 
 
