@@ -270,7 +270,7 @@ struct Solver {
   void cycle(int l, int iter, bool skip_opening_relax) {
     const int m = p->m;
     if (l == pl.L - 1) {                                        // coarsest level: serial solve
-      if (g[l]) chk(launch_copy_points(X[l], PtMap{0, 0}, g[l], PtMap{0, 0}, pl.E, 1, s));
+      // X[l][0] already holds the known value: the injection copied it together with the other points
       for (int j = 1; j <= pl.Nl[l]; ++j) propagate(l, j, 1, 1);
       return;
     }
@@ -285,15 +285,18 @@ struct Solver {
       if (g[l]) { a.E2 = g[l]; a.e2m = PtMap{m, m}; a.c2 = 1.0f; }
       if (l == 0) a.norm_partial = partial;
       launch(a, Nc);
+      // Alg. 1 step 2: injection of the C-points (the residual of point 0 is identically zero); on the fine
+      // level the same launch also sums the norm partials of the residual launch (Alg. 1 step 6)
       if (l == 0) {
         const int nb = step_grid_blocks(a, p->layer, p->dtype, Nc) * Nc;
         const double scale = p->norm_kind == MGRIT_NORM_RMS ? 1.0 / sqrt((double)(Nc + 1) * (double)pl.E) : 1.0;
-        chk(launch_norm_final(partial, nb, scale, hist_dev + iter, s));
+        chk(launch_copy_points_norm(X[l + 1], PtMap{0, 1}, X[l], pm(l, 0, m), pl.E, Nc + 1, partial, nb, scale,
+                                    hist_dev + iter, s));
+      } else {
+        chk(launch_copy_points(X[l + 1], PtMap{0, 1}, X[l], pm(l, 0, m), pl.E, Nc + 1, s));
       }
     }
-    // Alg. 1 step 2: injection of the C-points; the residual of point 0 is identically zero
-    chk(launch_copy_points(X[l + 1], PtMap{0, 1}, X[l], pm(l, 0, m), pl.E, Nc + 1, s));
-    chk(launch_copy_points(g[l + 1], PtMap{0, 0}, X[l], pm(l, 0, 0), pl.E, 1, s));
+    // g[l+1][0] = U[0] + R[0] is the known value at point 0 in every cycle (R[0] = 0): set once per solve
     {                                                           // Alg. 1 step 3: S_H = L_H(U_H) + R_H
       StepArgs a = base_args(l + 1, 1, 1);
       a.X = X[l + 1]; a.xm = PtMap{0, 1};
@@ -327,6 +330,8 @@ int run_solver(Solver& sv, const float* first, double* resnorm_hist, int32_t* it
   if (pl.L > 1 && p->init == MGRIT_INIT_COPY)
     sv.chk(launch_copy_points(sv.X[0], sv.pm(0, m, m), first, PtMap{0, 0}, pl.E, pl.Nl[1], sv.s));
   sv.chk(launch_copy_points(sv.X[0], sv.pm(0, 0, 0), first, PtMap{0, 0}, pl.E, 1, sv.s));
+  for (int l = 1; l < pl.L; ++l)       // right-hand side of point 0 on the coarse levels: the known value
+    sv.chk(launch_copy_points(sv.g[l], PtMap{0, 0}, first, PtMap{0, 0}, pl.E, 1, sv.s));
   if (pl.L > 1 && p->init == MGRIT_INIT_NESTED) sv.nested_start(first);
 
   int iters = 0;

@@ -84,6 +84,8 @@ hipError_t launch_grad(const GradArgs& a, int layer_kind, int dtype, int groups,
 // out[om(gi)] = in[im(gi)]                      (injection restriction, initial guesses)
 hipError_t launch_copy_points(float* out, PtMap om, const float* in, PtMap im, long long E, int groups,
                               hipStream_t s);
+hipError_t launch_copy_points_norm(float* out, PtMap om, const float* in, PtMap im, long long E, int groups,
+                                   const float* partial, int n, double scale, double* nout, hipStream_t s);
 // out[om(gi)] = 0
 hipError_t launch_zero_points(float* out, PtMap om, long long E, int groups, hipStream_t s);
 // U[um(gi)] += V[vm(gi)] - U[um(gi)]  evaluated as  U + (V - U)      (C-point correction)

@@ -1035,6 +1035,37 @@ __global__ __launch_bounds__(NT) void norm_final_kernel(const float* partial, in
   }
   if (threadIdx.x == 0) out[0] = sqrt(red[0]) * scale;
 }
+// The injection copy of the fine level and the final norm reduction of the same cycle in one launch: block
+// row `groups` (one past the copies) holds the reduction, done by its first workgroup exactly as above.
+__global__ __launch_bounds__(NT) void copy_points_norm_kernel(float* out, PtMap om, const float* in, PtMap im,
+                                                              long long E4, int groups, const float* partial, int n,
+                                                              double scale, double* nout) {
+  __shared__ double red[NT];
+  if ((int)blockIdx.y == groups) {
+    if (blockIdx.x != 0) return;
+    double s = 0.0;
+    for (int i = threadIdx.x; i < n; i += NT) s += (double)partial[i];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int o = NT / 2; o > 0; o >>= 1) {
+      if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+      __syncthreads();
+    }
+    if (threadIdx.x == 0) nout[0] = sqrt(red[0]) * scale;
+    return;
+  }
+  const long long gi = blockIdx.y;
+  const float4* src = reinterpret_cast<const float4*>(in) + (im.base + gi * im.stride) * E4;
+  float4* dst = reinterpret_cast<float4*>(out) + (om.base + gi * om.stride) * E4;
+  for (long long i = (long long)blockIdx.x * NT + threadIdx.x; i < E4; i += (long long)gridDim.x * NT) dst[i] = src[i];
+}
+hipError_t launch_copy_points_norm(float* out, PtMap om, const float* in, PtMap im, long long E, int groups,
+                                   const float* partial, int n, double scale, double* nout, hipStream_t s) {
+  if (groups <= 0) return launch_norm_final(partial, n, scale, nout, s);
+  hipLaunchKernelGGL(copy_points_norm_kernel, xfer_grid(E / 4, groups + 1), dim3(NT), 0, s, out, om, in, im, E / 4,
+                     groups, partial, n, scale, nout);
+  return hipGetLastError();
+}
 hipError_t launch_norm_final(const float* partial, int n, double scale, double* out, hipStream_t s) {
   hipLaunchKernelGGL(norm_final_kernel, dim3(1), dim3(NT), 0, s, partial, n, scale, out);
   return hipGetLastError();
