@@ -168,6 +168,7 @@ struct Solver {
     a.sp = 1.0f; a.hs = pl.hl[l]; a.mode = MODE_PHI; a.act = act;
     a.M = pl.M; a.Nf = pl.Nf; a.K = pl.K; a.Himg = p->Himg; a.Wimg = p->Wimg; a.TH = pl.TH;
     a.E = pl.E; a.wsize = pl.wsize;
+    a.wstream = (double)p->N * (double)pl.wsize * (double)pl.esize > 128.0 * 1024.0 * 1024.0 ? 1 : 0;
     return a;
   }
   void launch(const StepArgs& a, int groups) {

@@ -40,6 +40,8 @@ struct StepArgs {
   int K;                           // contraction length per output: q or 9*C
   int Himg, Wimg, TH;              // conv only: image size and rows of an output tile
   int tiles;                       // workgroups per group (filled in by the launch wrapper)
+  int wstream;                     // 1: all layers' weights together exceed the last-level cache, load them
+                                   // non-temporally; 0: they fit and later launches of the solve find them there
   long long E;                     // M * Nf
   long long wsize;                 // Nf * K elements per layer
 };

@@ -82,13 +82,18 @@ template <> struct Op<__bf16> {
   static constexpr int PAD = 8;
 };
 
-// 16-byte load of data that is used once per launch (layer weights): non-temporal, so that it does
-// not push the states, which the next launch reads again, out of the caches.
+// 16-byte load of layer weights.  STREAM: non-temporal, for parameter sets larger than the 256 MB last-level
+// cache -- a weight is used once per launch and must not push out the states, which the next launch reads
+// again.  Otherwise a plain load: the whole parameter set stays cached across the launches of a solve
+// (measured: 6 % on the q=256 workload with 64 MB of weights, the other way round -0.5 % with 2 GB).
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-template <typename T>
-__device__ __forceinline__ uint4 ld_stream(const T* p) {
-  const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
-  return make_uint4(v.x, v.y, v.z, v.w);
+template <bool STREAM, typename T>
+__device__ __forceinline__ uint4 ld_weights(const T* p) {
+  if (STREAM) {
+    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+  }
+  return *reinterpret_cast<const uint4*>(p);
 }
 __device__ __forceinline__ void cvt_store4(float* dst, float4 v) { *reinterpret_cast<float4*>(dst) = v; }
 __device__ __forceinline__ void cvt_store4(__bf16* dst, float4 v) {
@@ -322,7 +327,7 @@ __device__ __forceinline__ void epilogue(const StepArgs& a, int gi, long long la
 // 4 wavefronts arranged WR x WC, each owning TM x TN blocks of 32x32.  Both operands are
 // staged through LDS in BK-wide slabs with a register prefetch of the next slab.
 // ------------------------------------------------------------------------------------------
-template <typename WT, int BM, int BN, int WR, int WC, int BK, int PF>
+template <typename WT, int BM, int BN, int WR, int WC, int BK, int PF, bool WS>
 __global__ __launch_bounds__(NT) void dense_step_kernel(StepArgs a) {
   constexpr int ST = BK + Op<WT>::PAD, VEC = Op<WT>::VEC, KSTEP = Op<WT>::KSTEP;
   constexpr int TM = BM / WR / 32, TN = BN / WC / 32;
@@ -368,7 +373,7 @@ __global__ __launch_bounds__(NT) void dense_step_kernel(StepArgs a) {
       const bool ok = n0 + row < a.Nf && k0 + kc < K;
       const unsigned off = ok ? (unsigned)((n0 + row) * K + k0 + kc) : 0u;
       bm |= ok ? (1u << i) : 0u;
-      br[i] = ld_stream(Wp + off);
+      br[i] = ld_weights<WS>(Wp + off);
     }
   };
   auto store_slab = [&](const float4 (&ar)[AP], const float4 (&dr)[AP], const uint4 (&br)[BP], unsigned am,
@@ -486,7 +491,7 @@ __device__ __forceinline__ void ks_mma(const float4 (&af)[8], const float4 (&ag)
   }
 }
 
-template <typename WT>
+template <typename WT, bool WS>
 __global__ __launch_bounds__(NT) void dense_ksplit_kernel(StepArgs a) {
   constexpr int KC = KsOp<WT>::KC;
   constexpr bool BF = sizeof(WT) == 2;
@@ -539,7 +544,7 @@ __global__ __launch_bounds__(NT) void dense_ksplit_kernel(StepArgs a) {
         df[j] = *reinterpret_cast<const float4*>(Dp + ao);
         if (BF) dg[j] = *reinterpret_cast<const float4*>(Dp + ao + 4);
       }
-      wf[j] = ld_stream(Wp + wo);
+      wf[j] = ld_weights<WS>(Wp + wo);
     }
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -879,18 +884,28 @@ int step_grid_blocks(const StepArgs& a, int layer_kind, int dtype, int groups) {
   return ((a.M + t - 1) / t) * ((a.Nf + t - 1) / t);
 }
 
-template <typename WT, int BM, int BN, int BK, int PF>
-static void launch_dense(dim3 grid, hipStream_t s, const StepArgs& a) {
+template <typename WT, int BM, int BN, int BK, int PF, bool WS>
+static void launch_dense_ws(dim3 grid, hipStream_t s, const StepArgs& a) {
   constexpr size_t tiles_b = (size_t)(BM + BN) * (BK + Op<WT>::PAD) * sizeof(WT);
   constexpr size_t stage_b = (size_t)4 * 32 * (BN / 2 + 4) * sizeof(float);   // epilogue staging, 2 wavefront columns
   constexpr size_t smem = tiles_b > stage_b ? tiles_b : stage_b;
   static bool raised = false;              // opt in once to more than 64 KB of dynamic LDS
   if (smem > 64 * 1024 && !raised) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(dense_step_kernel<WT, BM, BN, 2, 2, BK, PF>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(dense_step_kernel<WT, BM, BN, 2, 2, BK, PF, WS>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     raised = true;
   }
-  hipLaunchKernelGGL((dense_step_kernel<WT, BM, BN, 2, 2, BK, PF>), grid, dim3(NT), smem, s, a);
+  hipLaunchKernelGGL((dense_step_kernel<WT, BM, BN, 2, 2, BK, PF, WS>), grid, dim3(NT), smem, s, a);
+}
+template <typename WT, int BM, int BN, int BK, int PF>
+static void launch_dense(dim3 grid, hipStream_t s, const StepArgs& a) {
+  if (a.wstream) launch_dense_ws<WT, BM, BN, BK, PF, true>(grid, s, a);
+  else           launch_dense_ws<WT, BM, BN, BK, PF, false>(grid, s, a);
+}
+template <typename WT>
+static void launch_ksplit(dim3 grid, hipStream_t s, const StepArgs& a) {
+  if (a.wstream) hipLaunchKernelGGL((dense_ksplit_kernel<WT, true>), grid, dim3(NT), 0, s, a);
+  else           hipLaunchKernelGGL((dense_ksplit_kernel<WT, false>), grid, dim3(NT), 0, s, a);
 }
 
 template <typename WT, int TN, bool N16 = false>
@@ -927,8 +942,8 @@ hipError_t launch_step(const StepArgs& a_in, int layer_kind, int dtype, int grou
     const int tc = dense_tile_class(a, dtype, groups);
     if (tc == -1) {
       cls = dtype == 0 ? TRACE_DENSE_F32_KS : TRACE_DENSE_BF16_KS;
-      if (dtype == 0) hipLaunchKernelGGL((dense_ksplit_kernel<float>), grid, dim3(NT), 0, s, a);
-      else            hipLaunchKernelGGL((dense_ksplit_kernel<__bf16>), grid, dim3(NT), 0, s, a);
+      if (dtype == 0) launch_ksplit<float>(grid, s, a);
+      else            launch_ksplit<__bf16>(grid, s, a);
     } else if (tc == 1) {
       cls = dtype == 0 ? TRACE_DENSE_F32_128 : TRACE_DENSE_BF16_128;
       if (dtype == 0) launch_dense<float, 128, 128, 32, 2>(grid, s, a);
