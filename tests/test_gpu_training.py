@@ -1,0 +1,100 @@
+"""GPU tests of the path used the way the paper uses it (Sec. IV-A, IV-C): early-stopped forward and
+adjoint solves drive a gradient-descent loop.  The head (softmax cross-entropy on u^N) and the parameter
+update are plain torch on the device; every layer step, adjoint step and parameter gradient runs in the
+library.  Synthetic inputs and labels."""
+import numpy as np
+import pytest
+
+import mgrit_inputs as I
+from oracle import mgrit_oracle as O
+from tests.gpu_util import GpuProblem, rel_l2_per_state
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(f"\n[case] {msg}", flush=True)
+
+
+def test_solve_on_a_side_stream_matches_default_stream():
+    """All work goes to the stream handed over: a solve on a non-default stream, overlapped with unrelated work
+    on the default stream, gives bitwise the same result as on the default stream."""
+    import torch
+    import paper_2007_07336_amd as M
+    wl = I.reduced(I.cfg2(2), name="dense_fp32_side_stream", q=72, B=37, N=64)
+    _say(wl.name)
+    data = I.generate(wl)
+    gp = GpuProblem(wl, data)
+    _, U_ref, hist_ref, _ = gp.forward()
+    side = torch.cuda.Stream()                      # default priority
+    gp.U.zero_()
+    torch.cuda.synchronize()
+    busy = torch.randn(2048, 2048, device="cuda")
+    with torch.cuda.stream(side):
+        rc, hist, it = M.mgrit_fas_forward(gp.p, gp.W, gp.b, gp.u0, gp.U, gp.ws, stream=side)
+    for _ in range(4):
+        busy = busy @ busy * 1e-3                   # default stream stays busy meanwhile
+    side.synchronize()
+    torch.cuda.synchronize()
+    same = bool(np.array_equal(gp.U.cpu().numpy(), U_ref))
+    assert same and hist == hist_ref
+
+
+@pytest.mark.parametrize("layer", ["dense", "conv"])
+def test_gradient_descent_with_early_stopped_multigrid(layer):
+    """Loss goes down under gradient descent with two-cycle multigrid gradients and follows the loss curve of
+    exact (serial) gradients; the first multigrid gradient is checked against the oracle's exact gradient."""
+    import torch
+    import paper_2007_07336_amd as M
+    if layer == "dense":
+        wl = I.reduced(I.cfg5(2), name="train_dense_fp32_q64_B32_N64", q=64, B=32, N=64, m=4, max_levels=3,
+                       min_coarse=1, dtype=I.FP32, head_classes=10)
+    else:
+        wl = I.reduced(I.cfg3(2), name="train_conv_fp32_c8_8x8_B8_N32", B=8, C=8, Himg=8, Wimg=8, N=32, m=4,
+                       max_levels=2, act=I.TANH, lifted_input=False, head_classes=10)
+    _say(wl.name)
+    data = I.generate(wl)
+    dev = "cuda"
+    W_o = torch.from_numpy(data["W_o"]).to(dev)
+    labels = torch.from_numpy(data["labels"]).to(dev)
+
+    def head(uN):                                    # mean cross-entropy of a linear head and d loss / d u^N
+        x = uN.reshape(wl.B, -1).detach().requires_grad_(True)
+        loss = torch.nn.functional.cross_entropy(x @ W_o.T, labels)
+        (g,) = torch.autograd.grad(loss, x)
+        return float(loss.detach()), g.reshape(uN.shape).contiguous()
+
+    def run(levels, steps, lr):
+        gp = GpuProblem(wl, data, max_levels=levels)
+        nb = M.mgrit_adjoint_workspace_bytes(gp.p)
+        ws = torch.empty(nb, dtype=torch.uint8, device=dev)
+        Lam = torch.zeros_like(gp.U)
+        dW = torch.zeros_like(gp.W)
+        db = torch.zeros_like(gp.b)
+        losses, first = [], None
+        for _ in range(steps):
+            M.mgrit_fas_forward(gp.p, gp.W, gp.b, gp.u0, gp.U, ws, want_hist=False)
+            loss, lamN = head(gp.U[-1])
+            M.mgrit_fas_adjoint(gp.p, gp.W, gp.b, gp.U, lamN, Lam, dW, db, ws, want_hist=False)
+            if first is None:
+                first = (dW.cpu().numpy().copy(), db.cpu().numpy().copy(), lamN.cpu().numpy().copy())
+            gp.W -= lr * dW
+            gp.b -= lr * db
+            losses.append(loss)
+        return losses, first
+
+    lr = 20.0 if layer == "dense" else 5.0
+    mg, first_mg = run(wl.max_levels, 15, lr)
+    ser, first_ser = run(1, 15, lr)
+    print("multigrid (2 cycles):", ["%.4f" % v for v in mg], "\nserial:              ", ["%.4f" % v for v in ser], flush=True)
+    assert mg[-1] < 0.9 * mg[0] and ser[-1] < 0.9 * ser[0]
+    assert all(b <= a + 1e-3 for a, b in zip(mg, mg[1:]))
+    assert abs(mg[-1] - ser[-1]) <= 0.1 * (ser[0] - ser[-1])
+    # the serial gradient of the first step against the oracle's exact backpropagation
+    Us = O.serial_forward(data["W"], data["b"], data["u0"], wl.h, wl.layer, wl.act)
+    _, dWo, dbo = O.serial_backward(data["W"], data["b"], Us, first_ser[2], wl.h, wl.layer, wl.act)
+    assert rel_l2_per_state(first_ser[0], dWo) <= 1e-5 and rel_l2_per_state(first_ser[1], dbo) <= 1e-5
+    # and the two-cycle multigrid gradient is close to it (Sec. IV-A: two cycles suffice)
+    eW = float(np.linalg.norm(first_mg[0] - dWo) / np.linalg.norm(dWo))
+    print(f"two-cycle gradient vs exact: {eW:.3e}", flush=True)
+    assert eW <= 1e-2
