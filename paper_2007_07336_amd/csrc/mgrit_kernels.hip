@@ -1159,8 +1159,12 @@ template <typename OT>
 __global__ __launch_bounds__(NT) void dense_grad_kernel(GradArgs a) {
   constexpr int BKR = 32, ST = BKR + Op<OT>::PAD, KSTEP = Op<OT>::KSTEP;
   constexpr int BM = 128, BN = 128, TM = 2, TN = 2;
-  __shared__ __attribute__((aligned(16))) OT As[BM * ST];
-  __shared__ __attribute__((aligned(16))) OT Bs[BN * ST];
+  // operand tiles during the contraction, afterwards the staging buffer of the row-wise output stores
+  constexpr int SW = 64 + 4;                          // staging row stride (floats) of a wavefront's 32 x 64 block row
+  constexpr size_t TILE_B = (size_t)(BM + BN) * ST * sizeof(OT), STAGE_B = (size_t)4 * 32 * SW * sizeof(float);
+  __shared__ __attribute__((aligned(16))) unsigned char lds_raw[TILE_B > STAGE_B ? TILE_B : STAGE_B];
+  OT* As = reinterpret_cast<OT*>(lds_raw);
+  OT* Bs = As + BM * ST;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, c = lane & 31;
   const int q = a.Nf;
   const int tiles_n = (q + BN - 1) / BN;
@@ -1230,17 +1234,26 @@ __global__ __launch_bounds__(NT) void dense_grad_kernel(GradArgs a) {
       mma_step<TM, TN>(ap, bp, acc, g);
     }
   }
+  // output through LDS so that a lane stores a float4 and 16 lanes a whole 256-byte row segment
+  __syncthreads();
+  float* stage = reinterpret_cast<float*>(lds_raw) + wave * 32 * SW;
+  const int lrow = lane >> 4, colq = (lane & 15) * 4;
+  const int col = n0 + wn0 + colq;
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+  for (int i = 0; i < TM; ++i) {
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int cc = n0 + wn0 + j * 32 + c;
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = m0 + wm0 + i * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-        if (row < q && cc < q) dWp[(long long)row * q + cc] = a.hs * acc[i][j][r];
-      }
+      for (int r = 0; r < 16; ++r) stage[(8 * (r >> 2) + 4 * g + (r & 3)) * SW + j * 32 + c] = acc[i][j][r];
+#pragma unroll
+    for (int h = 0; h < 8; ++h) {
+      const int rl = 4 * h + lrow;
+      const int row = m0 + wm0 + i * 32 + rl;
+      float4 z = *reinterpret_cast<const float4*>(&stage[rl * SW + colq]);
+      z.x *= a.hs; z.y *= a.hs; z.z *= a.hs; z.w *= a.hs;
+      if (row < q && col < q) *reinterpret_cast<float4*>(dWp + (long long)row * q + col) = z;
     }
+  }
 }
 // Parameter gradient (3x3 conv): dK[n][o][dy][dx][i] = hs * sum over pixels of G[b,y,x,o] *
 // U[b,y+dy-1,x+dx-1,i] (zero outside the image), G = Dm .* Lam.  One workgroup per (layer, tap):
