@@ -25,10 +25,10 @@ PEAK = {"fp32_mfma": 157.3, "bf16_mfma": 2500.0,       # TFLOP/s, published dens
 # mean over the dispatches of the same bench command; summaries and the calibration of the two factors
 # are in profiles/<workload>_bench_hbm_traffic.md).  None where no counter run was made.
 TRAFFIC_BYTES = {
-    ("cfg2", "dense_ksplit_kernel<float>"): 5.16e6 + 0.97e6,
-    ("cfg2", "dense_step_kernel<float,64,64>"): 31.52e6 + 8.39e6,
-    ("cfg4", "conv_step_kernel<bf16>"): 451.76e6 + 260.80e6,
-    ("cfg5", "dense_step_kernel<bf16,128,128>"): 328.61e6 + 72.41e6,
+    ("cfg2", "dense_ksplit_kernel<float>"): 5.15e6 + 0.97e6,
+    ("cfg2", "dense_step_kernel<float,64,64>"): 32.55e6 + 8.39e6,
+    ("cfg4", "conv_step_kernel<bf16>"): 451.70e6 + 260.80e6,
+    ("cfg5", "dense_step_kernel<bf16,128,128>"): 328.79e6 + 72.41e6,
 }
 
 
