@@ -170,12 +170,13 @@ def main():
                 "hbm_GBps_algorithmic": round(gbps, 1), "hbm_frac": round(gbps / PEAK["hbm_GBps"], 5),
                 "all_kernels_ms": {k: round(v[0] / args.steps, 4) for k, v in tr.items()}}
 
-    out = {"metric": "layer-steps/sec per FAS cycle (forward + adjoint + gradient), 1xMI355X",
+    out = {"metric": "layer-steps/sec per FAS cycle + time-to-1e-6 residual vs serial, 1\u00d7MI355X",
            "value": round(value, 1), "unit": "layer-steps/s", "n_gpus": 1, "steps": args.steps,
            "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None,
            "dtype": "f32" if wl.dtype == I.FP32 else "bf16", "data": "synthetic",
            "config": {"workload": wl.name, "levels": sizes, "m": wl.m, "relax": "FCF" if wl.relax else "F",
+                      "step": "forward solve + adjoint solve of %d V-cycles each + parameter gradient" % args.cycles,
                       "cycles_per_solve": args.cycles, "layer_steps_per_step": steps_per_step,
                       "sample_steps_per_s": round(value * wl.B, 1), "adjoint": adjoint},
            "roofline": roofline}
@@ -245,6 +246,9 @@ def main():
                 grad_err[str(k)] = float(torch.linalg.vector_norm((dW - dW_ref).double())) / ref_n
             del dW_ref
             grad_err["serial_forward_backward_gradient_gpu_ms"] = round(t_ser_train, 3)
+        # the second half of the metric: forward solve to an RMS residual of 1e-6 against serial forward propagation
+        out["time_to_tolerance"] = {"rms_residual": 1e-6, "ms": round(t_tol, 3), "cycles": res["r"][2],
+                                    "serial_forward_gpu_ms": round(t_ser, 3)}
         out["extras"] = {"gradient_rel_error_vs_cycles": grad_err, "time_to_rms_1e-6_ms": round(t_tol, 3), "cycles_to_rms_1e-6": res["r"][2],
                          "final_rms_residual": res["r"][1][-1], "start_comparison_to_rms_1e-6": nested,
                          "serial_forward_gpu_ms": round(t_ser, 3),
