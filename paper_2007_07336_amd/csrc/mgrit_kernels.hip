@@ -869,8 +869,7 @@ static size_t conv_smem_bytes(const StepArgs& a, int dtype) {
 static int dense_tile_class(const StepArgs& a, int dtype, int groups) {
   auto wgs = [&](int t) { return (long long)((a.M + t - 1) / t) * ((a.Nf + t - 1) / t) * groups; };
   if (wgs(128) >= 256) return 1;
-  static const long long ks_limit = getenv("MGRIT_KSPLIT_WGS") ? atoll(getenv("MGRIT_KSPLIT_WGS")) : 256;
-  if (wgs(64) < ks_limit) return -1;
+  if (wgs(64) < 256) return -1;      // fewer 64x64 tiles than CUs (measured: at 256 the tiled kernel already wins)
   return 0;
 }
 static int dense_tile_edge(int cls) { return cls == 1 ? 128 : cls == 0 ? 64 : 32; }
