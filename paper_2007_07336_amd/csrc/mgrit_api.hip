@@ -118,7 +118,7 @@ int make_plan(const mgrit_problem_t* p, Plan* pl) {
   pl->off_hist = off; off = align_up(off + (size_t)(p->max_iter + 1) * 8);
   pl->bytes_fwd = off;
   pl->off_Wt = off; off = align_up(off + (size_t)p->N * pl->wsize * pl->esize);
-  pl->off_D = off; off = align_up(off + (size_t)p->N * pl->E * 4);
+  pl->off_D = off; off = align_up(off + (size_t)p->N * pl->E * pl->esize);   // act' cache, in the weights' type
   pl->off_gpart = off;                 // partial sums of the conv parameter gradient when layers are split
   if (p->layer == MGRIT_LAYER_CONV3X3)
     off = align_up(off + conv_grad_partial_bytes(p->B, p->Himg, p->Wimg, p->C, p->dtype, p->N));
@@ -168,6 +168,7 @@ struct Solver {
     a.sp = 1.0f; a.hs = pl.hl[l]; a.mode = MODE_PHI; a.act = act;
     a.M = pl.M; a.Nf = pl.Nf; a.K = pl.K; a.Himg = p->Himg; a.Wimg = p->Wimg; a.TH = pl.TH;
     a.E = pl.E; a.wsize = pl.wsize;
+    a.dbf16 = p->dtype == MGRIT_BF16 ? 1 : 0;
     a.wstream = (double)p->N * (double)pl.wsize * (double)pl.esize > 128.0 * 1024.0 * 1024.0 ? 1 : 0;
     return a;
   }

@@ -25,7 +25,8 @@ struct PtMap {
 // out^2 over its tile to norm_partial[linear block index].
 struct StepArgs {
   const float* X;   PtMap xm;
-  const float* Dm;  PtMap dm;      // optional elementwise multiplier of the matrix operand
+  const float* Dm;  PtMap dm;      // optional elementwise multiplier of the matrix operand (the act' cache);
+                                   // its storage type is the weights' type: float, or bf16 when dbf16 is set
   const void*  W;   PtMap wm;      // weights of layer wm(gi); element type = template parameter
   const float* bias;               // [layers][Nf] or null (same layer index as W)
   float* Out;       PtMap om;      // may be null when only the norm is wanted
@@ -40,6 +41,7 @@ struct StepArgs {
   int K;                           // contraction length per output: q or 9*C
   int Himg, Wimg, TH;              // conv only: image size and rows of an output tile
   int tiles;                       // workgroups per group (filled in by the launch wrapper)
+  int dbf16;                       // 1: Dm (input) and the output of MODE_DACT are bf16 arrays
   int wstream;                     // 1: all layers' weights together exceed the last-level cache, load them
                                    // non-temporally; 0: they fit and later launches of the solve find them there
   long long E;                     // M * Nf
@@ -54,7 +56,7 @@ enum { ACT_TANH = 0, ACT_RELU = 1, ACT_IDENT = 2 };
 struct GradArgs {
   const float* U;   PtMap um;
   const float* Lam; PtMap lm;
-  const float* Dm;  PtMap dm;
+  const float* Dm;  PtMap dm;        // act' cache in the weights' type (float, or bf16 for a bf16 problem)
   float* dW;                        // [layers][Nf][K] float
   float* db;                        // [layers][Nf] or null
   float hs;

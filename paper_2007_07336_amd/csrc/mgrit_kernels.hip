@@ -95,6 +95,20 @@ __device__ __forceinline__ uint4 ld_weights(const T* p) {
   }
   return *reinterpret_cast<const uint4*>(p);
 }
+// The act' cache of the adjoint sweep (and of the parameter gradient) is stored in the weights' type: float, or
+// bf16 when the matrix-core operands are bf16 anyway (half the bytes of its many reads).  Four consecutive
+// values are loaded raw -- no conversion next to the load, which would make the compiler wait for it -- and
+// widened when they are used.
+__device__ __forceinline__ float4 ld_d4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+__device__ __forceinline__ uint2 ld_d4(const __bf16* p) { return *reinterpret_cast<const uint2*>(p); }
+__device__ __forceinline__ float4 d4_to_f4(float4 r) { return r; }
+__device__ __forceinline__ float4 d4_to_f4(uint2 r) {
+  return make_float4(__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xffff0000u),
+                     __uint_as_float(r.y << 16), __uint_as_float(r.y & 0xffff0000u));
+}
+template <typename T> struct DRaw;
+template <> struct DRaw<float>  { typedef float4 type; };
+template <> struct DRaw<__bf16> { typedef uint2 type; };
 __device__ __forceinline__ void cvt_store4(float* dst, float4 v) { *reinterpret_cast<float4*>(dst) = v; }
 __device__ __forceinline__ void cvt_store4(__bf16* dst, float4 v) {
   bf16x4 o;
@@ -288,7 +302,12 @@ __device__ __forceinline__ void epilogue_rows(const StepArgs& a, int gi, long lo
         const int rl = (h0 + i) * RPI + lrow;
         const long long row = row0[tm] + rl;
         if (colok && row < row_end) {
-          if (e.Op_) *reinterpret_cast<float4*>(e.Op_ + (unsigned)(row * a.Nf + col)) = xv[i];
+          if (dact && a.dbf16) {                     // act' cache of a bf16 problem: 4 x bf16
+            __bf16* ob = reinterpret_cast<__bf16*>(a.Out) + (a.om.base + gi * a.om.stride) * a.E;
+            cvt_store4(ob + (unsigned)(row * a.Nf + col), xv[i]);
+          } else if (e.Op_) {
+            *reinterpret_cast<float4*>(e.Op_ + (unsigned)(row * a.Nf + col)) = xv[i];
+          }
           sq += (xv[i].x * xv[i].x + xv[i].y * xv[i].y) + (xv[i].z * xv[i].z + xv[i].w * xv[i].w);
         }
       }
@@ -346,17 +365,19 @@ __global__ __launch_bounds__(NT) void dense_step_kernel(StepArgs a) {
   const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
   const long long layer = a.wm.base + gi * a.wm.stride;
   const float* Xp = a.X + (a.xm.base + gi * a.xm.stride) * a.E;
-  const float* Dp = a.Dm ? a.Dm + (a.dm.base + gi * a.dm.stride) * a.E : nullptr;
+  const WT* Dp = a.Dm ? reinterpret_cast<const WT*>(a.Dm) + (a.dm.base + gi * a.dm.stride) * a.E : nullptr;
   const WT* Wp = reinterpret_cast<const WT*>(a.W) + layer * a.wsize;
   const int K = a.K;
+  typedef typename DRaw<WT>::type DR;
 
   // PF register sets hold the slabs in flight from global memory.  Loads are unconditional (a
   // predicated load makes the compiler wait for it right away, which serialises the whole slab):
   // out-of-range pieces read element 0 instead and are zeroed when the slab goes to LDS.
-  float4 areg[PF][AP], dreg[PF][AP];
+  float4 areg[PF][AP];
+  DR dreg[PF][AP];
   uint4 breg[PF][BP];
   unsigned amask[PF], bmask[PF];
-  auto load_slab = [&](float4 (&ar)[AP], float4 (&dr)[AP], uint4 (&br)[BP], unsigned& am, unsigned& bm, int k0) {
+  auto load_slab = [&](float4 (&ar)[AP], DR (&dr)[AP], uint4 (&br)[BP], unsigned& am, unsigned& bm, int k0) {
     am = 0; bm = 0;
 #pragma unroll
     for (int i = 0; i < AP; ++i) {
@@ -365,7 +386,7 @@ __global__ __launch_bounds__(NT) void dense_step_kernel(StepArgs a) {
       const unsigned off = ok ? (unsigned)((m0 + row) * K + k0 + kc) : 0u;
       am |= ok ? (1u << i) : 0u;
       ar[i] = *reinterpret_cast<const float4*>(Xp + off);
-      if (Dp) dr[i] = *reinterpret_cast<const float4*>(Dp + off);
+      if (Dp) dr[i] = ld_d4(Dp + off);
     }
 #pragma unroll
     for (int i = 0; i < BP; ++i) {
@@ -376,13 +397,13 @@ __global__ __launch_bounds__(NT) void dense_step_kernel(StepArgs a) {
       br[i] = ld_weights<WS>(Wp + off);
     }
   };
-  auto store_slab = [&](const float4 (&ar)[AP], const float4 (&dr)[AP], const uint4 (&br)[BP], unsigned am,
+  auto store_slab = [&](const float4 (&ar)[AP], const DR (&dr)[AP], const uint4 (&br)[BP], unsigned am,
                         unsigned bm) {
 #pragma unroll
     for (int i = 0; i < AP; ++i) {
       const int p = tid + NT * i, row = p / (BK / 4), kc = (p % (BK / 4)) * 4;
       float4 v = ar[i];
-      if (Dp) { v.x *= dr[i].x; v.y *= dr[i].y; v.z *= dr[i].z; v.w *= dr[i].w; }
+      if (Dp) { const float4 d = d4_to_f4(dr[i]); v.x *= d.x; v.y *= d.y; v.z *= d.z; v.w *= d.w; }
       if (!((am >> i) & 1u)) v = make_float4(0.f, 0.f, 0.f, 0.f);
       cvt_store4(&As[row * ST + kc], v);
     }
@@ -505,9 +526,10 @@ __global__ __launch_bounds__(NT) void dense_ksplit_kernel(StepArgs a) {
   const int m0 = (tile / tiles_n) * 32, n0 = (tile % tiles_n) * 32;
   const long long layer = a.wm.base + gi * a.wm.stride;
   const float* Xp = a.X + (a.xm.base + gi * a.xm.stride) * a.E;
-  const float* Dp = a.Dm ? a.Dm + (a.dm.base + gi * a.dm.stride) * a.E : nullptr;
+  const WT* Dp = a.Dm ? reinterpret_cast<const WT*>(a.Dm) + (a.dm.base + gi * a.dm.stride) * a.E : nullptr;
   const WT* Wp = reinterpret_cast<const WT*>(a.W) + layer * a.wsize;
   const int K = a.K;
+  typedef typename DRaw<WT>::type DR;
   const EpiPtrs e = epi_ptrs(a, gi, layer);
 
   // ---- epilogue operands first (one float4 per thread: row tid/8, columns 4*(tid%8)..+3)
@@ -529,7 +551,8 @@ __global__ __launch_bounds__(NT) void dense_ksplit_kernel(StepArgs a) {
   const unsigned abase = arow_ok ? (unsigned)((m0 + c) * K) : 0u;
   const unsigned wbase = wrow_ok ? (unsigned)((n0 + c) * K) : 0u;
   for (int k0 = wave * KC; k0 < K; k0 += 4 * KC) {
-    float4 af[8], ag[8], df[8], dg[8];
+    float4 af[8], ag[8];
+    DR df[8], dg[8];
     uint4 wf[8];
     unsigned kmask = 0;
 #pragma unroll
@@ -541,16 +564,17 @@ __global__ __launch_bounds__(NT) void dense_ksplit_kernel(StepArgs a) {
       af[j] = *reinterpret_cast<const float4*>(Xp + ao);
       if (BF) ag[j] = *reinterpret_cast<const float4*>(Xp + ao + 4);
       if (Dp) {
-        df[j] = *reinterpret_cast<const float4*>(Dp + ao);
-        if (BF) dg[j] = *reinterpret_cast<const float4*>(Dp + ao + 4);
+        df[j] = ld_d4(Dp + ao);
+        if (BF) dg[j] = ld_d4(Dp + ao + 4);
       }
       wf[j] = ld_weights<WS>(Wp + wo);
     }
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       if (Dp) {
-        af[j].x *= df[j].x; af[j].y *= df[j].y; af[j].z *= df[j].z; af[j].w *= df[j].w;
-        if (BF) { ag[j].x *= dg[j].x; ag[j].y *= dg[j].y; ag[j].z *= dg[j].z; ag[j].w *= dg[j].w; }
+        const float4 d0 = d4_to_f4(df[j]);
+        af[j].x *= d0.x; af[j].y *= d0.y; af[j].z *= d0.z; af[j].w *= d0.w;
+        if (BF) { const float4 d1 = d4_to_f4(dg[j]); ag[j].x *= d1.x; ag[j].y *= d1.y; ag[j].z *= d1.z; ag[j].w *= d1.w; }
       }
       if (!((kmask >> j) & 1u) || !arow_ok) { af[j] = zero; ag[j] = zero; }
       if (!((kmask >> j) & 1u) || !wrow_ok) wf[j] = make_uint4(0, 0, 0, 0);
@@ -581,7 +605,8 @@ __global__ __launch_bounds__(NT) void dense_ksplit_kernel(StepArgs a) {
   }
   float sq = 0.0f;
   if (eok) {
-    if (e.Op_) *reinterpret_cast<float4*>(e.Op_ + eoff) = o;
+    if (dact && a.dbf16) cvt_store4(reinterpret_cast<__bf16*>(a.Out) + (a.om.base + gi * a.om.stride) * a.E + eoff, o);
+    else if (e.Op_) *reinterpret_cast<float4*>(e.Op_ + eoff) = o;
     sq = (o.x * o.x + o.y * o.y) + (o.z * o.z + o.w * o.w);
   }
   if (a.norm_partial) {
@@ -625,8 +650,9 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
   const int bimg = tile / tiles_per_img, y0 = (tile % tiles_per_img) * TH;
   const long long layer = a.wm.base + gi * a.wm.stride;
   const float* Xp = a.X + (a.xm.base + gi * a.xm.stride) * a.E;
-  const float* Dp = a.Dm ? a.Dm + (a.dm.base + gi * a.dm.stride) * a.E : nullptr;
+  const WT* Dp = a.Dm ? reinterpret_cast<const WT*>(a.Dm) + (a.dm.base + gi * a.dm.stride) * a.E : nullptr;
   const WT* Wp = reinterpret_cast<const WT*>(a.W) + layer * a.wsize;
+  typedef typename DRaw<WT>::type DR;
 
   // ---- input patch -> LDS (converted to the operand type).  The tile's own pixels are loaded in the
   // arrangement of the epilogue (lane -> 4 channels of a pixel row, NIT rows per 32-pixel block), so the
@@ -653,7 +679,8 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
     const int htotal = 2 * Wd * cq;
     constexpr int HU = 4;
     for (int p0 = tid; p0 < htotal; p0 += NT * HU) {
-      float4 v[HU], d[HU];
+      float4 v[HU];
+      DR d[HU];
       unsigned hm = 0;
 #pragma unroll
       for (int u = 0; u < HU; ++u) {
@@ -665,7 +692,7 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
         const unsigned off = ok ? (unsigned)((((long long)bimg * H + gy) * Wd + gx) * C + c4) : 0u;
         hm |= ok ? (1u << u) : 0u;
         v[u] = *reinterpret_cast<const float4*>(Xp + off);
-        if (Dp) d[u] = *reinterpret_cast<const float4*>(Dp + off);
+        if (Dp) d[u] = ld_d4(Dp + off);
       }
 #pragma unroll
       for (int u = 0; u < HU; ++u) {
@@ -674,7 +701,7 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
           const int pp = p / cq, c4 = (p % cq) * 4;
           const int prow = pp < Wd ? 0 : TH + 1, gx = pp < Wd ? pp : pp - Wd;
           float4 w = v[u];
-          if (Dp) { w.x *= d[u].x; w.y *= d[u].y; w.z *= d[u].z; w.w *= d[u].w; }
+          if (Dp) { const float4 dd = d4_to_f4(d[u]); w.x *= dd.x; w.y *= dd.y; w.z *= dd.z; w.w *= dd.w; }
           if (!((hm >> u) & 1u)) w = make_float4(0.f, 0.f, 0.f, 0.f);
           cvt_store4(&patch[(prow * PW + gx + 1) * CS + c4], w);
         }
@@ -690,14 +717,14 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
     // the act' factors of the adjoint sweep are fetched one block row at a time to bound the registers
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
-      float4 dreg[NIT];
+      DR dreg[NIT];
       if (Dp) {
 #pragma unroll
         for (int h = 0; h < NIT; ++h) {
           const int p = (wave * TM + tm) * 32 + h * RPI + lrow;
           const bool ok = (okm >> (tm * NIT + h)) & 1u;
           const unsigned off = ok ? (unsigned)((((long long)bimg * H + y0) * Wd + p) * C + colq) : 0u;
-          dreg[h] = *reinterpret_cast<const float4*>(Dp + off);
+          dreg[h] = ld_d4(Dp + off);
         }
       }
 #pragma unroll
@@ -706,7 +733,7 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
         const int p = (wave * TM + tm) * 32 + h * RPI + lrow;
         if (p < TH * Wd && colq < Cp) {
           float4 w = xreg[i];
-          if (Dp) { w.x *= dreg[h].x; w.y *= dreg[h].y; w.z *= dreg[h].z; w.w *= dreg[h].w; }
+          if (Dp) { const float4 dd = d4_to_f4(dreg[h]); w.x *= dd.x; w.y *= dd.y; w.z *= dd.z; w.w *= dd.w; }
           if (!((okm >> i) & 1u)) w = make_float4(0.f, 0.f, 0.f, 0.f);
           cvt_store4(&patch[((p / Wd + 1) * PW + p % Wd + 1) * CS + colq], w);
         }
@@ -1172,12 +1199,14 @@ __global__ __launch_bounds__(NT) void dense_grad_kernel(GradArgs a) {
   const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
   const float* Up = a.U + (a.um.base + gi * a.um.stride) * a.E;
   const float* Lp = a.Lam + (a.lm.base + gi * a.lm.stride) * a.E;
-  const float* Dp = a.Dm + (a.dm.base + gi * a.dm.stride) * a.E;
+  const OT* Dp = reinterpret_cast<const OT*>(a.Dm) + (a.dm.base + gi * a.dm.stride) * a.E;
   float* dWp = a.dW + (long long)gi * a.wsize;
+  typedef typename DRaw<OT>::type DR;
 
   const int rb = tid & 7, cb = tid >> 3;             // 4 batch rows x 4 columns per thread
   const bool aok = m0 + 4 * cb < q, bok = n0 + 4 * cb < q;      // q % 4 == 0: a float4 is in or out as a whole
-  float4 dv[4], lv[4], uv[4];
+  float4 lv[4], uv[4];
+  DR dv[4];
   unsigned rmask = 0;
   auto load_slab = [&](int r0) {
     rmask = 0;
@@ -1188,7 +1217,7 @@ __global__ __launch_bounds__(NT) void dense_grad_kernel(GradArgs a) {
       rmask |= rok ? (1u << rr) : 0u;
       const unsigned offa = (rok && aok) ? (unsigned)(row * q + m0 + 4 * cb) : 0u;
       const unsigned offb = (rok && bok) ? (unsigned)(row * q + n0 + 4 * cb) : 0u;
-      dv[rr] = *reinterpret_cast<const float4*>(Dp + offa);
+      dv[rr] = ld_d4(Dp + offa);
       lv[rr] = *reinterpret_cast<const float4*>(Lp + offa);
       uv[rr] = *reinterpret_cast<const float4*>(Up + offb);
     }
@@ -1199,8 +1228,9 @@ __global__ __launch_bounds__(NT) void dense_grad_kernel(GradArgs a) {
     for (int rr = 0; rr < 4; ++rr) {
       const bool rok = (rmask >> rr) & 1u;
       const float ga = (rok && aok) ? 1.0f : 0.0f, ub = (rok && bok) ? 1.0f : 0.0f;
-      gk[0][rr] = ga * dv[rr].x * lv[rr].x; gk[1][rr] = ga * dv[rr].y * lv[rr].y;
-      gk[2][rr] = ga * dv[rr].z * lv[rr].z; gk[3][rr] = ga * dv[rr].w * lv[rr].w;
+      const float4 dd = d4_to_f4(dv[rr]);
+      gk[0][rr] = ga * dd.x * lv[rr].x; gk[1][rr] = ga * dd.y * lv[rr].y;
+      gk[2][rr] = ga * dd.z * lv[rr].z; gk[3][rr] = ga * dd.w * lv[rr].w;
       uk[0][rr] = ub * uv[rr].x; uk[1][rr] = ub * uv[rr].y; uk[2][rr] = ub * uv[rr].z; uk[3][rr] = ub * uv[rr].w;
     }
 #pragma unroll
@@ -1271,12 +1301,14 @@ __global__ __launch_bounds__(NT) void conv_grad_tap_kernel(GradArgs a) {
   const int dy = tap / 3 - 1, dx = tap % 3 - 1;
   const float* Up = a.U + (a.um.base + gi * a.um.stride) * a.E;
   const float* Lp = a.Lam + (a.lm.base + gi * a.lm.stride) * a.E;
-  const float* Dp = a.Dm + (a.dm.base + gi * a.dm.stride) * a.E;
+  const OT* Dp = reinterpret_cast<const OT*>(a.Dm) + (a.dm.base + gi * a.dm.stride) * a.E;
   float* dKp = a.dW + (long long)gi * a.wsize;
+  typedef typename DRaw<OT>::type DR;
 
   const int rb = tid & 7, cb = (tid >> 3) & 15;      // 4 pixels x 4 channels per thread; threads 128.. idle
   const bool cok = tid < 128 && 4 * cb < C;
-  float4 dv[4], lv[4], uv[4];
+  float4 lv[4], uv[4];
+  DR dv[4];
   unsigned gmask = 0, umask = 0;
   auto load_slab = [&](int r0) {
     gmask = 0; umask = 0;
@@ -1290,7 +1322,7 @@ __global__ __launch_bounds__(NT) void conv_grad_tap_kernel(GradArgs a) {
       umask |= sok ? (1u << rr) : 0u;
       const unsigned og = pok ? (unsigned)(px * C + 4 * cb) : 0u;
       const unsigned ou = sok ? (unsigned)((px + dy * Wd + dx) * C + 4 * cb) : 0u;
-      dv[rr] = *reinterpret_cast<const float4*>(Dp + og);
+      dv[rr] = ld_d4(Dp + og);
       lv[rr] = *reinterpret_cast<const float4*>(Lp + og);
       uv[rr] = *reinterpret_cast<const float4*>(Up + ou);
     }
@@ -1301,8 +1333,9 @@ __global__ __launch_bounds__(NT) void conv_grad_tap_kernel(GradArgs a) {
 #pragma unroll
     for (int rr = 0; rr < 4; ++rr) {
       const float ga = ((gmask >> rr) & 1u) ? 1.0f : 0.0f, ub = ((umask >> rr) & 1u) ? 1.0f : 0.0f;
-      gk[0][rr] = ga * dv[rr].x * lv[rr].x; gk[1][rr] = ga * dv[rr].y * lv[rr].y;
-      gk[2][rr] = ga * dv[rr].z * lv[rr].z; gk[3][rr] = ga * dv[rr].w * lv[rr].w;
+      const float4 dd = d4_to_f4(dv[rr]);
+      gk[0][rr] = ga * dd.x * lv[rr].x; gk[1][rr] = ga * dd.y * lv[rr].y;
+      gk[2][rr] = ga * dd.z * lv[rr].z; gk[3][rr] = ga * dd.w * lv[rr].w;
       uk[0][rr] = ub * uv[rr].x; uk[1][rr] = ub * uv[rr].y; uk[2][rr] = ub * uv[rr].z; uk[3][rr] = ub * uv[rr].w;
     }
 #pragma unroll
@@ -1361,7 +1394,8 @@ __global__ __launch_bounds__(NT) void conv_grad_kernel(GradArgs a) {
   const int gi = L / a.gchunks, ch = L % a.gchunks;
   const float* Up = a.U + (a.um.base + gi * a.um.stride) * a.E;
   const float* Lp = a.Lam + (a.lm.base + gi * a.lm.stride) * a.E;
-  const float* Dp = a.Dm + (a.dm.base + gi * a.dm.stride) * a.E;
+  const OT* Dp = reinterpret_cast<const OT*>(a.Dm) + (a.dm.base + gi * a.dm.stride) * a.E;
+  typedef typename DRaw<OT>::type DR;
 
   {
     const int n16 = (int)(((size_t)3 * C * PU + (size_t)C * PG) * sizeof(OT) / 16);
@@ -1384,7 +1418,8 @@ __global__ __launch_bounds__(NT) void conv_grad_kernel(GradArgs a) {
     const int ub = uact[t] ? blk : 0;
     u_cg[t] = ub % CG; u_xg[t] = (ub / CG) % XG; u_r[t] = ub / (CG * XG);
   }
-  float4 dv[4], lv[4], uv[3][4];
+  float4 lv[4], uv[3][4];
+  DR dv[4];
   unsigned gmask = 0, umask[3] = {0, 0, 0};
   auto load_slab = [&](int sl) {
     const int b = sl / a.gspi, y0 = (sl % a.gspi) * R;
@@ -1398,7 +1433,7 @@ __global__ __launch_bounds__(NT) void conv_grad_kernel(GradArgs a) {
         const bool ok = rok && x < Wd;
         gmask |= ok ? (1u << j) : 0u;
         const unsigned off = ok ? (unsigned)((((long long)b * H + y) * Wd + x) * C + 4 * g_cg) : 0u;
-        dv[j] = *reinterpret_cast<const float4*>(Dp + off);
+        dv[j] = ld_d4(Dp + off);
         lv[j] = *reinterpret_cast<const float4*>(Lp + off);
       }
     }
@@ -1424,8 +1459,9 @@ __global__ __launch_bounds__(NT) void conv_grad_kernel(GradArgs a) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const bool ok = (gmask >> j) & 1u;
-        gk[0][j] = ok ? dv[j].x * lv[j].x : 0.0f; gk[1][j] = ok ? dv[j].y * lv[j].y : 0.0f;
-        gk[2][j] = ok ? dv[j].z * lv[j].z : 0.0f; gk[3][j] = ok ? dv[j].w * lv[j].w : 0.0f;
+        const float4 dd = d4_to_f4(dv[j]);
+        gk[0][j] = ok ? dd.x * lv[j].x : 0.0f; gk[1][j] = ok ? dd.y * lv[j].y : 0.0f;
+        gk[2][j] = ok ? dd.z * lv[j].z : 0.0f; gk[3][j] = ok ? dd.w * lv[j].w : 0.0f;
       }
 #pragma unroll
       for (int cc = 0; cc < 4; ++cc)
@@ -1538,18 +1574,19 @@ __global__ __launch_bounds__(NT) void conv_grad_reduce_kernel(const float* parti
 
 // db[n][o] = hs * sum over rows of Dm .* Lam (fixed order).  64 columns per workgroup: 16 lanes of
 // float4 across, 16 row lanes down, then a fixed-order LDS reduction over the row lanes.
+template <typename OT>
 __global__ __launch_bounds__(NT) void bias_grad_kernel(GradArgs a) {
   __shared__ float4 part[16][17];
   const int gi = blockIdx.y;
   const float* Lp = a.Lam + (a.lm.base + gi * a.lm.stride) * a.E;
-  const float* Dp = a.Dm + (a.dm.base + gi * a.dm.stride) * a.E;
+  const OT* Dp = reinterpret_cast<const OT*>(a.Dm) + (a.dm.base + gi * a.dm.stride) * a.E;
   const int cx = threadIdx.x & 15, ry = threadIdx.x >> 4;
   const int col = blockIdx.x * 64 + 4 * cx;
   float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
   if (col < a.Nf) {
     for (int r = ry; r < a.M; r += 16) {
       const unsigned off = (unsigned)(r * a.Nf + col);
-      const float4 d = *reinterpret_cast<const float4*>(Dp + off), l = *reinterpret_cast<const float4*>(Lp + off);
+      const float4 d = d4_to_f4(ld_d4(Dp + off)), l = *reinterpret_cast<const float4*>(Lp + off);
       s.x += d.x * l.x; s.y += d.y * l.y; s.z += d.z * l.z; s.w += d.w * l.w;
     }
   }
@@ -1592,6 +1629,11 @@ size_t conv_grad_partial_bytes(int B, int Himg, int Wimg, int C, int dtype, int 
   if (!gm.ok || gm.chunks <= 1) return 0;
   return (size_t)gm.chunks * layers * (9 * C * C + C) * sizeof(float);
 }
+static void launch_bias_grad(const GradArgs& a, int dtype, int groups, hipStream_t s) {
+  const dim3 grid((a.Nf + 63) / 64, groups);
+  if (dtype == 0) hipLaunchKernelGGL((bias_grad_kernel<float>), grid, dim3(NT), 0, s, a);
+  else            hipLaunchKernelGGL((bias_grad_kernel<__bf16>), grid, dim3(NT), 0, s, a);
+}
 template <typename OT, int TM, int TN>
 static hipError_t launch_conv_grad(const GradArgs& a, unsigned blocks, size_t smem, hipStream_t s) {
   if (smem > 64 * 1024) {
@@ -1623,7 +1665,7 @@ hipError_t launch_grad(const GradArgs& a_in, int layer_kind, int dtype, int grou
         if (dtype == 0) hipLaunchKernelGGL((conv_grad_tap_kernel<float>), grid, dim3(NT), 0, s, a);
         else            hipLaunchKernelGGL((conv_grad_tap_kernel<__bf16>), grid, dim3(NT), 0, s, a);
       }
-      if (a.db) hipLaunchKernelGGL(bias_grad_kernel, dim3((a.Nf + 63) / 64, groups), dim3(NT), 0, s, a);
+      if (a.db) launch_bias_grad(a, dtype, groups, s);
     } else {                                               // all taps and the bias gradient in one kernel
       a.layers = groups;
       a.gWp = gm.Wp; a.gR = gm.R; a.gKL = gm.KL; a.gPU = gm.PU; a.gPG = gm.PG;
@@ -1649,7 +1691,7 @@ hipError_t launch_grad(const GradArgs& a_in, int layer_kind, int dtype, int grou
       }
     }
   }
-  if (a.db && layer_kind == 0) hipLaunchKernelGGL(bias_grad_kernel, dim3((a.Nf + 63) / 64, groups), dim3(NT), 0, s, a);
+  if (a.db && layer_kind == 0) launch_bias_grad(a, dtype, groups, s);
   const hipError_t e = hipGetLastError();
   trace_after(s, TRACE_GRAD, groups);
   return e;
