@@ -28,7 +28,7 @@ TRAFFIC_BYTES = {
     ("cfg2", "dense_ksplit_kernel<float>"): 5.15e6 + 0.97e6,
     ("cfg2", "dense_step_kernel<float,64,64>"): 32.55e6 + 8.39e6,
     ("cfg4", "conv_step_kernel<bf16>"): 451.70e6 + 260.80e6,
-    ("cfg5", "dense_step_kernel<bf16,128,128>"): 328.79e6 + 72.41e6,
+    ("cfg5", "dense_step_kernel<bf16,128,128>"): 306.79e6 + 69.58e6,
 }
 
 
