@@ -62,7 +62,7 @@ enum { MGRIT_INIT_ZERO = 0, MGRIT_INIT_COPY = 1, MGRIT_INIT_USER = 2, MGRIT_INIT
 enum { MGRIT_MAX_LEVELS = 16 };
 
 typedef struct mgrit_problem {
-  int32_t N;           /* layer steps, >= 1                                   (Sec. II, Eq. (1)) */
+  int32_t N;           /* layer steps, >= 1 (at most 65535 in this build)     (Sec. II, Eq. (1)) */
   float   h;           /* fine step size                                      (Sec. II, Eq. (1)) */
   int32_t m;           /* coarsening factor, >= 2                             (Sec. III-C)       */
   int32_t max_levels;  /* 1 = serial propagation, 2 = two-level scheme of Alg. 1,

@@ -58,6 +58,7 @@ int make_plan(const mgrit_problem_t* p, Plan* pl) {
   int rc = build_levels(p, &pl->L, pl->Nl);
   if (rc != MGRIT_OK) return rc;
   if (!(p->h > 0.0f) || !isfinite(p->h)) return MGRIT_ERR_PROBLEM;
+  if (p->N > 65535) return MGRIT_ERR_UNSUPPORTED;            // layers / points index one grid dimension of the transfer kernels
   if (p->relax != MGRIT_RELAX_F && p->relax != MGRIT_RELAX_FCF) return MGRIT_ERR_PROBLEM;
   if (p->cycle != 0 || p->max_iter < 1) return MGRIT_ERR_PROBLEM;
   if (p->norm_kind != MGRIT_NORM_L2 && p->norm_kind != MGRIT_NORM_RMS) return MGRIT_ERR_PROBLEM;

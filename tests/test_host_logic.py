@@ -98,7 +98,7 @@ def test_forward_argument_validation():
                 dict(max_iter=0), dict(norm_kind=2), dict(layer=2), dict(act=5), dict(dtype=3), dict(init=4), dict(init=-1),
                 dict(h=0.0), dict(B=0), dict(q=0), dict(N=18, m=4), dict(N=24, m=4, max_levels=3)):
         assert _fwd(_problem(**bad)) == Bd.MGRIT_ERR_PROBLEM, bad
-    for uns in (dict(q=12), dict(layer=1, C=12, Himg=4, Wimg=4), dict(layer=1, C=128, Himg=4, Wimg=4),
+    for uns in (dict(q=12), dict(N=65536, m=2, max_levels=2), dict(layer=1, C=12, Himg=4, Wimg=4), dict(layer=1, C=128, Himg=4, Wimg=4),
                 dict(layer=1, C=16, Himg=4, Wimg=300)):
         assert _fwd(_problem(**uns)) == Bd.MGRIT_ERR_UNSUPPORTED, uns
     assert _fwd(_problem(layer=1, C=0, Himg=4, Wimg=4)) == Bd.MGRIT_ERR_PROBLEM
