@@ -106,6 +106,7 @@ int make_plan(const mgrit_problem_t* p, Plan* pl) {
   memset(&a, 0, sizeof(a));
   a.M = pl->M; a.Nf = pl->Nf; a.K = pl->K; a.Himg = p->Himg; a.Wimg = p->Wimg; a.TH = pl->TH;
   size_t np = (size_t)step_grid_blocks(a, p->layer, p->dtype, p->N) * p->N + diff_sq_blocks(pl->E);
+  if (np > 0x7fffffffu) return MGRIT_ERR_UNSUPPORTED;       // the largest launch (all N layers) must fit a 1-D grid
   if (pl->L > 1) {
     size_t np1 = (size_t)step_grid_blocks(a, p->layer, p->dtype, pl->Nl[1]) * pl->Nl[1];
     if (np1 > np) np = np1;
