@@ -47,6 +47,29 @@ def test_cfg1_two_level_f_relax_reproduces_serial():
     assert e <= 1e-5, e                             # N/m = 4 cycles of F-relaxation are exact
 
 
+def test_cfg1_against_the_stored_reference():
+    """The stored oracle output of the smallest workload (tests/golden/cfg1_oracle.json): forward solve, adjoint
+    solve about the stored states, parameter gradient."""
+    import json
+    import os
+    wl = I.cfg1()
+    _announce(wl.name + " vs stored reference")
+    with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "cfg1_oracle.json")) as f:
+        ref = json.load(f)
+    data = I.generate(wl)
+    gp = GpuProblem(wl, data)
+    rc, U, hist, it = gp.forward()
+    assert it == ref["cycles"]
+    assert rel_l2_per_state(U, np.asarray(ref["U"])) <= 1e-5
+    for a, b in zip(hist, ref["residual_history"]):
+        assert abs(a - b) <= 1e-3 * b
+    lamN = np.random.default_rng(1).standard_normal(wl.state_shape).astype(np.float32)
+    Lam, dW, db, hist_a, _ = gp.adjoint(np.asarray(ref["U"], dtype=np.float32), lamN)
+    assert rel_l2_per_state(Lam, np.asarray(ref["Lam"])) <= 1e-5
+    assert rel_l2_per_state(dW, np.asarray(ref["dW"])) <= 1e-5
+    assert rel_l2_per_state(db, np.asarray(ref["db"])) <= 1e-5
+
+
 # ------------------------------------------------------------------ dense, reduced sizes
 DENSE_CASES = [
     # ragged in batch and width (several tiles + a tail), 3 levels, FCF

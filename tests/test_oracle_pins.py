@@ -587,3 +587,29 @@ def test_nested_start_adjoint_two_level_brute_force():
         G = (1.0 - np.tanh(z) ** 2) * lam
         lam = lam + (m * h) * (G @ W[n])
         assert np.abs(Lam[n] - lam).max() < 1e-14
+
+
+# ---------------------------------------------------------------------------------------
+# Stored reference of the smallest benchmark workload (written by tests/golden/make_cfg1_oracle.py)
+# ---------------------------------------------------------------------------------------
+def test_stored_cfg1_reference_is_what_the_oracle_computes_today():
+    import importlib.util
+    import json
+    import os
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    spec = importlib.util.spec_from_file_location("make_cfg1_oracle", os.path.join(here, "make_cfg1_oracle.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    now = mod.compute()
+    with open(os.path.join(here, "cfg1_oracle.json")) as f:
+        stored = json.load(f)
+    assert stored["cycles"] == now["cycles"] == 4
+    for key in ("U", "Lam", "dW", "db", "residual_history", "adjoint_residual_history"):
+        a, b = np.asarray(stored[key]), np.asarray(now[key])
+        assert a.shape == b.shape and np.abs(a - b).max() <= 1e-13 * max(1.0, np.abs(b).max()), key
+    # and the stored iterate is the exact solution: N/m = 4 cycles of two-level F-relaxation
+    import mgrit_inputs as I
+    wl = I.cfg1()
+    d = I.generate(wl)
+    Us = O.serial_forward(d["W"], d["b"], d["u0"], wl.h, wl.layer, wl.act)
+    assert np.abs(np.asarray(stored["U"]) - Us).max() < 1e-12
