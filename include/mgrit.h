@@ -15,7 +15,9 @@
  * the end of this file aside).  All device work is enqueued
  * on `hip_stream` (a hipStream_t passed as void*; NULL = the default stream).  A call that
  * writes a host output (resnorm_hist, iters_done, norm_out) synchronises that stream before
- * it returns; otherwise it returns with its work in flight on the stream.
+ * it returns; otherwise it returns with its work in flight on the stream.  Such a call (tol <= 0,
+ * no host outputs) consists of kernel launches only, so it may be recorded into a HIP graph by
+ * stream capture and replayed.
  *
  * Layouts (all row-major, last index fastest):
  *   dense: state [B][q] float;  W [N][q_out][q_in];  b [N][q] float

@@ -41,6 +41,49 @@ def test_solve_on_a_side_stream_matches_default_stream():
 
 
 @pytest.mark.parametrize("layer", ["dense", "conv"])
+def test_solves_recorded_into_a_hip_graph_replay_bitwise(layer):
+    """A forward + adjoint pair without host outputs is kernel launches only: captured into a HIP graph it
+    replays, several times and with eager work and synchronisations in between, to bitwise the eager result."""
+    import torch
+    import paper_2007_07336_amd as M
+    if layer == "dense":
+        wl = I.reduced(I.cfg2(2), name="dense_fp32_graph", q=136, B=70, N=64)
+    else:
+        wl = I.reduced(I.cfg3(2), name="conv_fp32_graph", C=16, Himg=12, Wimg=12, B=5, N=32)
+    _say(wl.name)
+    data = I.generate(wl)
+    gp = GpuProblem(wl, data)
+    lamN = torch.from_numpy(np.random.default_rng(3).standard_normal(wl.state_shape).astype(np.float32)).cuda()
+    Lam = torch.zeros_like(gp.U)
+    dW = torch.zeros(gp.W.shape, dtype=torch.float32, device="cuda")
+    db = torch.zeros_like(gp.b)
+    ws = torch.empty(M.mgrit_adjoint_workspace_bytes(gp.p), dtype=torch.uint8, device="cuda")
+
+    def pair():
+        M.mgrit_fas_forward(gp.p, gp.W, gp.b, gp.u0, gp.U, ws, want_hist=False)
+        M.mgrit_fas_adjoint(gp.p, gp.W, gp.b, gp.U, lamN, Lam, dW, db, ws, want_hist=False)
+
+    pair()
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in (gp.U, Lam, dW, db)]
+    side = torch.cuda.Stream()                      # default priority
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            pair()
+    torch.cuda.synchronize()
+    for replay in range(3):
+        for t in (gp.U, Lam, dW, db):
+            t.fill_(float(replay + 1))              # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for t, r in zip((gp.U, Lam, dW, db), ref):
+            assert torch.equal(t, r), replay
+
+
+@pytest.mark.parametrize("layer", ["dense", "conv"])
 def test_gradient_descent_with_early_stopped_multigrid(layer):
     """Loss goes down under gradient descent with two-cycle multigrid gradients and follows the loss curve of
     exact (serial) gradients; the first multigrid gradient is checked against the oracle's exact gradient."""
