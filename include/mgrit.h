@@ -145,6 +145,42 @@ int32_t mgrit_residual_norm(const mgrit_problem_t* p, const void* W, const float
                             const float* U, double* norm_out,
                             void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* ---- Stacks that mix convolution layers with periodic fully connected layers (Sec. IV-E: blocks of one
+ * fully connected layer with equal input and output size followed by a run of residual convolution layers).
+ * The problem is a MGRIT_LAYER_CONV3X3 problem; in addition every fc_period-th layer, n = 0, fc_period,
+ * 2 fc_period, ... < N, is a fully connected layer acting on the flattened sample,
+ *   u^{n+1}[b] = u^n[b] + h act(Wfc_k vec(u^n[b]) + bfc_k),   k = n / fc_period,
+ * vec = the sample's [Himg][Wimg][C] values in storage order, d = Himg*Wimg*C of them.  The paper does not say
+ * whether its fully connected layers carry the skip connection; here they do, so that every layer has the form of
+ * Eq. (1).  Coarse levels inject layers as before (a coarse step uses the kind and parameters of its first fine
+ * layer).  The slots of W, b (and dW, db) at the fully connected layers' indices keep the [N] layout: their
+ * input values are ignored, and dW, db are written as zero there.
+ *   fc_period  >= 2;  n_fc = ceil(N / fc_period)
+ *   Wfc   device [n_fc][d][d] ([out][in], element type as W)   bfc   device [n_fc][d] float
+ *   dWfc  device float [n_fc][d][d], dbfc device [n_fc][d]: adjoint only, overwritten; computed when dW / db are
+ *         (dWfc with dW, dbfc with db) and then required
+ * MGRIT_ERR_UNSUPPORTED if d*d exceeds 2^31 - 1.  Everything else is as in the plain entry points. */
+typedef struct mgrit_fc_layers {
+  int32_t     fc_period;
+  const void* Wfc;
+  const float* bfc;
+  float*      dWfc;
+  float*      dbfc;
+} mgrit_fc_layers_t;
+
+size_t  mgrit_workspace_bytes_mixed(const mgrit_problem_t* p, int32_t fc_period);
+size_t  mgrit_adjoint_workspace_bytes_mixed(const mgrit_problem_t* p, int32_t fc_period);
+int32_t mgrit_fas_forward_mixed(const mgrit_problem_t* p, const mgrit_fc_layers_t* fc, const void* W, const float* b,
+                                const float* u0, float* U, double* resnorm_hist, int32_t* iters_done,
+                                void* workspace, size_t workspace_bytes, void* hip_stream);
+int32_t mgrit_fas_adjoint_mixed(const mgrit_problem_t* p, const mgrit_fc_layers_t* fc, const void* W, const float* b,
+                                const float* U, const float* lamN, float* Lam, float* dW, float* db,
+                                double* resnorm_hist, int32_t* iters_done,
+                                void* workspace, size_t workspace_bytes, void* hip_stream);
+int32_t mgrit_residual_norm_mixed(const mgrit_problem_t* p, const mgrit_fc_layers_t* fc, const void* W,
+                                  const float* b, const float* u0, const float* U, double* norm_out,
+                                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Diagnostic launch tracing, off by default and the one piece of state the library keeps: between
  * mgrit_trace_begin() and mgrit_trace_end() every layer-step and gradient launch is bracketed by a
  * pair of HIP events on its stream.  mgrit_trace_end synchronises on the last event and returns,

@@ -15,6 +15,9 @@ are exactly representable in bf16):
           u0 either ~N(0,1) directly or a one-channel image y ~ U[0,1] lifted to C
           channels by a fixed random 3x3 kernel K_in ~ N(0, 2/9) (the lifting is a
           plain data-preparation step done here with explicit shifts).
+  mixed:  a conv workload with fc_period = P > 0: layers 0, P, 2P, ... are fully connected on the
+          flattened sample (d = Himg Wimg C); Wfc[k] ~ N(0, 1/d), bfc[k] ~ N(0, bias_var), drawn after
+          everything else, so the other arrays are those of the same workload without them.
 """
 from __future__ import annotations
 
@@ -23,7 +26,7 @@ from typing import Optional
 
 import numpy as np
 
-DENSE, CONV = 0, 1
+DENSE, CONV, FC = 0, 1, 2           # FC: a fully connected layer inside a conv stack (mixed workloads)
 TANH, RELU = 0, 1
 FP32, BF16 = 0, 1
 RELAX_F, RELAX_FCF = 0, 1
@@ -54,6 +57,7 @@ class Workload:
     seed: int = 0
     tol: float = 0.0
     norm_kind: int = 0
+    fc_period: int = 0          # conv only, > 0: every fc_period-th layer is fully connected on the flattened sample
     smooth_depth: bool = False  # True: parameters vary smoothly with depth (a quarter turn between two
                                 # random draws) instead of being independent from layer to layer
 
@@ -70,6 +74,14 @@ class Workload:
     @property
     def E(self) -> int:
         return int(np.prod(self.state_shape))
+
+    @property
+    def n_fc(self) -> int:
+        return (self.N + self.fc_period - 1) // self.fc_period if self.fc_period else 0
+
+    @property
+    def d_fc(self) -> int:
+        return self.Himg * self.Wimg * self.C
 
 
 def round_to_bf16(x: np.ndarray) -> np.ndarray:
@@ -129,7 +141,26 @@ def generate(wl: Workload) -> dict:
     if wl.head_classes > 0:
         out["W_o"] = (rng.standard_normal((wl.head_classes, feat)) * np.sqrt(1.0 / feat)).astype(np.float32)
         out["labels"] = rng.integers(0, wl.head_classes, size=(wl.B,))
+    if wl.fc_period > 0:
+        d = wl.d_fc
+        Wfc = (rng.standard_normal((wl.n_fc, d, d)) * np.sqrt(1.0 / d)).astype(np.float32)
+        out["Wfc"] = round_to_bf16(Wfc) if wl.dtype == BF16 else Wfc
+        bfc = rng.standard_normal((wl.n_fc, d)) * np.sqrt(wl.bias_var) if wl.bias_var > 0 else np.zeros((wl.n_fc, d))
+        out["bfc"] = bfc.astype(np.float32)
     return out
+
+
+def per_layer_lists(wl: Workload, data: dict):
+    """A mixed workload as per-layer sequences (W_n, b_n, kind_n), n = 0..N-1: the fully connected layers'
+    arrays at n = 0, P, 2P, ..., the convolution layers' arrays elsewhere (pure re-arrangement)."""
+    P = wl.fc_period
+    Ws, bs, kinds = [], [], []
+    for n in range(wl.N):
+        if P and n % P == 0:
+            Ws.append(data["Wfc"][n // P]); bs.append(data["bfc"][n // P]); kinds.append(FC)
+        else:
+            Ws.append(data["W"][n]); bs.append(data["b"][n]); kinds.append(CONV)
+    return Ws, bs, kinds
 
 
 def terminal_adjoint(wl: Workload, data: dict, uN: np.ndarray) -> np.ndarray:
@@ -175,6 +206,13 @@ def cfg5(max_iter: int = 2) -> Workload:
     return Workload("cfg5_dense_q1024_N1024_train", DENSE, TANH, BF16, N=1024, m=16, max_levels=8,
                     min_coarse=8, relax=RELAX_FCF, max_iter=max_iter, B=256, q=1024,
                     head_classes=10)
+
+
+def mixed(max_iter: int = 2) -> Workload:
+    """Blocks of one fully connected layer followed by 63 convolution layers (the shape of the paper's second
+    training network, Sec. IV-E, at a size one GPU's oracle check can follow)."""
+    return Workload("mixed_conv_c16_16x16_fc64_N256", CONV, RELU, FP32, N=256, m=4, max_levels=3,
+                    relax=RELAX_FCF, max_iter=max_iter, B=32, C=16, Himg=16, Wimg=16, fc_period=64)
 
 
 def reduced(wl: Workload, **kw) -> Workload:

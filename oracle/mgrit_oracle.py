@@ -22,6 +22,9 @@ What is computed, and where the paper defines it
   derivative of Eq. (1), solved by the same cycle on the reversed layer axis.
 * the nested-iteration start (init = 3): the paper prints no start-up procedure; the coarsest
   level's equation is solved first and handed up level by level                [Sec. III-A background]
+* stacks that mix layer kinds (blocks of one fully connected layer followed by convolution
+  layers): `layer` may be a sequence with one kind per layer, W and b then are sequences of
+  per-layer arrays; the fully connected kind FC acts on the flattened sample   [Sec. IV-E]
 
 Index convention: N layer steps, N+1 states u^0..u^N, parameters theta^0..theta^{N-1}.
 Level l has N_l = N / c^l steps and step size h_l = c^l h; level-l point j is fine layer
@@ -33,7 +36,8 @@ serial solution, linear-F closed forms and the dense two-grid operator, brute-fo
 equation check, layer steps against an independent float64 library routine, gradients
 against finite differences and automatic differentiation, level maps against enumeration;
 the nested-iteration start against hand-written coarse forward-Euler loops, its exactness for a
-layer-independent constant F, and the unchanged fixed point.
+layer-independent constant F, and the unchanged fixed point; the fully connected kind and mixed
+stacks against the float64 library routines, automatic differentiation and two-level exactness.
 Parity unpinned: the value of a multilevel (3+ level) iterate at a fixed finite cycle count
 is pinned only through its limit, its fixed point and its agreement with the two-level case.
 """
@@ -41,7 +45,7 @@ from __future__ import annotations
 
 import numpy as np
 
-DENSE, CONV = 0, 1
+DENSE, CONV, FC = 0, 1, 2          # FC: fully connected on the flattened sample of an image state
 TANH, RELU, IDENT = 0, 1, 2
 RELAX_F, RELAX_FCF = 0, 1
 
@@ -75,6 +79,8 @@ def affine(u, Wn, bn, layer):
     """
     if layer == DENSE:
         return u @ Wn.T + bn
+    if layer == FC:                       # u [B,...] flattened per sample to [B,d]; Wn [d,d], bn [d]
+        return (u.reshape(u.shape[0], -1) @ Wn.T + bn).reshape(u.shape)
     B, H, W, C = u.shape
     up = np.zeros((B, H + 2, W + 2, C))
     up[:, 1:-1, 1:-1, :] = u
@@ -89,6 +95,8 @@ def affine_T(G, Wn, layer):
     """Transpose of the linear part of `affine`: returns A^T G (same shape as the state)."""
     if layer == DENSE:
         return G @ Wn
+    if layer == FC:
+        return (G.reshape(G.shape[0], -1) @ Wn).reshape(G.shape)
     B, H, W, _ = G.shape
     C = Wn.shape[3]
     gp = np.zeros((B, H + 2, W + 2, C))
@@ -102,6 +110,9 @@ def weight_grad(G, u, layer):
     """Gradient of sum(G * affine(u)) with respect to (Wn, bn)."""
     if layer == DENSE:
         return G.T @ u, G.sum(axis=0)
+    if layer == FC:
+        G2, u2 = G.reshape(G.shape[0], -1), u.reshape(u.shape[0], -1)
+        return G2.T @ u2, G2.sum(axis=0)
     B, H, W, C = u.shape
     Co = G.shape[3]
     up = np.zeros((B, H + 2, W + 2, C))
@@ -112,6 +123,22 @@ def weight_grad(G, u, layer):
         for dx in range(3):
             dK[:, dy, dx, :] = G2.T @ up[:, dy:dy + H, dx:dx + W, :].reshape(-1, C)
     return dK, G2.sum(axis=0)
+
+
+def _f64(x):
+    """float64 copy of an array, or of every array of a per-layer sequence (mixed stacks)."""
+    if isinstance(x, (list, tuple)):
+        return [np.asarray(v, np.float64) for v in x]
+    return np.asarray(x, np.float64)
+
+
+def _zeros_like(x):
+    return [np.zeros_like(v) for v in x] if isinstance(x, list) else np.zeros_like(x)
+
+
+def _kind_of(layer, n):
+    """Kind of layer n: `layer` is one kind for the whole stack or a sequence of per-layer kinds."""
+    return layer[n] if isinstance(layer, (list, tuple, np.ndarray)) else layer
 
 
 def step(u, Wn, bn, hs, layer, kind):
@@ -129,13 +156,13 @@ def adjoint_step(lam, u_lin, Wn, bn, hs, layer, kind):
 # Serial propagation (the plain definition the multigrid iteration converges to)
 # ----------------------------------------------------------------------------------------
 def serial_forward(W, b, u0, h, layer, kind):
-    W = np.asarray(W, np.float64)
-    b = np.asarray(b, np.float64)
-    N = W.shape[0]
+    W = _f64(W)
+    b = _f64(b)
+    N = len(W)
     U = np.zeros((N + 1,) + u0.shape)
     U[0] = u0
     for n in range(N):
-        U[n + 1] = step(U[n], W[n], b[n], h, layer, kind)
+        U[n + 1] = step(U[n], W[n], b[n], h, _kind_of(layer, n), kind)
     return U
 
 
@@ -145,18 +172,19 @@ def serial_backward(W, b, U, lamN, h, layer, kind):
     z^n = A_n U^n + b_n; G^n = act'(z^n) * lam^{n+1}; lam^n = lam^{n+1} + h A_n^T G^n;
     dA_n = h G^n (U^n)^T summed over the batch; db_n = h sum G^n.
     """
-    W = np.asarray(W, np.float64)
-    b = np.asarray(b, np.float64)
+    W = _f64(W)
+    b = _f64(b)
     U = np.asarray(U, np.float64)
-    N = W.shape[0]
+    N = len(W)
     Lam = np.zeros_like(U)
     Lam[N] = lamN
-    dW = np.zeros_like(W)
-    db = np.zeros_like(b)
+    dW = _zeros_like(W)
+    db = _zeros_like(b)
     for n in range(N - 1, -1, -1):
-        G = act_prime(affine(U[n], W[n], b[n], layer), kind) * Lam[n + 1]
-        Lam[n] = Lam[n + 1] + h * affine_T(G, W[n], layer)
-        gW, gb = weight_grad(G, U[n], layer)
+        ln = _kind_of(layer, n)
+        G = act_prime(affine(U[n], W[n], b[n], ln), kind) * Lam[n + 1]
+        Lam[n] = Lam[n + 1] + h * affine_T(G, W[n], ln)
+        gW, gb = weight_grad(G, U[n], ln)
         dW[n] = h * gW
         db[n] = h * gb
     return Lam, dW, db
@@ -164,14 +192,15 @@ def serial_backward(W, b, U, lamN, h, layer, kind):
 
 def parameter_gradient(W, b, U, Lam, h, layer, kind):
     """dtheta from given (possibly approximate) states U and adjoints Lam, layer by layer."""
-    W = np.asarray(W, np.float64)
-    b = np.asarray(b, np.float64)
-    N = W.shape[0]
-    dW = np.zeros_like(W)
-    db = np.zeros_like(b)
+    W = _f64(W)
+    b = _f64(b)
+    N = len(W)
+    dW = _zeros_like(W)
+    db = _zeros_like(b)
     for n in range(N):
-        G = act_prime(affine(U[n], W[n], b[n], layer), kind) * Lam[n + 1]
-        gW, gb = weight_grad(G, U[n], layer)
+        ln = _kind_of(layer, n)
+        G = act_prime(affine(U[n], W[n], b[n], ln), kind) * Lam[n + 1]
+        gW, gb = weight_grad(G, U[n], ln)
         dW[n] = h * gW
         db[n] = h * gb
     return dW, db
@@ -309,15 +338,15 @@ def _solve(sizes, m, relax, phi, first, shape, init, X_init, max_iter, tol, norm
 def fas_forward(W, b, u0, h, m, max_levels, min_coarse, relax, max_iter, layer, kind,
                 tol=0.0, norm_kind=0, init=1, U_init=None):
     """Forward MGRIT-FAS solve.  Returns (U [N+1,...], residual history, cycles done)."""
-    W = np.asarray(W, np.float64)
-    b = np.asarray(b, np.float64)
+    W = _f64(W)
+    b = _f64(b)
     u0 = np.asarray(u0, np.float64)
-    N = W.shape[0]
+    N = len(W)
     sizes = level_sizes(N, m, max_levels, min_coarse)
 
     def phi(l, j, u):
         n = j * m ** l
-        return step(u, W[n], b[n], h * m ** l, layer, kind)
+        return step(u, W[n], b[n], h * m ** l, _kind_of(layer, n), kind)
 
     return _solve(sizes, m, relax, phi, u0, u0.shape, init, U_init, max_iter, tol, norm_kind)
 
@@ -331,17 +360,17 @@ def fas_adjoint(W, b, U, lamN, h, m, max_levels, min_coarse, relax, max_iter, la
     parameters of fine layer j c^l (the first layer of the coarse interval) and step h_l.
     Returns (Lam [N+1,...], dW, db, residual history, cycles done).
     """
-    W = np.asarray(W, np.float64)
-    b = np.asarray(b, np.float64)
+    W = _f64(W)
+    b = _f64(b)
     U = np.asarray(U, np.float64)
     lamN = np.asarray(lamN, np.float64)
-    N = W.shape[0]
+    N = len(W)
     sizes = level_sizes(N, m, max_levels, min_coarse)
 
     def psi(l, jr, lam):
         j = sizes[l] - (jr + 1)            # reversed sweep jr -> jr+1 lands on point j
         n = j * m ** l
-        return adjoint_step(lam, U[n], W[n], b[n], h * m ** l, layer, kind)
+        return adjoint_step(lam, U[n], W[n], b[n], h * m ** l, _kind_of(layer, n), kind)
 
     Xi = None if Lam_init is None else np.asarray(Lam_init, np.float64)[::-1]
     LamR, hist, iters = _solve(sizes, m, relax, psi, lamN, lamN.shape, init, Xi, max_iter, tol,
@@ -353,13 +382,13 @@ def fas_adjoint(W, b, U, lamN, h, m, max_levels, min_coarse, relax, max_iter, la
 
 def residual_norm(W, b, u0, U, h, layer, kind, norm_kind=0):
     """|| f_h - L_h(U) || over all N+1 points, Eq. (18)-(19)."""
-    W = np.asarray(W, np.float64)
-    b = np.asarray(b, np.float64)
+    W = _f64(W)
+    b = _f64(b)
     U = np.asarray(U, np.float64)
-    N = W.shape[0]
+    N = len(W)
     s = float(np.sum((np.asarray(u0, np.float64) - U[0]) ** 2))
     for n in range(1, N + 1):
-        r = step(U[n - 1], W[n - 1], b[n - 1], h, layer, kind) - U[n]
+        r = step(U[n - 1], W[n - 1], b[n - 1], h, _kind_of(layer, n - 1), kind) - U[n]
         s += float(np.sum(r * r))
     nrm = np.sqrt(s)
     if norm_kind == 1:

@@ -37,6 +37,11 @@ class mgrit_problem_t(ctypes.Structure):
                 ("init", ctypes.c_int32)]
 
 
+class mgrit_fc_layers_t(ctypes.Structure):
+    _fields_ = [("fc_period", ctypes.c_int32), ("Wfc", ctypes.c_void_p), ("bfc", ctypes.c_void_p),
+                ("dWfc", ctypes.c_void_p), ("dbfc", ctypes.c_void_p)]
+
+
 _lib = None
 
 
@@ -62,6 +67,17 @@ def lib() -> ctypes.CDLL:
         L.mgrit_fas_adjoint.restype = ctypes.c_int32
         L.mgrit_residual_norm.argtypes = [P, vp, vp, vp, vp, dp, vp, ctypes.c_size_t, vp]
         L.mgrit_residual_norm.restype = ctypes.c_int32
+        F = ctypes.POINTER(mgrit_fc_layers_t)
+        L.mgrit_workspace_bytes_mixed.argtypes = [P, ctypes.c_int32]
+        L.mgrit_workspace_bytes_mixed.restype = ctypes.c_size_t
+        L.mgrit_adjoint_workspace_bytes_mixed.argtypes = [P, ctypes.c_int32]
+        L.mgrit_adjoint_workspace_bytes_mixed.restype = ctypes.c_size_t
+        L.mgrit_fas_forward_mixed.argtypes = [P, F, vp, vp, vp, vp, dp, i32p, vp, ctypes.c_size_t, vp]
+        L.mgrit_fas_forward_mixed.restype = ctypes.c_int32
+        L.mgrit_fas_adjoint_mixed.argtypes = [P, F, vp, vp, vp, vp, vp, vp, vp, dp, i32p, vp, ctypes.c_size_t, vp]
+        L.mgrit_fas_adjoint_mixed.restype = ctypes.c_int32
+        L.mgrit_residual_norm_mixed.argtypes = [P, F, vp, vp, vp, vp, dp, vp, ctypes.c_size_t, vp]
+        L.mgrit_residual_norm_mixed.restype = ctypes.c_int32
         L.mgrit_trace_begin.argtypes = []
         L.mgrit_trace_begin.restype = None
         L.mgrit_trace_end.argtypes = [dp, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64),
@@ -160,6 +176,55 @@ def mgrit_residual_norm(p: mgrit_problem_t, W, b, u0, U, workspace, *, stream=No
                                    _stream(stream))
     if check and rc != MGRIT_OK:
         raise MgritError(rc, "mgrit_residual_norm")
+    return rc, out.value
+
+
+def make_fc_layers(fc_period: int, Wfc, bfc, dWfc=None, dbfc=None) -> mgrit_fc_layers_t:
+    """Fully connected layers of a mixed stack (device tensors owned by the caller, which keeps them alive)."""
+    return mgrit_fc_layers_t(fc_period=fc_period, Wfc=_ptr(Wfc), bfc=_ptr(bfc), dWfc=_ptr(dWfc), dbfc=_ptr(dbfc))
+
+
+def mgrit_workspace_bytes_mixed(p: mgrit_problem_t, fc_period: int) -> int:
+    return int(lib().mgrit_workspace_bytes_mixed(ctypes.byref(p), fc_period))
+
+
+def mgrit_adjoint_workspace_bytes_mixed(p: mgrit_problem_t, fc_period: int) -> int:
+    return int(lib().mgrit_adjoint_workspace_bytes_mixed(ctypes.byref(p), fc_period))
+
+
+def mgrit_fas_forward_mixed(p: mgrit_problem_t, fc: mgrit_fc_layers_t, W, b, u0, U, workspace, *, want_hist=True,
+                            stream=None, check=True):
+    hist = (ctypes.c_double * max(p.max_iter, 1))() if want_hist else None
+    iters = ctypes.c_int32(0)
+    rc = lib().mgrit_fas_forward_mixed(ctypes.byref(p), ctypes.byref(fc), _ptr(W), _ptr(b), _ptr(u0), _ptr(U), hist,
+                                       ctypes.byref(iters) if want_hist else None, _ptr(workspace),
+                                       workspace.numel() * workspace.element_size(), _stream(stream))
+    if check and rc != MGRIT_OK:
+        raise MgritError(rc, "mgrit_fas_forward_mixed")
+    return rc, ([hist[i] for i in range(iters.value)] if want_hist else None), iters.value
+
+
+def mgrit_fas_adjoint_mixed(p: mgrit_problem_t, fc: mgrit_fc_layers_t, W, b, U, lamN, Lam, dW, db, workspace, *,
+                            want_hist=True, stream=None, check=True):
+    hist = (ctypes.c_double * max(p.max_iter, 1))() if want_hist else None
+    iters = ctypes.c_int32(0)
+    rc = lib().mgrit_fas_adjoint_mixed(ctypes.byref(p), ctypes.byref(fc), _ptr(W), _ptr(b), _ptr(U), _ptr(lamN),
+                                       _ptr(Lam), _ptr(dW), _ptr(db), hist,
+                                       ctypes.byref(iters) if want_hist else None, _ptr(workspace),
+                                       workspace.numel() * workspace.element_size(), _stream(stream))
+    if check and rc != MGRIT_OK:
+        raise MgritError(rc, "mgrit_fas_adjoint_mixed")
+    return rc, ([hist[i] for i in range(iters.value)] if want_hist else None), iters.value
+
+
+def mgrit_residual_norm_mixed(p: mgrit_problem_t, fc: mgrit_fc_layers_t, W, b, u0, U, workspace, *, stream=None,
+                              check=True):
+    out = ctypes.c_double(0.0)
+    rc = lib().mgrit_residual_norm_mixed(ctypes.byref(p), ctypes.byref(fc), _ptr(W), _ptr(b), _ptr(u0), _ptr(U),
+                                         ctypes.byref(out), _ptr(workspace),
+                                         workspace.numel() * workspace.element_size(), _stream(stream))
+    if check and rc != MGRIT_OK:
+        raise MgritError(rc, "mgrit_residual_norm_mixed")
     return rc, out.value
 
 

@@ -34,6 +34,10 @@ struct Plan {
   bool chain_fwd, chain_adj;           // dense layers: temporally fused chain kernels usable
   size_t off_partial, n_partial, off_hist, off_Wt, off_D, off_gpart;
   size_t bytes_fwd, bytes_adj;
+  // mixed stacks (Sec. IV-E): every fcP-th layer is fully connected on the flattened sample; 0 = none
+  int fcP, nfc, B;
+  long long dfc, wsize_fc;             // flattened sample size d and d*d
+  size_t off_Wfct;                     // transposed fully connected weights (adjoint)
 };
 
 // Level hierarchy (Sec. III-C): coarsen by m while fewer than max_levels levels exist and the
@@ -53,10 +57,11 @@ int build_levels(const mgrit_problem_t* p, int* L, int* Nl) {
   return MGRIT_OK;
 }
 
-int make_plan(const mgrit_problem_t* p, Plan* pl) {
+int make_plan(const mgrit_problem_t* p, Plan* pl, int fcP = 0) {
   memset(pl, 0, sizeof(*pl));
   int rc = build_levels(p, &pl->L, pl->Nl);
   if (rc != MGRIT_OK) return rc;
+  if (fcP != 0 && (fcP < 2 || p->layer != MGRIT_LAYER_CONV3X3)) return MGRIT_ERR_PROBLEM;
   if (!(p->h > 0.0f) || !isfinite(p->h)) return MGRIT_ERR_PROBLEM;
   if (p->N > 65535) return MGRIT_ERR_UNSUPPORTED;            // layers / points index one grid dimension of the transfer kernels
   if (p->relax != MGRIT_RELAX_F && p->relax != MGRIT_RELAX_FCF) return MGRIT_ERR_PROBLEM;
@@ -82,6 +87,14 @@ int make_plan(const mgrit_problem_t* p, Plan* pl) {
   pl->E = (long long)pl->M * pl->Nf;
   pl->wsize = (long long)pl->Nf * pl->K;
   pl->esize = p->dtype == MGRIT_FP32 ? 4 : 2;
+  pl->B = p->B;
+  if (fcP) {
+    pl->fcP = fcP;
+    pl->nfc = (p->N + fcP - 1) / fcP;
+    pl->dfc = (long long)p->Himg * p->Wimg * p->C;
+    if (pl->dfc * pl->dfc > 0x7fffffffLL) return MGRIT_ERR_UNSUPPORTED;      // 32-bit offsets inside a weight matrix
+    pl->wsize_fc = pl->dfc * pl->dfc;
+  }
   long long mp = 1;
   for (int l = 0; l < pl->L; ++l) {
     pl->mpow[l] = mp;
@@ -115,6 +128,9 @@ int make_plan(const mgrit_problem_t* p, Plan* pl) {
       if (npc > np) np = npc;
     }
   }
+  if (fcP)     // the dense launch of the fully connected groups adds its workgroups (at most 32x32 tiles of each)
+    np += (size_t)((p->B + 31) / 32) * (size_t)((pl->dfc + 31) / 32) * (size_t)pl->nfc;
+  if (np > 0x7fffffffu) return MGRIT_ERR_UNSUPPORTED;
   pl->n_partial = np;
   pl->off_partial = off; off = align_up(off + np * 4);
   pl->off_hist = off; off = align_up(off + (size_t)(p->max_iter + 1) * 8);
@@ -124,6 +140,8 @@ int make_plan(const mgrit_problem_t* p, Plan* pl) {
   pl->off_gpart = off;                 // partial sums of the conv parameter gradient when layers are split
   if (p->layer == MGRIT_LAYER_CONV3X3)
     off = align_up(off + conv_grad_partial_bytes(p->B, p->Himg, p->Wimg, p->C, p->dtype, p->N));
+  pl->off_Wfct = off;
+  if (fcP) off = align_up(off + (size_t)pl->nfc * pl->wsize_fc * pl->esize);
   pl->bytes_adj = off;
   return MGRIT_OK;
 }
@@ -146,6 +164,8 @@ struct Solver {
   const void* W;
   const float* bias;
   const float* Dm;
+  const void* Wfc = nullptr;           // fully connected layers of a mixed stack (their transposes in the adjoint)
+  const float* bfc = nullptr;
   int act;
   float* partial;
   double* hist_dev;
@@ -174,8 +194,60 @@ struct Solver {
     a.wstream = (double)p->N * (double)pl.wsize * (double)pl.esize > 128.0 * 1024.0 * 1024.0 ? 1 : 0;
     return a;
   }
+  // Groups of a launch whose layer a.wm(gi) is fully connected: gi = g0 + per * j, j < cnt.  The layer index is
+  // affine in gi, so the solutions of  layer = 0 (mod fcP)  form an arithmetic progression.
+  void fc_subset(const PtMap& wm, int groups, long long* g0, long long* per, int* cnt) const {
+    *g0 = 0; *per = 1; *cnt = 0;
+    const long long P = pl.fcP;
+    if (!P) return;
+    const long long st = ((wm.stride % P) + P) % P;
+    long long a = st, b = P;                                // gcd(stride mod P, P); gcd(0, P) = P
+    while (a) { const long long t = b % a; b = a; a = t; }
+    *per = P / b;
+    const long long lim = groups < *per ? groups : *per;
+    for (long long gi = 0; gi < lim; ++gi)
+      if ((((wm.base + gi * wm.stride) % P) + P) % P == 0) {
+        *g0 = gi;
+        *cnt = (int)((groups - 1 - gi) / *per + 1);
+        return;
+      }
+  }
+  StepArgs fc_args(const StepArgs& a, long long g0, long long per) const {
+    auto sub = [&](const PtMap& mp) { return PtMap{mp.base + g0 * mp.stride, mp.stride * per}; };
+    StepArgs d = a;
+    d.xm = sub(a.xm); d.dm = sub(a.dm); d.om = sub(a.om); d.e1m = sub(a.e1m); d.e2m = sub(a.e2m);
+    d.wm = PtMap{(a.wm.base + g0 * a.wm.stride) / pl.fcP, a.wm.stride * per / pl.fcP};
+    d.W = Wfc; d.bias = a.bias ? bfc : nullptr;
+    d.M = pl.B; d.Nf = (int)pl.dfc; d.K = (int)pl.dfc; d.Himg = 0; d.Wimg = 0; d.TH = 0;
+    d.wsize = pl.wsize_fc;
+    d.wstream = (double)pl.nfc * (double)pl.wsize_fc * (double)pl.esize > 128.0 * 1024.0 * 1024.0 ? 1 : 0;
+    d.skip0 = 0; d.skipper = 0;
+    return d;
+  }
+  // workgroups (= norm partials) of a step launch over `groups` groups
+  int launch_blocks(const StepArgs& a, int groups) const {
+    int nb = step_grid_blocks(a, p->layer, p->dtype, groups) * groups;
+    if (pl.fcP) {
+      long long g0, per; int cnt;
+      fc_subset(a.wm, groups, &g0, &per, &cnt);
+      if (cnt) nb += step_grid_blocks(fc_args(a, g0, per), MGRIT_LAYER_DENSE, p->dtype, cnt) * cnt;
+    }
+    return nb;
+  }
   void launch(const StepArgs& a, int groups) {
-    if (err == hipSuccess) chk(launch_step(a, p->layer, p->dtype, groups, s));
+    if (err != hipSuccess) return;
+    if (!pl.fcP) { chk(launch_step(a, p->layer, p->dtype, groups, s)); return; }
+    // mixed stack: the convolution kernel passes over the fully connected groups, a dense launch serves them
+    long long g0, per; int cnt;
+    fc_subset(a.wm, groups, &g0, &per, &cnt);
+    StepArgs c = a;
+    if (cnt) { c.skip0 = (int)g0; c.skipper = (int)per; }
+    if (cnt < groups || a.norm_partial) chk(launch_step(c, p->layer, p->dtype, groups, s));
+    if (cnt && err == hipSuccess) {
+      StepArgs d = fc_args(a, g0, per);
+      if (a.norm_partial) d.norm_partial = a.norm_partial + (size_t)step_grid_blocks(a, p->layer, p->dtype, groups) * groups;
+      chk(launch_step(d, MGRIT_LAYER_DENSE, p->dtype, cnt, s));
+    }
   }
   // X[js] = Phi(X[js-1]) + g[js] for js = js0 + gi*jstride        (relaxation, coarsest solve)
   void propagate(int l, long long js0, long long jstride, int groups) {
@@ -292,7 +364,7 @@ struct Solver {
       // Alg. 1 step 2: injection of the C-points (the residual of point 0 is identically zero); on the fine
       // level the same launch also sums the norm partials of the residual launch (Alg. 1 step 6)
       if (l == 0) {
-        const int nb = step_grid_blocks(a, p->layer, p->dtype, Nc) * Nc;
+        const int nb = launch_blocks(a, Nc);
         const double scale = p->norm_kind == MGRIT_NORM_RMS ? 1.0 / sqrt((double)(Nc + 1) * (double)pl.E) : 1.0;
         chk(launch_copy_points_norm(X[l + 1], PtMap{0, 1}, X[l], pm(l, 0, m), pl.E, Nc + 1, partial, nb, scale,
                                     hist_dev + iter, s));
@@ -388,6 +460,151 @@ void bind_workspace(Solver& sv, void* workspace) {
   sv.hist_dev = reinterpret_cast<double*>(ws + pl.off_hist);
 }
 
+// checks of the fully connected part of a mixed stack (fc == nullptr: plain stack)
+int check_fc(const mgrit_fc_layers_t* fc, bool adjoint, const float* dW, const float* db) {
+  if (!fc) return MGRIT_OK;
+  if (!fc->Wfc || !fc->bfc || !aligned(fc->Wfc) || !aligned(fc->bfc)) return MGRIT_ERR_POINTER;
+  if (adjoint) {
+    if ((dW && !fc->dWfc) || (db && !fc->dbfc)) return MGRIT_ERR_POINTER;
+    if (!aligned(fc->dWfc) || !aligned(fc->dbfc)) return MGRIT_ERR_POINTER;
+  }
+  return MGRIT_OK;
+}
+
+int forward_impl(const mgrit_problem_t* p, const mgrit_fc_layers_t* fc, const void* W, const float* b,
+                 const float* u0, float* U, double* resnorm_hist, int32_t* iters_done, void* workspace,
+                 size_t workspace_bytes, void* hip_stream) {
+  if (!p || !W || !b || !u0 || !U || !workspace) return MGRIT_ERR_POINTER;
+  if (!aligned(W) || !aligned(b) || !aligned(u0) || !aligned(U) || !aligned(workspace)) return MGRIT_ERR_POINTER;
+  int rc = check_fc(fc, false, nullptr, nullptr);
+  if (rc != MGRIT_OK) return rc;
+  Solver sv;
+  rc = make_plan(p, &sv.pl, fc ? fc->fc_period : 0);
+  if (rc != MGRIT_OK) return rc;
+  if (fc && !sv.pl.fcP) return MGRIT_ERR_PROBLEM;
+  if (workspace_bytes < sv.pl.bytes_fwd) return MGRIT_ERR_WORKSPACE;
+  sv.p = p; sv.s = static_cast<hipStream_t>(hip_stream); sv.adjoint = false;
+  memset(sv.X, 0, sizeof(sv.X)); memset(sv.g, 0, sizeof(sv.g)); memset(sv.R, 0, sizeof(sv.R)); memset(sv.Cb, 0, sizeof(sv.Cb));
+  sv.X[0] = U;
+  sv.W = W; sv.bias = b; sv.Dm = nullptr; sv.act = p->act;
+  if (fc) { sv.Wfc = fc->Wfc; sv.bfc = fc->bfc; }
+  sv.use_chain = sv.pl.chain_fwd && chain_enabled();
+  bind_workspace(sv, workspace);
+  return run_solver(sv, u0, resnorm_hist, iters_done);
+}
+
+int adjoint_impl(const mgrit_problem_t* p, const mgrit_fc_layers_t* fc, const void* W, const float* b,
+                 const float* U, const float* lamN, float* Lam, float* dW, float* db, double* resnorm_hist,
+                 int32_t* iters_done, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!p || !W || !b || !U || !lamN || !Lam || !workspace) return MGRIT_ERR_POINTER;
+  if (!aligned(W) || !aligned(b) || !aligned(U) || !aligned(lamN) || !aligned(Lam) || !aligned(workspace) ||
+      !aligned(dW) || !aligned(db))
+    return MGRIT_ERR_POINTER;
+  int rc = check_fc(fc, true, dW, db);
+  if (rc != MGRIT_OK) return rc;
+  Solver sv;
+  rc = make_plan(p, &sv.pl, fc ? fc->fc_period : 0);
+  if (rc != MGRIT_OK) return rc;
+  if (fc && !sv.pl.fcP) return MGRIT_ERR_PROBLEM;
+  if (workspace_bytes < sv.pl.bytes_adj) return MGRIT_ERR_WORKSPACE;
+  const Plan& pl = sv.pl;
+  sv.p = p; sv.s = static_cast<hipStream_t>(hip_stream); sv.adjoint = true;
+  memset(sv.X, 0, sizeof(sv.X)); memset(sv.g, 0, sizeof(sv.g)); memset(sv.R, 0, sizeof(sv.R)); memset(sv.Cb, 0, sizeof(sv.Cb));
+  sv.X[0] = Lam;
+  bind_workspace(sv, workspace);
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  void* Wt = ws + pl.off_Wt;
+  void* Wfct = ws + pl.off_Wfct;
+  float* D = reinterpret_cast<float*>(ws + pl.off_D);
+  // transposed parameters, and act'(A_n U^n + b_n) for every layer in one grouped launch
+  sv.chk(launch_transpose_weights(W, Wt, p->layer, p->dtype, p->N, pl.Nf, sv.s));
+  if (fc) sv.chk(launch_transpose_weights(fc->Wfc, Wfct, MGRIT_LAYER_DENSE, p->dtype, pl.nfc, (int)pl.dfc, sv.s));
+  {
+    sv.W = W; sv.bias = b; sv.Dm = nullptr; sv.act = p->act;
+    if (fc) { sv.Wfc = fc->Wfc; sv.bfc = fc->bfc; }
+    StepArgs a = sv.base_args(0, 1, 1);
+    a.wm = PtMap{0, 1};
+    a.mode = MODE_DACT;
+    a.X = U; a.xm = PtMap{0, 1};
+    a.Out = D; a.om = PtMap{0, 1};
+    sv.launch(a, p->N);
+  }
+  sv.W = Wt; sv.bias = nullptr; sv.Dm = D; sv.act = ACT_IDENT;
+  if (fc) { sv.Wfc = Wfct; sv.bfc = nullptr; }
+  sv.use_chain = pl.chain_adj && chain_enabled();
+  rc = run_solver(sv, lamN, resnorm_hist, iters_done);
+  if (rc != MGRIT_OK && rc != MGRIT_ERR_NONFINITE) return rc;
+  if (dW || db) {
+    GradArgs ga;
+    memset(&ga, 0, sizeof(ga));
+    ga.U = U; ga.um = PtMap{0, 1};
+    ga.Lam = Lam; ga.lm = PtMap{1, 1};
+    ga.Dm = D; ga.dm = PtMap{0, 1};
+    ga.dW = dW; ga.db = db; ga.hs = p->h;
+    ga.M = pl.M; ga.Nf = pl.Nf; ga.K = pl.K; ga.Himg = p->Himg; ga.Wimg = p->Wimg; ga.B = p->B;
+    ga.E = pl.E; ga.wsize = pl.wsize;
+    ga.partial = reinterpret_cast<float*>(ws + pl.off_gpart);
+    if (launch_grad(ga, p->layer, p->dtype, p->N, sv.s) != hipSuccess) return MGRIT_ERR_HIP;
+    if (fc) {
+      // the convolution gradient ran over every layer: its slots at the fully connected layers are defined as
+      // zero; their own gradient is the dense contraction over the batch
+      const long long P = pl.fcP;
+      if (dW) sv.chk(launch_zero_points(dW, PtMap{0, P}, pl.wsize, pl.nfc, sv.s));
+      if (db) sv.chk(launch_zero_points(db, PtMap{0, P}, pl.Nf, pl.nfc, sv.s));
+      GradArgs gd;
+      memset(&gd, 0, sizeof(gd));
+      gd.U = U; gd.um = PtMap{0, P};
+      gd.Lam = Lam; gd.lm = PtMap{1, P};
+      gd.Dm = D; gd.dm = PtMap{0, P};
+      gd.dW = dW ? fc->dWfc : nullptr; gd.db = db ? fc->dbfc : nullptr; gd.hs = p->h;
+      gd.M = p->B; gd.Nf = (int)pl.dfc; gd.K = (int)pl.dfc; gd.B = p->B;
+      gd.E = pl.E; gd.wsize = pl.wsize_fc;
+      if (sv.err != hipSuccess || launch_grad(gd, MGRIT_LAYER_DENSE, p->dtype, pl.nfc, sv.s) != hipSuccess)
+        return MGRIT_ERR_HIP;
+    }
+    if (resnorm_hist || iters_done)
+      if (hipStreamSynchronize(sv.s) != hipSuccess) return MGRIT_ERR_HIP;
+  }
+  return rc;
+}
+
+int residual_norm_impl(const mgrit_problem_t* p, const mgrit_fc_layers_t* fc, const void* W, const float* b,
+                       const float* u0, const float* U, double* norm_out, void* workspace, size_t workspace_bytes,
+                       void* hip_stream) {
+  if (!p || !W || !b || !u0 || !U || !norm_out || !workspace) return MGRIT_ERR_POINTER;
+  if (!aligned(W) || !aligned(b) || !aligned(u0) || !aligned(U) || !aligned(workspace)) return MGRIT_ERR_POINTER;
+  int rc = check_fc(fc, false, nullptr, nullptr);
+  if (rc != MGRIT_OK) return rc;
+  Solver sv;
+  rc = make_plan(p, &sv.pl, fc ? fc->fc_period : 0);
+  if (rc != MGRIT_OK) return rc;
+  if (fc && !sv.pl.fcP) return MGRIT_ERR_PROBLEM;
+  if (workspace_bytes < sv.pl.bytes_fwd) return MGRIT_ERR_WORKSPACE;
+  const Plan& pl = sv.pl;
+  sv.p = p; sv.s = static_cast<hipStream_t>(hip_stream); sv.adjoint = false;
+  memset(sv.X, 0, sizeof(sv.X)); memset(sv.g, 0, sizeof(sv.g)); memset(sv.R, 0, sizeof(sv.R)); memset(sv.Cb, 0, sizeof(sv.Cb));
+  sv.W = W; sv.bias = b; sv.Dm = nullptr; sv.act = p->act;
+  if (fc) { sv.Wfc = fc->Wfc; sv.bfc = fc->bfc; }
+  bind_workspace(sv, workspace);
+  // rows n = 1..N of f_h - L_h(U): Phi(U[n-1]) - U[n]; row 0: u0 - U[0]
+  StepArgs a = sv.base_args(0, 1, 1);
+  a.X = U; a.xm = PtMap{0, 1};
+  a.E1 = U; a.e1m = PtMap{1, 1}; a.c1 = -1.0f;
+  a.norm_partial = sv.partial;
+  sv.launch(a, p->N);
+  const int nb = sv.launch_blocks(a, p->N);
+  int nb0 = 0;
+  sv.chk(launch_diff_sq(u0, U, pl.E, sv.partial + nb, &nb0, sv.s));
+  const double scale = p->norm_kind == MGRIT_NORM_RMS ? 1.0 / sqrt((double)(p->N + 1) * (double)pl.E) : 1.0;
+  sv.chk(launch_norm_final(sv.partial, nb + nb0, scale, sv.hist_dev, sv.s));
+  double v = 0.0;
+  sv.chk(hipMemcpyAsync(&v, sv.hist_dev, sizeof(double), hipMemcpyDeviceToHost, sv.s));
+  sv.chk(hipStreamSynchronize(sv.s));
+  if (sv.err != hipSuccess) return MGRIT_ERR_HIP;
+  *norm_out = v;
+  return isfinite(v) ? MGRIT_OK : MGRIT_ERR_NONFINITE;
+}
+
 }  // namespace
 
 extern "C" {
@@ -424,102 +641,54 @@ size_t mgrit_adjoint_workspace_bytes(const mgrit_problem_t* p) {
 int32_t mgrit_fas_forward(const mgrit_problem_t* p, const void* W, const float* b, const float* u0, float* U,
                           double* resnorm_hist, int32_t* iters_done, void* workspace, size_t workspace_bytes,
                           void* hip_stream) {
-  if (!p || !W || !b || !u0 || !U || !workspace) return MGRIT_ERR_POINTER;
-  if (!aligned(W) || !aligned(b) || !aligned(u0) || !aligned(U) || !aligned(workspace)) return MGRIT_ERR_POINTER;
-  Solver sv;
-  int rc = make_plan(p, &sv.pl);
-  if (rc != MGRIT_OK) return rc;
-  if (workspace_bytes < sv.pl.bytes_fwd) return MGRIT_ERR_WORKSPACE;
-  sv.p = p; sv.s = static_cast<hipStream_t>(hip_stream); sv.adjoint = false;
-  memset(sv.X, 0, sizeof(sv.X)); memset(sv.g, 0, sizeof(sv.g)); memset(sv.R, 0, sizeof(sv.R)); memset(sv.Cb, 0, sizeof(sv.Cb));
-  sv.X[0] = U;
-  sv.W = W; sv.bias = b; sv.Dm = nullptr; sv.act = p->act;
-  sv.use_chain = sv.pl.chain_fwd && chain_enabled();
-  bind_workspace(sv, workspace);
-  return run_solver(sv, u0, resnorm_hist, iters_done);
+  return forward_impl(p, nullptr, W, b, u0, U, resnorm_hist, iters_done, workspace, workspace_bytes, hip_stream);
 }
 
 int32_t mgrit_fas_adjoint(const mgrit_problem_t* p, const void* W, const float* b, const float* U, const float* lamN,
                           float* Lam, float* dW, float* db, double* resnorm_hist, int32_t* iters_done,
                           void* workspace, size_t workspace_bytes, void* hip_stream) {
-  if (!p || !W || !b || !U || !lamN || !Lam || !workspace) return MGRIT_ERR_POINTER;
-  if (!aligned(W) || !aligned(b) || !aligned(U) || !aligned(lamN) || !aligned(Lam) || !aligned(workspace) ||
-      !aligned(dW) || !aligned(db))
-    return MGRIT_ERR_POINTER;
-  Solver sv;
-  int rc = make_plan(p, &sv.pl);
-  if (rc != MGRIT_OK) return rc;
-  if (workspace_bytes < sv.pl.bytes_adj) return MGRIT_ERR_WORKSPACE;
-  const Plan& pl = sv.pl;
-  sv.p = p; sv.s = static_cast<hipStream_t>(hip_stream); sv.adjoint = true;
-  memset(sv.X, 0, sizeof(sv.X)); memset(sv.g, 0, sizeof(sv.g)); memset(sv.R, 0, sizeof(sv.R)); memset(sv.Cb, 0, sizeof(sv.Cb));
-  sv.X[0] = Lam;
-  bind_workspace(sv, workspace);
-  unsigned char* ws = static_cast<unsigned char*>(workspace);
-  void* Wt = ws + pl.off_Wt;
-  float* D = reinterpret_cast<float*>(ws + pl.off_D);
-  // transposed parameters, and act'(A_n U^n + b_n) for every layer in one grouped launch
-  sv.chk(launch_transpose_weights(W, Wt, p->layer, p->dtype, p->N, pl.Nf, sv.s));
-  {
-    sv.W = W; sv.bias = b; sv.Dm = nullptr; sv.act = p->act;
-    StepArgs a = sv.base_args(0, 1, 1);
-    a.wm = PtMap{0, 1};
-    a.mode = MODE_DACT;
-    a.X = U; a.xm = PtMap{0, 1};
-    a.Out = D; a.om = PtMap{0, 1};
-    sv.launch(a, p->N);
-  }
-  sv.W = Wt; sv.bias = nullptr; sv.Dm = D; sv.act = ACT_IDENT;
-  sv.use_chain = pl.chain_adj && chain_enabled();
-  rc = run_solver(sv, lamN, resnorm_hist, iters_done);
-  if (rc != MGRIT_OK && rc != MGRIT_ERR_NONFINITE) return rc;
-  if (dW || db) {
-    GradArgs ga;
-    memset(&ga, 0, sizeof(ga));
-    ga.U = U; ga.um = PtMap{0, 1};
-    ga.Lam = Lam; ga.lm = PtMap{1, 1};
-    ga.Dm = D; ga.dm = PtMap{0, 1};
-    ga.dW = dW; ga.db = db; ga.hs = p->h;
-    ga.M = pl.M; ga.Nf = pl.Nf; ga.K = pl.K; ga.Himg = p->Himg; ga.Wimg = p->Wimg; ga.B = p->B;
-    ga.E = pl.E; ga.wsize = pl.wsize;
-    ga.partial = reinterpret_cast<float*>(ws + pl.off_gpart);
-    if (launch_grad(ga, p->layer, p->dtype, p->N, sv.s) != hipSuccess) return MGRIT_ERR_HIP;
-    if (resnorm_hist || iters_done)
-      if (hipStreamSynchronize(sv.s) != hipSuccess) return MGRIT_ERR_HIP;
-  }
-  return rc;
+  return adjoint_impl(p, nullptr, W, b, U, lamN, Lam, dW, db, resnorm_hist, iters_done, workspace, workspace_bytes,
+                      hip_stream);
 }
 
 int32_t mgrit_residual_norm(const mgrit_problem_t* p, const void* W, const float* b, const float* u0, const float* U,
                             double* norm_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
-  if (!p || !W || !b || !u0 || !U || !norm_out || !workspace) return MGRIT_ERR_POINTER;
-  if (!aligned(W) || !aligned(b) || !aligned(u0) || !aligned(U) || !aligned(workspace)) return MGRIT_ERR_POINTER;
-  Solver sv;
-  int rc = make_plan(p, &sv.pl);
-  if (rc != MGRIT_OK) return rc;
-  if (workspace_bytes < sv.pl.bytes_fwd) return MGRIT_ERR_WORKSPACE;
-  const Plan& pl = sv.pl;
-  sv.p = p; sv.s = static_cast<hipStream_t>(hip_stream); sv.adjoint = false;
-  memset(sv.X, 0, sizeof(sv.X)); memset(sv.g, 0, sizeof(sv.g)); memset(sv.R, 0, sizeof(sv.R)); memset(sv.Cb, 0, sizeof(sv.Cb));
-  sv.W = W; sv.bias = b; sv.Dm = nullptr; sv.act = p->act;
-  bind_workspace(sv, workspace);
-  // rows n = 1..N of f_h - L_h(U): Phi(U[n-1]) - U[n]; row 0: u0 - U[0]
-  StepArgs a = sv.base_args(0, 1, 1);
-  a.X = U; a.xm = PtMap{0, 1};
-  a.E1 = U; a.e1m = PtMap{1, 1}; a.c1 = -1.0f;
-  a.norm_partial = sv.partial;
-  sv.launch(a, p->N);
-  const int nb = step_grid_blocks(a, p->layer, p->dtype, p->N) * p->N;
-  int nb0 = 0;
-  sv.chk(launch_diff_sq(u0, U, pl.E, sv.partial + nb, &nb0, sv.s));
-  const double scale = p->norm_kind == MGRIT_NORM_RMS ? 1.0 / sqrt((double)(p->N + 1) * (double)pl.E) : 1.0;
-  sv.chk(launch_norm_final(sv.partial, nb + nb0, scale, sv.hist_dev, sv.s));
-  double v = 0.0;
-  sv.chk(hipMemcpyAsync(&v, sv.hist_dev, sizeof(double), hipMemcpyDeviceToHost, sv.s));
-  sv.chk(hipStreamSynchronize(sv.s));
-  if (sv.err != hipSuccess) return MGRIT_ERR_HIP;
-  *norm_out = v;
-  return isfinite(v) ? MGRIT_OK : MGRIT_ERR_NONFINITE;
+  return residual_norm_impl(p, nullptr, W, b, u0, U, norm_out, workspace, workspace_bytes, hip_stream);
+}
+
+size_t mgrit_workspace_bytes_mixed(const mgrit_problem_t* p, int32_t fc_period) {
+  Plan pl;
+  if (!p || fc_period < 2 || make_plan(p, &pl, fc_period) != MGRIT_OK) return 0;
+  return pl.bytes_fwd;
+}
+
+size_t mgrit_adjoint_workspace_bytes_mixed(const mgrit_problem_t* p, int32_t fc_period) {
+  Plan pl;
+  if (!p || fc_period < 2 || make_plan(p, &pl, fc_period) != MGRIT_OK) return 0;
+  return pl.bytes_adj;
+}
+
+int32_t mgrit_fas_forward_mixed(const mgrit_problem_t* p, const mgrit_fc_layers_t* fc, const void* W, const float* b,
+                                const float* u0, float* U, double* resnorm_hist, int32_t* iters_done,
+                                void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!fc) return MGRIT_ERR_POINTER;
+  return forward_impl(p, fc, W, b, u0, U, resnorm_hist, iters_done, workspace, workspace_bytes, hip_stream);
+}
+
+int32_t mgrit_fas_adjoint_mixed(const mgrit_problem_t* p, const mgrit_fc_layers_t* fc, const void* W, const float* b,
+                                const float* U, const float* lamN, float* Lam, float* dW, float* db,
+                                double* resnorm_hist, int32_t* iters_done, void* workspace, size_t workspace_bytes,
+                                void* hip_stream) {
+  if (!fc) return MGRIT_ERR_POINTER;
+  return adjoint_impl(p, fc, W, b, U, lamN, Lam, dW, db, resnorm_hist, iters_done, workspace, workspace_bytes,
+                      hip_stream);
+}
+
+int32_t mgrit_residual_norm_mixed(const mgrit_problem_t* p, const mgrit_fc_layers_t* fc, const void* W,
+                                  const float* b, const float* u0, const float* U, double* norm_out,
+                                  void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!fc) return MGRIT_ERR_POINTER;
+  return residual_norm_impl(p, fc, W, b, u0, U, norm_out, workspace, workspace_bytes, hip_stream);
 }
 
 void mgrit_trace_begin(void) { trace_begin(); }

@@ -44,6 +44,9 @@ struct StepArgs {
   int dbf16;                       // 1: Dm (input) and the output of MODE_DACT are bf16 arrays
   int wstream;                     // 1: all layers' weights together exceed the last-level cache, load them
                                    // non-temporally; 0: they fit and later launches of the solve find them there
+  int skip0, skipper;              // conv only, skipper > 0: groups skip0, skip0 + skipper, ... do nothing (their
+                                   // layer is a fully connected one, served by a dense launch) and write 0 to
+                                   // their norm partials
   long long E;                     // M * Nf
   long long wsize;                 // Nf * K elements per layer
 };

@@ -646,6 +646,10 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
 
   const int L = logical_block();
   const int gi = L / a.tiles, tile = L % a.tiles;
+  if (a.skipper > 0 && gi >= a.skip0 && (gi - a.skip0) % a.skipper == 0) {   // not a convolution layer (whole workgroup)
+    if (a.norm_partial && threadIdx.x == 0) a.norm_partial[L] = 0.0f;
+    return;
+  }
   const int tiles_per_img = (H + TH - 1) / TH;
   const int bimg = tile / tiles_per_img, y0 = (tile % tiles_per_img) * TH;
   const long long layer = a.wm.base + gi * a.wm.stride;

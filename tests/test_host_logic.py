@@ -122,6 +122,51 @@ def test_adjoint_and_norm_argument_validation():
     assert rc == Bd.MGRIT_ERR_POINTER
 
 
+def test_mixed_stack_argument_validation_and_workspace():
+    L = M.lib()
+    conv = _problem(layer=1, C=8, Himg=4, Wimg=4, q=0, N=16, m=2, max_levels=3)
+    assert M.mgrit_workspace_bytes_mixed(conv, 4) >= M.mgrit_workspace_bytes(conv) > 0   # plus partials of the dense launches
+    d, nfc = 4 * 4 * 8, 4
+    assert (M.mgrit_adjoint_workspace_bytes_mixed(conv, 4) - M.mgrit_workspace_bytes_mixed(conv, 4)
+            >= M.mgrit_adjoint_workspace_bytes(conv) - M.mgrit_workspace_bytes(conv) + nfc * d * d * 4)
+    assert M.mgrit_workspace_bytes_mixed(conv, 1) == 0 and M.mgrit_workspace_bytes_mixed(conv, 0) == 0
+    assert M.mgrit_workspace_bytes_mixed(_problem(), 4) == 0                               # dense stacks have no mixed form
+    big = _problem(layer=1, C=64, Himg=32, Wimg=32, q=0)                                   # d = 65536: d*d overflows
+    assert M.mgrit_workspace_bytes_mixed(big, 4) == 0
+    fc = Bd.mgrit_fc_layers_t(fc_period=4, Wfc=FAKE, bfc=FAKE, dWfc=None, dbfc=None)
+    rc = L.mgrit_fas_forward_mixed(ctypes.byref(conv), None, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, 1 << 40, None)
+    assert rc == Bd.MGRIT_ERR_POINTER
+    rc = L.mgrit_fas_forward_mixed(ctypes.byref(conv), ctypes.byref(fc), FAKE, FAKE, FAKE, FAKE, None, None, FAKE, 8, None)
+    assert rc == Bd.MGRIT_ERR_WORKSPACE
+    nofc = Bd.mgrit_fc_layers_t(fc_period=4, Wfc=None, bfc=FAKE, dWfc=None, dbfc=None)
+    rc = L.mgrit_fas_forward_mixed(ctypes.byref(conv), ctypes.byref(nofc), FAKE, FAKE, FAKE, FAKE, None, None, FAKE, 8, None)
+    assert rc == Bd.MGRIT_ERR_POINTER
+    for bad_period in (1, -3):
+        bad = Bd.mgrit_fc_layers_t(fc_period=bad_period, Wfc=FAKE, bfc=FAKE, dWfc=None, dbfc=None)
+        rc = L.mgrit_fas_forward_mixed(ctypes.byref(conv), ctypes.byref(bad), FAKE, FAKE, FAKE, FAKE, None, None, FAKE, 8, None)
+        assert rc == Bd.MGRIT_ERR_PROBLEM
+    zero = Bd.mgrit_fc_layers_t(fc_period=0, Wfc=FAKE, bfc=FAKE, dWfc=None, dbfc=None)
+    rc = L.mgrit_fas_forward_mixed(ctypes.byref(conv), ctypes.byref(zero), FAKE, FAKE, FAKE, FAKE, None, None, FAKE, 8, None)
+    assert rc == Bd.MGRIT_ERR_PROBLEM
+    # the adjoint wants dWfc with dW (and dbfc with db)
+    rc = L.mgrit_fas_adjoint_mixed(ctypes.byref(conv), ctypes.byref(fc), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, None,
+                                   FAKE, 8, None)
+    assert rc == Bd.MGRIT_ERR_POINTER
+    rc = L.mgrit_fas_adjoint_mixed(ctypes.byref(conv), ctypes.byref(fc), FAKE, FAKE, FAKE, FAKE, FAKE, None, None, None, None,
+                                   FAKE, 8, None)
+    assert rc == Bd.MGRIT_ERR_WORKSPACE
+    out = ctypes.c_double()
+    rc = L.mgrit_residual_norm_mixed(ctypes.byref(conv), ctypes.byref(fc), FAKE, FAKE, FAKE, FAKE, ctypes.byref(out), FAKE, 8, None)
+    assert rc == Bd.MGRIT_ERR_WORKSPACE
+
+
+def test_fc_layers_struct_matches_header_field_order():
+    hdr = open(os.path.join(ROOT, "include", "mgrit.h")).read()
+    body = hdr[hdr.index("typedef struct mgrit_fc_layers {"):hdr.index("} mgrit_fc_layers_t;")]
+    fields = re.findall(r"([A-Za-z_]+);", body)
+    assert fields == [f[0] for f in Bd.mgrit_fc_layers_t._fields_]
+
+
 def test_inputs_are_reproducible_and_bf16_exact():
     import numpy as np
     wl = I.reduced(I.cfg5(1), q=16, B=3, N=4, m=2)

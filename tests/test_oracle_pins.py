@@ -590,6 +590,93 @@ def test_nested_start_adjoint_two_level_brute_force():
 
 
 # ---------------------------------------------------------------------------------------
+# Fully connected layers inside a convolution stack (Sec. IV-E): the kind itself, a mixed serial
+# propagation and its gradient against the float64 library routines, and the multigrid limit
+# ---------------------------------------------------------------------------------------
+def _mixed_problem(rng, N, C, B, H, Wd, P):
+    d = H * Wd * C
+    Ws, bs, kinds = [], [], []
+    for n in range(N):
+        if n % P == 0:
+            Ws.append(rng.standard_normal((d, d)) / math.sqrt(d)); bs.append(rng.standard_normal(d) * 0.3)
+            kinds.append(O.FC)
+        else:
+            Ws.append(rng.standard_normal((C, 3, 3, C)) * math.sqrt(2.0 / (9 * C)))
+            bs.append(rng.standard_normal(C) * 0.3); kinds.append(CONV)
+    return Ws, bs, kinds, rng.standard_normal((B, H, Wd, C))
+
+
+def _torch_mixed_forward(Ws, bs, kinds, x, h, f):
+    for Wn, bn, kn in zip(Ws, bs, kinds):
+        if kn == O.FC:
+            z = torch.nn.functional.linear(x.reshape(x.shape[0], -1), Wn, bn).reshape(x.shape)
+        else:
+            z = torch.nn.functional.conv2d(x.permute(0, 3, 1, 2), Wn.permute(0, 3, 1, 2), bn,
+                                           padding=1).permute(0, 2, 3, 1)
+        x = x + h * f(z)
+    return x
+
+
+@pytest.mark.parametrize("kind", [TANH, RELU])
+def test_fully_connected_step_on_an_image_state_matches_torch_linear(kind):
+    rng = np.random.default_rng(41)
+    Ws, bs, kinds, u0 = _mixed_problem(rng, 1, 3, 2, 4, 5, 1)
+    got = O.step(u0, Ws[0], bs[0], 0.3, O.FC, kind)
+    f = torch.tanh if kind == TANH else torch.relu
+    ref = _torch_mixed_forward([torch.from_numpy(Ws[0])], [torch.from_numpy(bs[0])], kinds, torch.from_numpy(u0), 0.3, f)
+    np.testing.assert_allclose(got, ref.numpy(), rtol=1e-13, atol=1e-13)
+    # flattening order is the storage order of the sample: row y, column x, channel c
+    e = np.zeros_like(u0); e[1, 2, 3, 1] = 1.0
+    z = O.affine(e, Ws[0], np.zeros_like(bs[0]), O.FC)
+    np.testing.assert_allclose(z[1].reshape(-1), Ws[0][:, (2 * 5 + 3) * 3 + 1], rtol=0, atol=0)
+    assert not z[0].any()
+
+
+def test_mixed_stack_serial_forward_and_gradient_vs_autograd():
+    rng = np.random.default_rng(42)
+    N, h, P = 7, 1.0 / 7, 3
+    Ws, bs, kinds, u0 = _mixed_problem(rng, N, 2, 2, 3, 4, P)
+    assert kinds == [O.FC, CONV, CONV, O.FC, CONV, CONV, O.FC]
+    Cw = rng.standard_normal(u0.shape)
+    U = O.serial_forward(Ws, bs, u0, h, kinds, TANH)
+    Lam, dW, db = O.serial_backward(Ws, bs, U, Cw, h, kinds, TANH)
+    Wt = [torch.tensor(w, requires_grad=True) for w in Ws]
+    bt = [torch.tensor(b, requires_grad=True) for b in bs]
+    ut = torch.tensor(u0, requires_grad=True)
+    x = _torch_mixed_forward(Wt, bt, kinds, ut, h, torch.tanh)
+    np.testing.assert_allclose(U[-1], x.detach().numpy(), rtol=1e-12, atol=1e-13)
+    (x * torch.tensor(Cw)).sum().backward()
+    for n in range(N):
+        np.testing.assert_allclose(dW[n], Wt[n].grad.numpy(), rtol=1e-10, atol=1e-13)
+        np.testing.assert_allclose(db[n], bt[n].grad.numpy(), rtol=1e-10, atol=1e-13)
+    np.testing.assert_allclose(Lam[0], ut.grad.numpy(), rtol=1e-10, atol=1e-13)
+    dW2, db2 = O.parameter_gradient(Ws, bs, U, Lam, h, kinds, TANH)
+    for n in range(N):
+        np.testing.assert_allclose(dW2[n], dW[n], rtol=1e-12, atol=1e-15)
+
+
+@pytest.mark.parametrize("P", [4, 3, 16])
+def test_mixed_stack_two_level_exactness_forward_and_adjoint(P):
+    """The fully connected layers sit on C-points (P = 4), on F-points too (P = 3), or only at layer 0."""
+    rng = np.random.default_rng(43)
+    N, m, h = 12, 4, 1.0 / 12
+    Ws, bs, kinds, u0 = _mixed_problem(rng, N, 2, 2, 3, 3, P)
+    Us = O.serial_forward(Ws, bs, u0, h, kinds, TANH)
+    U, hist, it = O.fas_forward(Ws, bs, u0, h, m, 2, 1, O.RELAX_F, N // m, kinds, TANH)
+    assert np.abs(U - Us).max() < 1e-12 and hist[-1] < hist[0]
+    U1, _, _ = O.fas_forward(Ws, bs, u0, h, m, 2, 1, O.RELAX_F, 1, kinds, TANH)
+    assert np.abs(U1[:m + 1] - Us[:m + 1]).max() < 1e-12 and np.abs(U1[-1] - Us[-1]).max() > 1e-6
+    lamN = rng.standard_normal(u0.shape)
+    Ls, dWs, dbs = O.serial_backward(Ws, bs, Us, lamN, h, kinds, TANH)
+    Lam, dW, db, _, _ = O.fas_adjoint(Ws, bs, Us, lamN, h, m, 2, 1, O.RELAX_F, N // m, kinds, TANH)
+    assert np.abs(Lam - Ls).max() < 1e-12
+    for n in range(N):
+        assert np.abs(dW[n] - dWs[n]).max() < 1e-12 and np.abs(db[n] - dbs[n]).max() < 1e-12
+    r = O.residual_norm(Ws, bs, u0, Us, h, kinds, TANH)
+    assert r < 1e-12 and O.residual_norm(Ws, bs, u0, U1, h, kinds, TANH) > 1e-6
+
+
+# ---------------------------------------------------------------------------------------
 # Stored reference of the smallest benchmark workload (written by tests/golden/make_cfg1_oracle.py)
 # ---------------------------------------------------------------------------------------
 def test_stored_cfg1_reference_is_what_the_oracle_computes_today():
