@@ -64,7 +64,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5", "mixed"])
     ap.add_argument("--cycles", type=int, default=2, help="V-cycles per forward / adjoint solve (Sec. IV-A: two)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip time-to-tolerance and serial comparisons")
@@ -82,7 +82,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    wl = I.ALL[args.workload](args.cycles)
+    wl = I.mixed(args.cycles) if args.workload == "mixed" else I.ALL[args.workload](args.cycles)
     adjoint = True
     data = I.generate(wl)
     p = M.problem_from_workload(wl)
@@ -93,8 +93,35 @@ def main():
     b = torch.from_numpy(data["b"]).to(dev)
     u0 = torch.from_numpy(data["u0"]).to(dev)
     U = torch.zeros((wl.N + 1,) + wl.state_shape, dtype=torch.float32, device=dev)
-    ws = torch.empty(M.mgrit_adjoint_workspace_bytes(p) if adjoint else M.mgrit_workspace_bytes(p),
-                     dtype=torch.uint8, device=dev)
+    # mixed stacks (periodic fully connected layers inside a convolution stack) go through the *_mixed entry
+    # points with the same arguments plus the fully connected layers' arrays
+    mixed = wl.fc_period > 0
+    fc = None
+    if mixed:
+        Wfc = torch.from_numpy(data["Wfc"]).to(dev)
+        if wl.dtype == I.BF16:
+            Wfc = Wfc.to(torch.bfloat16)
+        bfc = torch.from_numpy(data["bfc"]).to(dev)
+        dWfc = torch.zeros(Wfc.shape, dtype=torch.float32, device=dev)
+        dbfc = torch.zeros_like(bfc)
+        fc = M.make_fc_layers(wl.fc_period, Wfc, bfc, dWfc, dbfc)
+
+    def ws_bytes(pp, adj):
+        if mixed:
+            return (M.mgrit_adjoint_workspace_bytes_mixed if adj else M.mgrit_workspace_bytes_mixed)(pp, wl.fc_period)
+        return (M.mgrit_adjoint_workspace_bytes if adj else M.mgrit_workspace_bytes)(pp)
+
+    def FWD(pp, Wx, bx, wsx, **kw):
+        if mixed:
+            return M.mgrit_fas_forward_mixed(pp, fc, Wx, bx, u0, U, wsx, **kw)
+        return M.mgrit_fas_forward(pp, Wx, bx, u0, U, wsx, **kw)
+
+    def ADJ(pp, wsx, **kw):
+        if mixed:
+            return M.mgrit_fas_adjoint_mixed(pp, fc, W, b, U, lamN, Lam, dW, db, wsx, **kw)
+        return M.mgrit_fas_adjoint(pp, W, b, U, lamN, Lam, dW, db, wsx, **kw)
+
+    ws = torch.empty(ws_bytes(p, adjoint), dtype=torch.uint8, device=dev)
     if adjoint:
         rng = np.random.default_rng(1)
         if wl.head_classes:
@@ -109,12 +136,12 @@ def main():
             lamN.copy_(torch.from_numpy(lamN_np))
 
     def step():
-        M.mgrit_fas_forward(p, W, b, u0, U, ws, want_hist=False)
+        FWD(p, W, b, ws, want_hist=False)
         if adjoint:
-            M.mgrit_fas_adjoint(p, W, b, U, lamN, Lam, dW, db, ws, want_hist=False)
+            ADJ(p, ws, want_hist=False)
 
     if adjoint and wl.head_classes:       # terminal adjoint of the softmax head from a first forward solve
-        M.mgrit_fas_forward(p, W, b, u0, U, ws, want_hist=False)
+        FWD(p, W, b, ws, want_hist=False)
         torch.cuda.synchronize()
         lamN.copy_(torch.from_numpy(I.terminal_adjoint(wl, data, U[-1].cpu().numpy())))
 
@@ -151,6 +178,9 @@ def main():
     else:
         flops_per_unit = 2.0 * wl.B * wl.Himg * wl.Wimg * wl.C * 9 * wl.C
         bytes_per_unit = 9 * wl.C * wl.C * (4 if wl.dtype == I.FP32 else 2) + 2 * wl.E * 4
+    if mixed and dom.startswith("dense"):      # the fully connected layers' launches dominate
+        flops_per_unit = 2.0 * wl.B * wl.d_fc * wl.d_fc
+        bytes_per_unit = wl.d_fc * wl.d_fc * (4 if wl.dtype == I.FP32 else 2) + 2 * wl.E * 4
     peak_mfma = PEAK["fp32_mfma"] if wl.dtype == I.FP32 else PEAK["bf16_mfma"]
     avg_us = ms_tot * 1e3 / launches
     tflops = units * flops_per_unit / (ms_tot * 1e-3) / 1e12
@@ -195,17 +225,17 @@ def main():
             return float(np.median(ts))
 
         p_tol = M.problem_from_workload(wl, max_iter=40, tol=1e-6, norm_kind=1)
-        ws_tol = torch.empty(M.mgrit_workspace_bytes(p_tol), dtype=torch.uint8, device=dev)
+        ws_tol = torch.empty(ws_bytes(p_tol, False), dtype=torch.uint8, device=dev)
         res = {}
 
         def solve_tol():
-            res["r"] = M.mgrit_fas_forward(p_tol, W, b, u0, U, ws_tol)
+            res["r"] = FWD(p_tol, W, b, ws_tol)
         t_tol = timed(solve_tol, 5)
         p_ser = M.problem_from_workload(wl, max_levels=1)
-        t_ser = timed(lambda: M.mgrit_fas_forward(p_ser, W, b, u0, U, ws_tol, want_hist=False))
+        t_ser = timed(lambda: FWD(p_ser, W, b, ws_tol, want_hist=False))
         p_one = M.problem_from_workload(wl, max_iter=1)
-        t_one = timed(lambda: M.mgrit_fas_forward(p_one, W, b, u0, U, ws, want_hist=False))
-        t_two = timed(lambda: M.mgrit_fas_forward(p, W, b, u0, U, ws, want_hist=False))
+        t_one = timed(lambda: FWD(p_one, W, b, ws, want_hist=False))
+        t_two = timed(lambda: FWD(p, W, b, ws, want_hist=False))
         # nested-iteration start against the copy start, on this workload's independent random layers
         # and on the same shapes with parameters that vary smoothly with depth
         nested = {}
@@ -220,7 +250,7 @@ def main():
                 r = {}
 
                 def run():
-                    r["r"] = M.mgrit_fas_forward(p_i, Wx, bx, u0, U, ws_tol)
+                    r["r"] = FWD(p_i, Wx, bx, ws_tol)
                 t_i = timed(run, 3)
                 nested["%s_%s" % (tag, iname)] = {"cycles": r["r"][2], "ms": round(t_i, 3),
                                                   "first_rms_residual": r["r"][1][0]}
@@ -231,17 +261,17 @@ def main():
         grad_err = {}
         if adjoint:
             p_ser_a = M.problem_from_workload(wl, max_levels=1)
-            M.mgrit_fas_forward(p_ser_a, W, b, u0, U, ws, want_hist=False)
-            M.mgrit_fas_adjoint(p_ser_a, W, b, U, lamN, Lam, dW, db, ws, want_hist=False)
+            FWD(p_ser_a, W, b, ws, want_hist=False)
+            ADJ(p_ser_a, ws, want_hist=False)
             torch.cuda.synchronize()
             ref_n = float(torch.linalg.vector_norm(dW.double()))
             dW_ref = dW.clone()
-            t_ser_train = timed(lambda: (M.mgrit_fas_forward(p_ser_a, W, b, u0, U, ws, want_hist=False),
-                                         M.mgrit_fas_adjoint(p_ser_a, W, b, U, lamN, Lam, dW, db, ws, want_hist=False)), 3)
+            t_ser_train = timed(lambda: (FWD(p_ser_a, W, b, ws, want_hist=False),
+                                         ADJ(p_ser_a, ws, want_hist=False)), 3)
             for k in (1, 2, 3, 4):
                 p_k = M.problem_from_workload(wl, max_iter=k)
-                M.mgrit_fas_forward(p_k, W, b, u0, U, ws, want_hist=False)
-                M.mgrit_fas_adjoint(p_k, W, b, U, lamN, Lam, dW, db, ws, want_hist=False)
+                FWD(p_k, W, b, ws, want_hist=False)
+                ADJ(p_k, ws, want_hist=False)
                 torch.cuda.synchronize()
                 grad_err[str(k)] = float(torch.linalg.vector_norm((dW - dW_ref).double())) / ref_n
             del dW_ref
@@ -268,6 +298,8 @@ def main():
         # cycle count) cut to its first Ns layers and, if one pass is still too long, to its first Bs samples;
         # if one pass is short it is repeated.  Layer steps are counted as for the GPU, scaled by Bs / B.
         flop_step = 2.0 * wl.E * (wl.q if wl.layer == I.DENSE else 9 * wl.C)       # one layer step, whole batch
+        if mixed:
+            flop_step += 2.0 * wl.B * wl.d_fc * wl.d_fc / wl.fc_period              # share of the fully connected layers
         budget = 4.0e12 if wl.layer == I.DENSE else 5.0e11                          # flops of oracle work aimed at
         per_layer = 3.2 * cyc_factor(adjoint) * args.cycles
         Ns, unit, Bs = wl.N, wl.m ** (len(sizes) - 1), wl.B
@@ -278,6 +310,9 @@ def main():
             Bs //= 2
         sizes_s = O.level_sizes(Ns, wl.m, wl.max_levels, wl.min_coarse)
         Ws, bs, u0s = data["W"][:Ns], data["b"][:Ns], data["u0"][:Bs]
+        kinds = wl.layer
+        if mixed:
+            Ws, bs, kinds = I.per_layer_lists(I.reduced(wl, N=Ns), data)
         cyc = args.cycles
         n_cpu = layer_steps_per_solve(sizes_s, wl.m, wl.relax, cyc)   # counted as for the GPU
         sample = "first %d of %d layers, first %d of %d samples, forward solve of %d cycle(s)" % (Ns, wl.N, Bs, wl.B, cyc)
@@ -289,10 +324,10 @@ def main():
         reps, want = 0, 1
         while reps < want:
             Uo, _, _ = O.fas_forward(Ws, bs, u0s, wl.h, wl.m, wl.max_levels, wl.min_coarse,
-                                     wl.relax, cyc, wl.layer, wl.act)
+                                     wl.relax, cyc, kinds, wl.act)
             if adjoint:
                 O.fas_adjoint(Ws, bs, Uo, lam_np, wl.h, wl.m, wl.max_levels, wl.min_coarse, wl.relax,
-                              cyc, wl.layer, wl.act)
+                              cyc, kinds, wl.act)
             reps += 1
             if reps == 1:                                          # short pass: repeat it up to about 12 s in all
                 want = int(min(50, max(1, 12.0 // max(time.perf_counter() - a, 1e-3))))

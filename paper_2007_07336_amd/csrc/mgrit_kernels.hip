@@ -985,7 +985,9 @@ hipError_t launch_step(const StepArgs& a_in, int layer_kind, int dtype, int grou
     }
   }
   const hipError_t e = hipGetLastError();
-  trace_after(s, cls, groups);
+  int worked = groups;                 // groups that did a layer step (a mixed stack's convolution launch skips some)
+  if (layer_kind == 1 && a.skipper > 0 && a.skip0 < groups) worked -= (groups - 1 - a.skip0) / a.skipper + 1;
+  trace_after(s, cls, worked);
   return e;
 }
 

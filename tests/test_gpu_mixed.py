@@ -162,3 +162,51 @@ def test_mixed_adjoint_and_gradient(wl):
         else:
             eW, eb = rel_l2_per_state(dW[n][None], dWo[n][None]), rel_l2_per_state(db[n][None], dbo[n][None])
         assert eW <= tol and eb <= tol, (n, eW, eb)
+
+
+# ------------------------------------------------------------------ the benchmark's mixed workload at full size
+def test_mixed_full_size_forward_elementwise():
+    wl = I.mixed(2)
+    _announce(wl.name)
+    data = I.generate(wl)
+    gp = GpuMixed(wl, data)
+    U, hist, it = gp.forward()
+    Uo, hist_o, _ = _oracle_forward(wl, data)
+    err = rel_l2_per_state(U, Uo)
+    print(f"mixed forward: {err:.3e}  residuals {hist} vs {hist_o}", flush=True)
+    assert err <= 1e-5, err
+    for a, b in zip(hist, hist_o):
+        assert abs(a - b) <= 1e-3 * b
+
+
+def test_mixed_full_size_adjoint_elementwise():
+    """ReLU' is a 0/1 decision on the sign of z, so both sides must see the same z: weights (steps of 2^-7 below
+    1/2), biases (steps of 2^-12) and the states to linearise about (steps of 2^-5 below 2) are put on binary
+    grids on which every product and every partial sum of z -- 144 terms in a convolution layer, 4096 in a fully
+    connected one -- is exact in float32 in any order."""
+    wl = I.mixed(2)
+    _announce(wl.name + " adjoint + gradient")
+    data = dict(I.generate(wl))
+    for k in ("W", "Wfc"):
+        data[k] = (np.clip(np.round(data[k] * 128.0), -63, 63) / 128.0).astype(np.float32)
+    for k in ("b", "bfc"):
+        data[k] = (np.round(data[k] * 4096.0) / 4096.0).astype(np.float32)
+    Ws, bs, kinds = I.per_layer_lists(wl, data)
+    Uo, _, _ = _oracle_forward(wl, data)
+    U = (np.clip(np.round(Uo * 32.0), -63, 63) / 32.0).astype(np.float32)
+    del Uo
+    lamN = (np.random.default_rng(21).standard_normal(wl.state_shape) / wl.B).astype(np.float32)
+    gp = GpuMixed(wl, data)
+    Lam, dW, db, dWfc, dbfc, hist, it = gp.adjoint(U, lamN)
+    Lo, dWo, dbo, hist_o, _ = O.fas_adjoint(Ws, bs, U, lamN, wl.h, wl.m, wl.max_levels, wl.min_coarse, wl.relax,
+                                            wl.max_iter, kinds, wl.act)
+    eL = rel_l2_per_state(Lam, Lo)
+    P = wl.fc_period
+    conv = [n for n in range(wl.N) if n % P]
+    eW = rel_l2_per_state(dW[conv], np.stack([dWo[n] for n in conv]))
+    eb = rel_l2_per_state(db[conv], np.stack([dbo[n] for n in conv]))
+    eWf = rel_l2_per_state(dWfc, np.stack([dWo[n] for n in range(0, wl.N, P)]))
+    ebf = rel_l2_per_state(dbfc, np.stack([dbo[n] for n in range(0, wl.N, P)]))
+    print(f"mixed adjoint: Lam {eL:.3e}  dW {eW:.3e}  db {eb:.3e}  dWfc {eWf:.3e}  dbfc {ebf:.3e}", flush=True)
+    assert max(eL, eW, eb, eWf, ebf) <= 1e-5
+    assert not dW[::P].any() and not db[::P].any()
