@@ -171,7 +171,7 @@ def main():
     torch.cuda.synchronize()
     step_classes = {k: v for k, v in tr.items() if k != "dense_grad_kernel"}
     dom = max(step_classes, key=lambda k: step_classes[k][0])
-    ms_tot, launches, units = step_classes[dom]
+    ms_tot, launches, units, alg_bytes = step_classes[dom]
     if wl.layer == I.DENSE:
         flops_per_unit = 2.0 * wl.B * wl.q * wl.q
         bytes_per_unit = wl.q * wl.q * (4 if wl.dtype == I.FP32 else 2) + 2 * wl.B * wl.q * 4
@@ -184,9 +184,13 @@ def main():
     peak_mfma = PEAK["fp32_mfma"] if wl.dtype == I.FP32 else PEAK["bf16_mfma"]
     avg_us = ms_tot * 1e3 / launches
     tflops = units * flops_per_unit / (ms_tot * 1e-3) / 1e12
-    gbps = units * bytes_per_unit / (ms_tot * 1e-3) / 1e9
+    # algorithmic bytes: the library's launch trace sums, per layer step, weights and bias, the input state, every
+    # fused epilogue operand (residual and right-hand-side launches read one or two more states), the act' factor
+    # of the adjoint and the output, each once; bytes_per_unit is the bare step (weights, state in, state out)
+    gbps = alg_bytes / (ms_tot * 1e-3) / 1e9
+    gbps_bare = units * bytes_per_unit / (ms_tot * 1e-3) / 1e9
     # the roof that binds is the one that takes longer for this kernel's flops and algorithmic bytes
-    hbm_bound = bytes_per_unit / (PEAK["hbm_GBps"] * 1e9) > flops_per_unit / (peak_mfma * 1e12)
+    hbm_bound = alg_bytes / (PEAK["hbm_GBps"] * 1e9) > units * flops_per_unit / (peak_mfma * 1e12)
     roofline = {"bound": "hbm" if hbm_bound else "mfma", "kernel": dom,
                 "achieved": round(gbps if hbm_bound else tflops, 3),
                 "peak": PEAK["hbm_GBps"] if hbm_bound else peak_mfma,
@@ -195,7 +199,9 @@ def main():
                 "traffic": TRAFFIC_BYTES.get((args.workload, dom)),
                 "launches": launches, "avg_launch_us": round(avg_us, 3),
                 "flops_per_launch": units * flops_per_unit / launches,
-                "algorithmic_bytes_per_launch": units * bytes_per_unit / launches,
+                "algorithmic_bytes_per_launch": alg_bytes / launches,
+                "bare_step_bytes_per_launch": units * bytes_per_unit / launches,
+                "hbm_GBps_bare_step": round(gbps_bare, 1),
                 "mfma_TFLOPs": round(tflops, 3), "mfma_frac": round(tflops / peak_mfma, 5),
                 "hbm_GBps_algorithmic": round(gbps, 1), "hbm_frac": round(gbps / PEAK["hbm_GBps"], 5),
                 "all_kernels_ms": {k: round(v[0] / args.steps, 4) for k, v in tr.items()}}

@@ -184,8 +184,10 @@ int32_t mgrit_residual_norm_mixed(const mgrit_problem_t* p, const mgrit_fc_layer
 /* Diagnostic launch tracing, off by default and the one piece of state the library keeps: between
  * mgrit_trace_begin() and mgrit_trace_end() every layer-step and gradient launch is bracketed by a
  * pair of HIP events on its stream.  mgrit_trace_end synchronises on the last event and returns,
- * per kernel class (MGRIT_TRACE_*), the summed elapsed milliseconds, the number of launches and the
- * number of layer steps (groups) they processed; arrays of n_classes entries, host.  Not thread
+ * per kernel class (MGRIT_TRACE_*), the summed elapsed milliseconds, the number of launches, the
+ * number of layer steps (groups) they processed and (bytes, may be NULL) their algorithmic bytes --
+ * per layer step the layer's weights and bias, the input state, every fused epilogue operand, the
+ * act' factor and the output, each moved once; arrays of n_classes entries, host.  Not thread
  * safe; meant for the benchmark's roofline figures (Sec. IV-B reports such a timeline). */
 enum {
   MGRIT_TRACE_DENSE_F32_T64 = 0, MGRIT_TRACE_DENSE_F32_T128, MGRIT_TRACE_DENSE_BF16_T64,
@@ -194,7 +196,7 @@ enum {
   MGRIT_TRACE_DENSE_F32_KSPLIT, MGRIT_TRACE_DENSE_BF16_KSPLIT, MGRIT_TRACE_NCLASS
 };
 void    mgrit_trace_begin(void);
-int32_t mgrit_trace_end(double* ms, int64_t* launches, int64_t* units, int32_t n_classes);
+int32_t mgrit_trace_end(double* ms, int64_t* launches, int64_t* units, double* bytes, int32_t n_classes);
 
 #ifdef __cplusplus
 }

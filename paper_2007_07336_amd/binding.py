@@ -80,7 +80,7 @@ def lib() -> ctypes.CDLL:
         L.mgrit_residual_norm_mixed.restype = ctypes.c_int32
         L.mgrit_trace_begin.argtypes = []
         L.mgrit_trace_begin.restype = None
-        L.mgrit_trace_end.argtypes = [dp, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64),
+        L.mgrit_trace_end.argtypes = [dp, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64), dp,
                                       ctypes.c_int32]
         L.mgrit_trace_end.restype = ctypes.c_int32
         _lib = L
@@ -240,12 +240,14 @@ def mgrit_trace_begin() -> None:
 
 
 def mgrit_trace_end() -> dict:
-    """{kernel class: (total ms, launches, layer steps)} of the launches since mgrit_trace_begin()."""
+    """{kernel class: (total ms, launches, layer steps, algorithmic bytes)} of the launches since
+    mgrit_trace_begin()."""
     n = len(TRACE_CLASSES)
     ms = (ctypes.c_double * n)()
     la = (ctypes.c_int64 * n)()
     un = (ctypes.c_int64 * n)()
-    rc = lib().mgrit_trace_end(ms, la, un, n)
+    by = (ctypes.c_double * n)()
+    rc = lib().mgrit_trace_end(ms, la, un, by, n)
     if rc != MGRIT_OK:
         raise MgritError(rc, "mgrit_trace_end")
-    return {TRACE_CLASSES[i]: (ms[i], la[i], un[i]) for i in range(n) if la[i] > 0}
+    return {TRACE_CLASSES[i]: (ms[i], la[i], un[i], by[i]) for i in range(n) if la[i] > 0}

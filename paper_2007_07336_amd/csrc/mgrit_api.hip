@@ -693,15 +693,16 @@ int32_t mgrit_residual_norm_mixed(const mgrit_problem_t* p, const mgrit_fc_layer
 
 void mgrit_trace_begin(void) { trace_begin(); }
 
-int32_t mgrit_trace_end(double* ms, int64_t* launches, int64_t* units, int32_t n_classes) {
+int32_t mgrit_trace_end(double* ms, int64_t* launches, int64_t* units, double* bytes, int32_t n_classes) {
   if (!ms || !launches || !units || n_classes < 1) return MGRIT_ERR_POINTER;
   long long l[TRACE_NCLASS], u[TRACE_NCLASS];
-  double m[TRACE_NCLASS];
-  if (trace_end(m, l, u, TRACE_NCLASS) != 0) return MGRIT_ERR_HIP;
+  double m[TRACE_NCLASS], b[TRACE_NCLASS];
+  if (trace_end(m, l, u, b, TRACE_NCLASS) != 0) return MGRIT_ERR_HIP;
   for (int i = 0; i < n_classes; ++i) {
     ms[i] = i < TRACE_NCLASS ? m[i] : 0.0;
     launches[i] = i < TRACE_NCLASS ? l[i] : 0;
     units[i] = i < TRACE_NCLASS ? u[i] : 0;
+    if (bytes) bytes[i] = i < TRACE_NCLASS ? b[i] : 0.0;
   }
   return MGRIT_OK;
 }

@@ -274,7 +274,7 @@ hipError_t launch_chain(const ChainArgs& a, int dtype, hipStream_t s) {
     trace_before(s);
     hipLaunchKernelGGL((dense_chain_kernel<float>), dim3(blocks), dim3(NT), smem, s, a);
     e = hipGetLastError();
-    trace_after(s, TRACE_CHAIN_F32, (long long)a.nchains * a.nsteps);
+    trace_after(s, TRACE_CHAIN_F32, (long long)a.nchains * a.nsteps, 0.0);
   } else {
     if (smem > 48 * 1024) {
       e = hipFuncSetAttribute(reinterpret_cast<const void*>(dense_chain_kernel<__bf16>),
@@ -284,7 +284,7 @@ hipError_t launch_chain(const ChainArgs& a, int dtype, hipStream_t s) {
     trace_before(s);
     hipLaunchKernelGGL((dense_chain_kernel<__bf16>), dim3(blocks), dim3(NT), smem, s, a);
     e = hipGetLastError();
-    trace_after(s, TRACE_CHAIN_BF16, (long long)a.nchains * a.nsteps);
+    trace_after(s, TRACE_CHAIN_BF16, (long long)a.nchains * a.nsteps, 0.0);
   }
   return e;
 }

@@ -147,8 +147,8 @@ enum { TRACE_DENSE_F32_64 = 0, TRACE_DENSE_F32_128, TRACE_DENSE_BF16_64, TRACE_D
        TRACE_CONV_F32, TRACE_CONV_BF16, TRACE_GRAD, TRACE_CHAIN_F32, TRACE_CHAIN_BF16, TRACE_DENSE_BF16_256,
        TRACE_DENSE_F32_KS, TRACE_DENSE_BF16_KS, TRACE_NCLASS };
 void trace_begin();
-int  trace_end(double* ms, long long* launches, long long* units, int ncls);
+int  trace_end(double* ms, long long* launches, long long* units, double* bytes, int ncls);
 void trace_before(hipStream_t s);
-void trace_after(hipStream_t s, int cls, long long units);
+void trace_after(hipStream_t s, int cls, long long units, double bytes);
 
 }  // namespace mgrit

@@ -25,6 +25,7 @@ struct Trace {
   std::vector<hipEvent_t> ev;       // pairs
   std::vector<int> cls;
   std::vector<long long> units;
+  std::vector<double> bytes;        // algorithmic bytes of the launch (every operand moved once)
   size_t used = 0;                  // pairs in use
 } g_trace;
 
@@ -40,26 +41,29 @@ void trace_before(hipStream_t s) {
   }
   (void)hipEventRecord(g_trace.ev[g_trace.used * 2], s);
 }
-void trace_after(hipStream_t s, int cls, long long units) {
+void trace_after(hipStream_t s, int cls, long long units, double bytes) {
   if (!g_trace.on) return;
   (void)hipEventRecord(g_trace.ev[g_trace.used * 2 + 1], s);
-  if (g_trace.cls.size() <= g_trace.used) { g_trace.cls.resize(g_trace.used + 1); g_trace.units.resize(g_trace.used + 1); }
+  if (g_trace.cls.size() <= g_trace.used) {
+    g_trace.cls.resize(g_trace.used + 1); g_trace.units.resize(g_trace.used + 1); g_trace.bytes.resize(g_trace.used + 1);
+  }
   g_trace.cls[g_trace.used] = cls;
   g_trace.units[g_trace.used] = units;
+  g_trace.bytes[g_trace.used] = bytes;
   ++g_trace.used;
 }
 
 void trace_begin() { g_trace.on = true; g_trace.used = 0; }
-int trace_end(double* ms, long long* launches, long long* units, int ncls) {
+int trace_end(double* ms, long long* launches, long long* units, double* bytes, int ncls) {
   g_trace.on = false;
-  for (int i = 0; i < ncls; ++i) { ms[i] = 0.0; launches[i] = 0; units[i] = 0; }
+  for (int i = 0; i < ncls; ++i) { ms[i] = 0.0; launches[i] = 0; units[i] = 0; bytes[i] = 0.0; }
   if (g_trace.used == 0) return 0;
   if (hipEventSynchronize(g_trace.ev[g_trace.used * 2 - 1]) != hipSuccess) return -1;
   for (size_t i = 0; i < g_trace.used; ++i) {
     float t = 0.0f;
     if (hipEventElapsedTime(&t, g_trace.ev[2 * i], g_trace.ev[2 * i + 1]) != hipSuccess) return -1;
     const int c = g_trace.cls[i];
-    if (c >= 0 && c < ncls) { ms[c] += t; launches[c] += 1; units[c] += g_trace.units[i]; }
+    if (c >= 0 && c < ncls) { ms[c] += t; launches[c] += 1; units[c] += g_trace.units[i]; bytes[c] += g_trace.bytes[i]; }
   }
   g_trace.used = 0;
   return 0;
@@ -987,7 +991,15 @@ hipError_t launch_step(const StepArgs& a_in, int layer_kind, int dtype, int grou
   const hipError_t e = hipGetLastError();
   int worked = groups;                 // groups that did a layer step (a mixed stack's convolution launch skips some)
   if (layer_kind == 1 && a.skipper > 0 && a.skip0 < groups) worked -= (groups - 1 - a.skip0) / a.skipper + 1;
-  trace_after(s, cls, worked);
+  // algorithmic bytes: per layer step the layer's weights and bias once, the input state, every fused epilogue
+  // operand and the act' factor once, the output once
+  const double es = dtype == 0 ? 4.0 : 2.0;
+  double per = (double)a.wsize * es + (a.bias ? 4.0 * a.Nf : 0.0) + 4.0 * (double)a.E;
+  if (a.E1 && a.c1 != 0.0f) per += 4.0 * (double)a.E;
+  if (a.E2 && a.c2 != 0.0f) per += 4.0 * (double)a.E;
+  if (a.Dm) per += es * (double)a.E;
+  if (a.Out) per += (a.mode == MODE_DACT ? es : 4.0) * (double)a.E;
+  trace_after(s, cls, worked, per * worked);
   return e;
 }
 
@@ -1687,7 +1699,7 @@ hipError_t launch_grad(const GradArgs& a_in, int layer_kind, int dtype, int grou
                        : launch_conv_grad<__bf16, TM_, TN_>(a, blocks, gm.smem, s);
       MGRIT_CG(1, 1) MGRIT_CG(1, 2) MGRIT_CG(1, 3) MGRIT_CG(2, 3) MGRIT_CG(2, 4) MGRIT_CG(2, 5)
 #undef MGRIT_CG
-      if (e != hipSuccess) { trace_after(s, TRACE_GRAD, groups); return e; }
+      if (e != hipSuccess) { trace_after(s, TRACE_GRAD, groups, 0.0); return e; }
       if (gm.chunks > 1) {
         const long long total4 = (long long)groups * (a.wsize + a.Nf) / 4;
         long long nb = (total4 + NT - 1) / NT;
@@ -1699,7 +1711,10 @@ hipError_t launch_grad(const GradArgs& a_in, int layer_kind, int dtype, int grou
   }
   if (a.db && layer_kind == 0) launch_bias_grad(a, dtype, groups, s);
   const hipError_t e = hipGetLastError();
-  trace_after(s, TRACE_GRAD, groups);
+  // algorithmic bytes of a layer's gradient: U, Lam and the act' factors in, dW and db out
+  const double ges = dtype == 0 ? 4.0 : 2.0;
+  trace_after(s, TRACE_GRAD, groups,
+              (double)groups * ((8.0 + ges) * (double)a.E + (a.dW ? 4.0 * (double)a.wsize : 0.0) + (a.db ? 4.0 * a.Nf : 0.0)));
   return e;
 }
 
