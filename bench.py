@@ -64,7 +64,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5", "mixed"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5", "mixed", "mixed_bf16"])
     ap.add_argument("--cycles", type=int, default=2, help="V-cycles per forward / adjoint solve (Sec. IV-A: two)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip time-to-tolerance and serial comparisons")
@@ -82,7 +82,10 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    wl = I.mixed(args.cycles) if args.workload == "mixed" else I.ALL[args.workload](args.cycles)
+    if args.workload.startswith("mixed"):
+        wl = I.mixed(args.cycles, I.BF16 if args.workload == "mixed_bf16" else I.FP32)
+    else:
+        wl = I.ALL[args.workload](args.cycles)
     adjoint = True
     data = I.generate(wl)
     p = M.problem_from_workload(wl)

@@ -208,11 +208,11 @@ def cfg5(max_iter: int = 2) -> Workload:
                     head_classes=10)
 
 
-def mixed(max_iter: int = 2) -> Workload:
+def mixed(max_iter: int = 2, dtype: int = FP32) -> Workload:
     """Blocks of one fully connected layer followed by 63 convolution layers (the shape of the paper's second
-    training network, Sec. IV-E, at a size one GPU's oracle check can follow)."""
-    return Workload("mixed_conv_c16_16x16_fc64_N256", CONV, RELU, FP32, N=256, m=4, max_levels=3,
-                    relax=RELAX_FCF, max_iter=max_iter, B=32, C=16, Himg=16, Wimg=16, fc_period=64)
+    training network, Sec. IV-E, at a size one GPU's oracle check can follow); float or bf16 operands."""
+    return Workload("mixed_conv_c16_16x16_fc64_N256" + ("_bf16" if dtype == BF16 else ""), CONV, RELU, dtype, N=256,
+                    m=4, max_levels=3, relax=RELAX_FCF, max_iter=max_iter, B=32, C=16, Himg=16, Wimg=16, fc_period=64)
 
 
 def reduced(wl: Workload, **kw) -> Workload:

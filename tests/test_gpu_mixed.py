@@ -210,3 +210,36 @@ def test_mixed_full_size_adjoint_elementwise():
     print(f"mixed adjoint: Lam {eL:.3e}  dW {eW:.3e}  db {eb:.3e}  dWfc {eWf:.3e}  dbfc {ebf:.3e}", flush=True)
     assert max(eL, eW, eb, eWf, ebf) <= 1e-5
     assert not dW[::P].any() and not db[::P].any()
+
+
+def test_mixed_full_size_bf16_forward_and_adjoint_elementwise():
+    """The same stack with bf16 operands (weights stored in bf16, states float): element by element at the bf16
+    tolerance; the states to linearise about are bf16-representable so that both sides take every ReLU' decision
+    on the same operand."""
+    wl = I.mixed(2, I.BF16)
+    _announce(wl.name)
+    data = I.generate(wl)
+    Ws, bs, kinds = I.per_layer_lists(wl, data)
+    gp = GpuMixed(wl, data)
+    U, hist, it = gp.forward()
+    Uo, hist_o, _ = _oracle_forward(wl, data)
+    err = rel_l2_per_state(U, Uo)
+    inc = rel_l2_per_state(U[1:] - U[:-1], Uo[1:] - Uo[:-1])
+    print(f"mixed bf16 forward: states {err:.3e}  increments {inc:.3e}", flush=True)
+    assert err <= 2e-2 and it == 2
+    for a, b in zip(hist, hist_o):
+        assert abs(a - b) <= 5e-2 * b
+    Ul = I.round_to_bf16(Uo.astype(np.float32))
+    del Uo, U
+    lamN = (np.random.default_rng(21).standard_normal(wl.state_shape) / wl.B).astype(np.float32)
+    Lam, dW, db, dWfc, dbfc, _, _ = gp.adjoint(Ul, lamN)
+    Lo, dWo, dbo, _, _ = O.fas_adjoint(Ws, bs, Ul, lamN, wl.h, wl.m, wl.max_levels, wl.min_coarse, wl.relax,
+                                       wl.max_iter, kinds, wl.act)
+    P = wl.fc_period
+    conv = [n for n in range(wl.N) if n % P]
+    errs = (rel_l2_per_state(Lam, Lo), rel_l2_per_state(dW[conv], np.stack([dWo[n] for n in conv])),
+            rel_l2_per_state(db[conv], np.stack([dbo[n] for n in conv])),
+            rel_l2_per_state(dWfc, np.stack([dWo[n] for n in range(0, wl.N, P)])),
+            rel_l2_per_state(dbfc, np.stack([dbo[n] for n in range(0, wl.N, P)])))
+    print("mixed bf16 adjoint: Lam %.3e dW %.3e db %.3e dWfc %.3e dbfc %.3e" % errs, flush=True)
+    assert max(errs) <= 2e-2
