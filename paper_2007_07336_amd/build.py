@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libmgrit.so")
-SOURCES = ["mgrit_api.hip", "mgrit_kernels.hip", "mgrit_chain.hip"]
+SOURCES = ["mgrit_api.hip", "mgrit_kernels.hip"]
 
 
 def hipcc() -> str:

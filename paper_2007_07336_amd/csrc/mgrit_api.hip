@@ -17,10 +17,12 @@ constexpr size_t ALIGN = 256;
 inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 inline bool aligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) % ALIGN) == 0; }
 
-// The temporally fused chain kernels (mgrit_chain.hip) are switched OFF: their first run on the
-// GPU ended in a memory fault whose cause has not been found (the index arithmetic of schedule and
-// kernel is clean under AddressSanitizer in a CPU build).  Until a cause is shown they stay off.
-inline bool chain_enabled() { return false; }
+// The fused F-relaxation sweep (one launch per sweep instead of one per step) can be switched off with
+// MGRIT_NO_SWEEP=1 in the environment; the tests run both ways.
+inline bool sweep_enabled() {
+  const char* e = getenv("MGRIT_NO_SWEEP");
+  return !(e && e[0] == '1');
+}
 
 struct Plan {
   int L;
@@ -30,8 +32,7 @@ struct Plan {
   long long E, wsize;
   int M, Nf, K, TH;
   size_t esize;                        // bytes per weight element
-  size_t off_X[MGRIT_MAX_LEVELS], off_g[MGRIT_MAX_LEVELS], off_R[MGRIT_MAX_LEVELS], off_C[MGRIT_MAX_LEVELS];
-  bool chain_fwd, chain_adj;           // dense layers: temporally fused chain kernels usable
+  size_t off_X[MGRIT_MAX_LEVELS], off_g[MGRIT_MAX_LEVELS], off_R[MGRIT_MAX_LEVELS];
   size_t off_partial, n_partial, off_hist, off_Wt, off_D, off_gpart;
   size_t bytes_fwd, bytes_adj;
   // mixed stacks (Sec. IV-E): every fcP-th layer is fully connected on the flattened sample; 0 = none
@@ -110,11 +111,7 @@ int make_plan(const mgrit_problem_t* p, Plan* pl, int fcP = 0) {
   }
   for (int l = 0; l + 1 < pl->L; ++l) {
     pl->off_R[l] = off; off = align_up(off + (size_t)(pl->Nl[l + 1] + 1) * pl->E * 4);
-    pl->off_C[l] = off;                // C-relaxation results of the fused dense sweeps
-    if (p->layer == MGRIT_LAYER_DENSE && chain_enabled()) off = align_up(off + (size_t)(pl->Nl[l + 1] + 1) * pl->E * 4);
   }
-  pl->chain_fwd = p->layer == MGRIT_LAYER_DENSE && chain_supported(p->q, p->dtype, false);
-  pl->chain_adj = p->layer == MGRIT_LAYER_DENSE && chain_supported(p->q, p->dtype, true);
   StepArgs a;
   memset(&a, 0, sizeof(a));
   a.M = pl->M; a.Nf = pl->Nf; a.K = pl->K; a.Himg = p->Himg; a.Wimg = p->Wimg; a.TH = pl->TH;
@@ -123,10 +120,6 @@ int make_plan(const mgrit_problem_t* p, Plan* pl, int fcP = 0) {
   if (pl->L > 1) {
     size_t np1 = (size_t)step_grid_blocks(a, p->layer, p->dtype, pl->Nl[1]) * pl->Nl[1];
     if (np1 > np) np = np1;
-    if (p->layer == MGRIT_LAYER_DENSE) {
-      const size_t npc = (size_t)chain_blocks(pl->M, pl->Nl[1]);
-      if (npc > np) np = npc;
-    }
   }
   if (fcP)     // the dense launch of the fully connected groups adds its workgroups (at most 32x32 tiles of each)
     np += (size_t)((p->B + 31) / 32) * (size_t)((pl->dfc + 31) / 32) * (size_t)pl->nfc;
@@ -158,8 +151,6 @@ struct Solver {
   float* X[MGRIT_MAX_LEVELS];
   float* g[MGRIT_MAX_LEVELS];
   float* R[MGRIT_MAX_LEVELS];
-  float* Cb[MGRIT_MAX_LEVELS];
-  bool use_chain = false;
   bool plain_rhs = false;              // nested start: every level carries the right-hand side (first, 0, .., 0)
   const void* W;
   const float* bias;
@@ -257,74 +248,34 @@ struct Solver {
     if (g[l] && !plain_rhs) { a.E1 = g[l]; a.e1m = PtMap{js0, jstride}; a.c1 = 1.0f; }
     launch(a, groups);
   }
+  // One fused launch per F-relaxation sweep where it pays: dense layers of a supported width, at least two
+  // steps per interval, and enough (interval, 32-row slice) workgroups to occupy the chip -- with fewer, the
+  // lockstep launches (which spread one step over many workgroups) are as fast.
+  bool use_sweep(int l) const {
+    if (p->layer != MGRIT_LAYER_DENSE || pl.fcP || p->m < 3 || !sweep_enabled()) return false;
+    if (!sweep_supported(p->q, p->dtype)) return false;
+    return sweep_blocks(pl.M, pl.Nl[l + 1]) >= 128;
+  }
   void f_relax(int l) {                                        // Sec. III-C, Fig. 3
+    if (use_sweep(l)) {
+      SweepArgs a;
+      memset(&a, 0, sizeof(a));
+      const long long mp = pl.mpow[l];
+      const PtMap unit = pm(l, 0, 1);                          // storage index of sweep point js = base + js * stride
+      a.S = X[l]; a.sm = pm(l, 0, p->m);
+      a.X = X[l]; a.xb = unit.base; a.xs = unit.stride * p->m; a.xk = unit.stride;
+      if (g[l] && !plain_rhs) { a.G = g[l]; a.gb = 0; a.gs = p->m; }
+      a.W = W; a.bias = bias; a.Dm = Dm;
+      if (adjoint) { a.lb = (pl.Nl[l] - 1) * mp; a.ls = -(long long)p->m * mp; a.lk = -mp; }
+      else         { a.lb = 0;                   a.ls = (long long)p->m * mp;  a.lk = mp; }
+      a.hs = pl.hl[l]; a.act = act; a.nsteps = p->m - 1; a.nchains = pl.Nl[l + 1];
+      a.M = pl.M; a.q = pl.Nf; a.E = pl.E; a.wsize = pl.wsize;
+      if (err == hipSuccess) chk(launch_sweep(a, p->dtype, s));
+      return;
+    }
     for (int k = 1; k < p->m; ++k) propagate(l, k, p->m, pl.Nl[l + 1]);
   }
   void c_relax(int l) { propagate(l, p->m, p->m, pl.Nl[l + 1]); }
-
-  // ---- temporally fused sweeps (dense layers): one launch per relaxation sweep of a level
-  ChainArgs chain_args(int l) const {
-    ChainArgs a;
-    memset(&a, 0, sizeof(a));
-    const long long mp = pl.mpow[l];
-    const PtMap unit = pm(l, 0, 1);                       // storage index of sweep point js = base + js*stride
-    a.X = X[l]; a.xb = unit.base; a.xs = unit.stride * p->m; a.xk = unit.stride;
-    a.G = g[l]; a.gb = 0; a.gs = p->m;
-    a.W = W; a.bias = bias; a.Dm = Dm;
-    if (adjoint) { a.lb = (pl.Nl[l] - 1) * mp; a.ls = -(long long)p->m * mp; a.lk = -mp; }
-    else         { a.lb = 0;                   a.ls = (long long)p->m * mp;  a.lk = mp; }
-    a.hs = pl.hl[l]; a.hsH = l + 1 < pl.L ? pl.hl[l + 1] : 0.0f;
-    a.tau_on_last_step = adjoint ? 1 : 0;
-    a.act = act; a.M = pl.M; a.q = pl.Nf; a.E = pl.E; a.wsize = pl.wsize;
-    return a;
-  }
-  void launch(const ChainArgs& a) {
-    if (err == hipSuccess) chk(launch_chain(a, p->dtype, s));
-  }
-  void chain_f_relax(int l) {                             // F-points follow their C-point
-    ChainArgs a = chain_args(l);
-    a.S = X[l]; a.sm = pm(l, 0, p->m);
-    a.nsteps = p->m - 1; a.nchains = pl.Nl[l + 1]; a.last = LAST_F;
-    launch(a);
-  }
-  void cycle_chain(int l, int iter) {
-    const int m = p->m;
-    if (l == pl.L - 1) {                                  // coarsest level: the whole serial solve is one chain
-      ChainArgs a = chain_args(l);
-      if (g[l]) { a.S = g[l]; a.sm = PtMap{0, 0}; a.write_start = 1; }
-      else      { a.S = X[l]; a.sm = pm(l, 0, 0); }
-      a.xs = 0; a.gs = 0; a.ls = 0;
-      a.nsteps = pl.Nl[l]; a.nchains = 1; a.last = LAST_F;
-      launch(a);
-      return;
-    }
-    const int Nc = pl.Nl[l + 1];
-    const bool fcf = p->relax == MGRIT_RELAX_FCF;
-    if (fcf) {                                            // F-relaxation then C-relaxation, Fig. 3
-      ChainArgs a = chain_args(l);
-      a.S = X[l]; a.sm = pm(l, 0, m);
-      a.nsteps = m; a.nchains = Nc; a.last = LAST_CRELAX;
-      a.Cb = Cb[l]; a.cbb = 1; a.cbs = 1;
-      launch(a);
-    }
-    {                                                     // F-relaxation, then residual, injection and S_H
-      ChainArgs a = chain_args(l);
-      if (fcf) { a.S = Cb[l]; a.sm = PtMap{0, 1}; a.write_start = 1; a.Ue = Cb[l]; a.uem = PtMap{1, 1};
-                 a.Xlast = X[l]; a.xlast_pt = pm(l, pl.Nl[l], 0).base; }
-      else     { a.S = X[l]; a.sm = pm(l, 0, m); a.Ue = X[l]; a.uem = pm(l, m, m); }
-      a.nsteps = m; a.nchains = Nc; a.last = LAST_RESID;
-      a.GH = g[l + 1]; a.XH = X[l + 1];
-      if (l == 0) a.norm_partial = partial;
-      launch(a);
-      if (l == 0) {
-        const double scale = p->norm_kind == MGRIT_NORM_RMS ? 1.0 / sqrt((double)(Nc + 1) * (double)pl.E) : 1.0;
-        chk(launch_norm_final(partial, chain_blocks(pl.M, Nc), scale, hist_dev + iter, s));
-      }
-    }
-    cycle_chain(l + 1, iter);
-    chk(launch_correct(X[l], pm(l, m, m), X[l + 1], PtMap{1, 1}, pl.E, Nc, s));
-    if (l > 0) chain_f_relax(l);                          // on the fine level the next sweep does it
-  }
 
   // Nested-iteration start: the coarsest level's own equation is solved in sequence from the known
   // value; going up, the C-points of a level take the coarser level's values and (on the middle
@@ -413,13 +364,13 @@ int run_solver(Solver& sv, const float* first, double* resnorm_hist, int32_t* it
   int iters = 0;
   int rc = MGRIT_OK;
   if (pl.L == 1) {
-    if (sv.use_chain) sv.cycle_chain(0, 0); else sv.cycle(0, 0, false);
+    sv.cycle(0, 0, false);
     iters = 1;
     if (resnorm_hist) resnorm_hist[0] = 0.0;
     if (sv.err == hipSuccess && (resnorm_hist || iters_done)) sv.chk(hipStreamSynchronize(sv.s));
   } else {
     for (int k = 0; k < p->max_iter && sv.err == hipSuccess; ++k) {
-      if (sv.use_chain) sv.cycle_chain(0, k); else sv.cycle(0, k, k > 0);
+      sv.cycle(0, k, k > 0);
       ++iters;
       if (p->tol > 0.0f) {
         double v = 0.0;
@@ -431,7 +382,6 @@ int run_solver(Solver& sv, const float* first, double* resnorm_hist, int32_t* it
         if (v <= (double)p->tol) break;
       }
     }
-    if (sv.use_chain && sv.err == hipSuccess) sv.chain_f_relax(0);   // F-points after the last correction
     if (!(p->tol > 0.0f) && resnorm_hist && sv.err == hipSuccess) {
       sv.chk(hipMemcpyAsync(resnorm_hist, sv.hist_dev, sizeof(double) * iters, hipMemcpyDeviceToHost, sv.s));
       sv.chk(hipStreamSynchronize(sv.s));
@@ -454,7 +404,6 @@ void bind_workspace(Solver& sv, void* workspace) {
   }
   for (int l = 0; l + 1 < pl.L; ++l) {
     sv.R[l] = reinterpret_cast<float*>(ws + pl.off_R[l]);
-    sv.Cb[l] = reinterpret_cast<float*>(ws + pl.off_C[l]);
   }
   sv.partial = reinterpret_cast<float*>(ws + pl.off_partial);
   sv.hist_dev = reinterpret_cast<double*>(ws + pl.off_hist);
@@ -484,11 +433,10 @@ int forward_impl(const mgrit_problem_t* p, const mgrit_fc_layers_t* fc, const vo
   if (fc && !sv.pl.fcP) return MGRIT_ERR_PROBLEM;
   if (workspace_bytes < sv.pl.bytes_fwd) return MGRIT_ERR_WORKSPACE;
   sv.p = p; sv.s = static_cast<hipStream_t>(hip_stream); sv.adjoint = false;
-  memset(sv.X, 0, sizeof(sv.X)); memset(sv.g, 0, sizeof(sv.g)); memset(sv.R, 0, sizeof(sv.R)); memset(sv.Cb, 0, sizeof(sv.Cb));
+  memset(sv.X, 0, sizeof(sv.X)); memset(sv.g, 0, sizeof(sv.g)); memset(sv.R, 0, sizeof(sv.R));
   sv.X[0] = U;
   sv.W = W; sv.bias = b; sv.Dm = nullptr; sv.act = p->act;
   if (fc) { sv.Wfc = fc->Wfc; sv.bfc = fc->bfc; }
-  sv.use_chain = sv.pl.chain_fwd && chain_enabled();
   bind_workspace(sv, workspace);
   return run_solver(sv, u0, resnorm_hist, iters_done);
 }
@@ -509,7 +457,7 @@ int adjoint_impl(const mgrit_problem_t* p, const mgrit_fc_layers_t* fc, const vo
   if (workspace_bytes < sv.pl.bytes_adj) return MGRIT_ERR_WORKSPACE;
   const Plan& pl = sv.pl;
   sv.p = p; sv.s = static_cast<hipStream_t>(hip_stream); sv.adjoint = true;
-  memset(sv.X, 0, sizeof(sv.X)); memset(sv.g, 0, sizeof(sv.g)); memset(sv.R, 0, sizeof(sv.R)); memset(sv.Cb, 0, sizeof(sv.Cb));
+  memset(sv.X, 0, sizeof(sv.X)); memset(sv.g, 0, sizeof(sv.g)); memset(sv.R, 0, sizeof(sv.R));
   sv.X[0] = Lam;
   bind_workspace(sv, workspace);
   unsigned char* ws = static_cast<unsigned char*>(workspace);
@@ -531,7 +479,6 @@ int adjoint_impl(const mgrit_problem_t* p, const mgrit_fc_layers_t* fc, const vo
   }
   sv.W = Wt; sv.bias = nullptr; sv.Dm = D; sv.act = ACT_IDENT;
   if (fc) { sv.Wfc = Wfct; sv.bfc = nullptr; }
-  sv.use_chain = pl.chain_adj && chain_enabled();
   rc = run_solver(sv, lamN, resnorm_hist, iters_done);
   if (rc != MGRIT_OK && rc != MGRIT_ERR_NONFINITE) return rc;
   if (dW || db) {
@@ -582,7 +529,7 @@ int residual_norm_impl(const mgrit_problem_t* p, const mgrit_fc_layers_t* fc, co
   if (workspace_bytes < sv.pl.bytes_fwd) return MGRIT_ERR_WORKSPACE;
   const Plan& pl = sv.pl;
   sv.p = p; sv.s = static_cast<hipStream_t>(hip_stream); sv.adjoint = false;
-  memset(sv.X, 0, sizeof(sv.X)); memset(sv.g, 0, sizeof(sv.g)); memset(sv.R, 0, sizeof(sv.R)); memset(sv.Cb, 0, sizeof(sv.Cb));
+  memset(sv.X, 0, sizeof(sv.X)); memset(sv.g, 0, sizeof(sv.g)); memset(sv.R, 0, sizeof(sv.R));
   sv.W = W; sv.bias = b; sv.Dm = nullptr; sv.act = p->act;
   if (fc) { sv.Wfc = fc->Wfc; sv.bfc = fc->bfc; }
   bind_workspace(sv, workspace);

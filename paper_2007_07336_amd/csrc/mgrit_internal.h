@@ -109,42 +109,30 @@ hipError_t launch_norm_final(const float* partial, int n, double scale, double* 
 hipError_t launch_transpose_weights(const void* W, void* Wt, int layer_kind, int dtype, int layers, int Nf,
                                     hipStream_t s);
 
-// Temporally fused chain launch (dense layers): workgroup (chain ci, slice of 32 batch rows) starts
-// from S[sm(ci)] and performs nsteps layer steps in sequence with the state slice resident in LDS:
-//   step k = 1..nsteps:  u <- u + hs * act(A_layer (Dm .* u) + bias) + G[gb + ci*gs + k]
-//   layer(k) = lb + ci*ls + (k-1)*lk;   state of step k stored to X[xb + ci*xs + k*xk]
-// The final step either stores like the others (LAST_F), stores to the C-point buffer
-// Cb[cbb + ci*cbs] (LAST_CRELAX; chain 0 also copies its start to Cb[0]), or forms the residual
-// against Ue[uem(ci)] and from it the coarse right-hand side GH[ci+1], the injected coarse state
-// XH[ci+1] = Ue and the squared-norm partial (LAST_RESID; chain 0 also sets XH[0] = GH[0] = start).
-// The coarse step Phi_H(start) needed by GH shares the affine map of step 1 (forward sweep) or of
-// the last step applied to the start state (tau_on_last_step, adjoint sweep).
-enum { LAST_F = 0, LAST_CRELAX = 1, LAST_RESID = 2 };
-struct ChainArgs {
+// Fused F-relaxation sweep (dense layers): workgroup (interval ci, slice of 32 batch rows) starts from
+// S[sm(ci)] and performs nsteps layer steps in sequence with the state slice resident in LDS -- a dense
+// layer acts on every batch row by itself, so the slices of an interval never exchange anything:
+//   step k = 1..nsteps:  u <- u + hs * act(A_layer (Dm_layer .* u) + bias_layer) + G[gb + ci*gs + k]
+//   layer(k) = lb + ci*ls + (k-1)*lk;   the state after step k is stored to X[xb + ci*xs + k*xk]
+// One launch replaces the nsteps lockstep launches of a sweep (Sec. III-C, Fig. 3).
+struct SweepArgs {
   const float* S;  PtMap sm;
-  int write_start;
   float* X;  long long xb, xs, xk;
-  const float* G;  long long gb, gs;
-  const void* W;  const float* bias;  const float* Dm;  long long lb, ls, lk;
-  int nsteps, nchains, last;
-  float* Cb;  long long cbb, cbs;
-  const float* Ue;  PtMap uem;
-  float* GH;  float* XH;
-  float* Xlast;  long long xlast_pt;
-  float hs, hsH;
-  int tau_on_last_step;
-  float* norm_partial;
-  int act, M, q;
+  const float* G;  long long gb, gs;     // optional right-hand side (null: none)
+  const void* W;  const float* bias;     // weights in the problem's type; bias may be null
+  const void* Dm;                        // optional act' factors in the weights' type, [layers][E]
+  long long lb, ls, lk;
+  float hs;
+  int act, nsteps, nchains, M, q;
   long long E, wsize;
 };
-bool       chain_supported(int q, int dtype, bool needs_a0);
-size_t     chain_smem_bytes(int q, int dtype, bool needs_a0);
-int        chain_blocks(int M, int nchains);
-hipError_t launch_chain(const ChainArgs& a, int dtype, hipStream_t s);
+bool       sweep_supported(int q, int dtype);
+int        sweep_blocks(int M, int nchains);
+hipError_t launch_sweep(const SweepArgs& a, int dtype, hipStream_t s);
 
 // launch tracing (diagnostic): kernel classes, and begin / collect
 enum { TRACE_DENSE_F32_64 = 0, TRACE_DENSE_F32_128, TRACE_DENSE_BF16_64, TRACE_DENSE_BF16_128,
-       TRACE_CONV_F32, TRACE_CONV_BF16, TRACE_GRAD, TRACE_CHAIN_F32, TRACE_CHAIN_BF16, TRACE_DENSE_BF16_256,
+       TRACE_CONV_F32, TRACE_CONV_BF16, TRACE_GRAD, TRACE_SWEEP_F32, TRACE_SWEEP_BF16, TRACE_DENSE_BF16_256,
        TRACE_DENSE_F32_KS, TRACE_DENSE_BF16_KS, TRACE_NCLASS };
 void trace_begin();
 int  trace_end(double* ms, long long* launches, long long* units, double* bytes, int ncls);

@@ -1663,6 +1663,228 @@ static hipError_t launch_conv_grad(const GradArgs& a, unsigned blocks, size_t sm
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------
+// Fused F-relaxation sweep for dense layers.  A workgroup owns 32 batch rows of one coarse interval
+// and marches through all steps of the sweep: the fp32 state slice S and its matrix-core operand
+// copy A (Dm .* S in the operand type) stay in LDS, the weights of each layer stream through two LDS
+// slabs of BK values of k (coalesced 16-byte loads into a register ring of PF slabs, running ahead
+// across layer boundaries; while one slab is multiplied the next is written to the other buffer, one
+// barrier per slab).  Wavefront w owns the column blocks w*NBW .. w*NBW + NBW - 1 of 32 columns;
+// q = 128 * NBW.
+// ------------------------------------------------------------------------------------------
+constexpr int SWEEP_R = 32;
+template <typename WT> struct SweepOp;
+template <> struct SweepOp<float>  { static constexpr int BK = 32; };
+template <> struct SweepOp<__bf16> { static constexpr int BK = 64; };
+
+template <typename WT, int NBW, int PF>
+__global__ __launch_bounds__(NT) void dense_sweep_kernel(SweepArgs a) {
+  constexpr int R = SWEEP_R, BK = SweepOp<WT>::BK, VEC = Op<WT>::VEC, KSTEP = Op<WT>::KSTEP, PAD = Op<WT>::PAD;
+  constexpr int Q = 128 * NBW, Q4 = Q / 4;
+  constexpr int AST = Q + PAD, ST = BK + PAD;
+  constexpr int PPR = BK / VEC;                 // 16-byte pieces per weight row and slab
+  constexpr int BP = Q * PPR / NT;              // pieces per thread and slab
+  constexpr int NSL = Q / BK;                   // slabs per layer
+  static_assert(Q * PPR % NT == 0 && R * Q4 % NT == 0, "slab and slice must divide over 256 threads");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  float* S = reinterpret_cast<float*>(smem_raw);           // [R][Q] state slice
+  WT* A = reinterpret_cast<WT*>(S + R * Q);                // [R][AST] operand of the current step
+  WT* Bs = A + R * AST;                                    // [2][Q][ST] weight slabs: row = output column, k fastest
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, c = lane & 31;
+  const int L = logical_block();
+  const int nsl = (a.M + R - 1) / R;
+  const long long ci = L / nsl;
+  const int r0 = (L % nsl) * R;
+  const int rows = min(R, a.M - r0);
+  const long long slice_off = (long long)r0 * Q;
+  const WT* Wall = reinterpret_cast<const WT*>(a.W);
+  const WT* Dall = reinterpret_cast<const WT*>(a.Dm);
+  auto layer_of = [&](int k) { return a.lb + ci * a.ls + (long long)(k - 1) * a.lk; };
+
+  // ---- weight slabs: the sweep's slabs are numbered through, it = (k - 1) * NSL + sl; PF of them are in
+  // flight in registers (a workgroup has a CU to itself, so the loaded memory latency is hidden by depth)
+  const int total = a.nsteps * NSL;
+  uint4 breg[PF][BP];
+  auto load_slab = [&](uint4 (&br)[BP], int it) {
+    const WT* Wp = Wall + layer_of(it / NSL + 1) * a.wsize + (it % NSL) * BK;
+#pragma unroll
+    for (int i = 0; i < BP; ++i) {
+      const int p = tid + NT * i, row = p / PPR, kc = (p % PPR) * VEC;
+      br[i] = ld_weights<false>(Wp + row * Q + kc);
+    }
+  };
+  auto store_slab = [&](const uint4 (&br)[BP], WT* dst) {
+#pragma unroll
+    for (int i = 0; i < BP; ++i) {
+      const int p = tid + NT * i, row = p / PPR, kc = (p % PPR) * VEC;
+      *reinterpret_cast<uint4*>(&dst[row * ST + kc]) = br[i];
+    }
+  };
+#pragma unroll
+  for (int sidx = 0; sidx < PF; ++sidx)
+    if (sidx < total) load_slab(breg[sidx], sidx);
+
+  // ---- start state -> S (rows past the batch end are zero; loads are unconditional)
+  {
+    const float* sp = a.S + (a.sm.base + ci * a.sm.stride) * a.E + slice_off;
+#pragma unroll
+    for (int i = 0; i < R * Q4 / NT; ++i) {
+      const int p = tid + NT * i, row = p / Q4, c4 = (p % Q4) * 4;
+      const bool ok = row < rows;
+      float4 v = *reinterpret_cast<const float4*>(sp + (ok ? row * Q + c4 : 0));
+      if (!ok) v = make_float4(0.f, 0.f, 0.f, 0.f);
+      *reinterpret_cast<float4*>(S + row * Q + c4) = v;
+    }
+  }
+  // One pass over the state slice in LDS, a float4 per thread and piece: the finished state goes to global
+  // memory (out, whole 16-byte pieces of coalesced rows; null: nothing to write), and the operand of the next
+  // step, (Dm[layer] .* S) in the matrix-core type, is built (build = false after the last step)
+  auto flush_and_build = [&](float* out, bool build, long long layer) {
+    const WT* dp = (Dall && build) ? Dall + layer * a.E + slice_off : nullptr;
+#pragma unroll
+    for (int i = 0; i < R * Q4 / NT; ++i) {
+      const int p = tid + NT * i, row = p / Q4, c4 = (p % Q4) * 4;
+      float4 v = *reinterpret_cast<const float4*>(S + row * Q + c4);
+      if (out && row < rows) *reinterpret_cast<float4*>(out + row * Q + c4) = v;
+      if (build) {
+        if (dp) {
+          const float4 d = d4_to_f4(ld_d4(dp + (row < rows ? row * Q + c4 : 0)));
+          v.x *= d.x; v.y *= d.y; v.z *= d.z; v.w *= d.w;     // rows past the end hold 0 in S
+        }
+        cvt_store4(&A[row * AST + c4], v);
+      }
+    }
+  };
+#ifdef MGRIT_TIMING
+  long long t_mma = 0, t_epi = 0, t_bld = 0;
+  const long long t_begin = __builtin_readcyclecounter();
+#endif
+  __syncthreads();                                         // S complete
+  flush_and_build(nullptr, true, layer_of(1));
+  // slab j lives in ring slot j % PF and goes to LDS buffer j % 2; a slot is reloaded with slab j + PF as
+  // soon as slab j has been written to LDS
+  static_assert(NSL % PF == 0 && PF % 2 == 0, "ring slot and LDS buffer of a slab must be compile-time values");
+  store_slab(breg[0], Bs);
+  if (PF < total) load_slab(breg[0], PF);
+
+  for (int k = 1; k <= a.nsteps; ++k) {
+#ifdef MGRIT_TIMING
+    const long long t_k0 = __builtin_readcyclecounter();
+#endif
+    floatx16 acc[1][NBW];
+    float bv[NBW];                                         // bias of this lane's columns: requested before the
+    const long long layer = layer_of(k);                   // contraction, its latency would otherwise open the epilogue
+#pragma unroll
+    for (int t = 0; t < NBW; ++t) {
+      acc[0][t] = zero16();
+      bv[t] = a.bias ? a.bias[layer * Q + (wave * NBW + t) * 32 + c] : 0.0f;
+    }
+    for (int sl0 = 0; sl0 < NSL; sl0 += PF) {
+#pragma unroll
+      for (int sidx = 0; sidx < PF; ++sidx) {
+        const int sl = sl0 + sidx, it = (k - 1) * NSL + sl;
+        __syncthreads();                                   // slab it (and A) visible; slab it-1 consumed
+        if (it + 1 < total) {                              // next slab (maybe the next layer's first) -> other buffer
+          store_slab(breg[(sidx + 1) % PF], Bs + ((sidx + 1) & 1) * (Q * ST));
+          if (it + 1 + PF < total) load_slab(breg[(sidx + 1) % PF], it + 1 + PF);
+        }
+        const WT* Bcur = Bs + (sidx & 1) * (Q * ST);
+#pragma unroll
+        for (int ks = 0; ks < BK; ks += KSTEP) {
+          const WT* ap[1] = {&A[c * AST + sl * BK + ks]};
+          const WT* bp[NBW];
+#pragma unroll
+          for (int t = 0; t < NBW; ++t) bp[t] = &Bcur[((wave * NBW + t) * 32 + c) * ST + ks];
+          mma_step<1, NBW>(ap, bp, acc, g);
+        }
+      }
+    }
+#ifdef MGRIT_TIMING
+    const long long t_k1 = __builtin_readcyclecounter();
+#endif
+    // ---- epilogue of step k: lane holds rows 8*(r/4) + 4*g + r%4 of column n of each of its blocks
+    const float* gp = a.G ? a.G + (a.gb + ci * a.gs + k) * a.E + slice_off : nullptr;
+    float* xo = a.X + (a.xb + ci * a.xs + (long long)k * a.xk) * a.E + slice_off;
+#pragma unroll
+    for (int t = 0; t < NBW; ++t) {
+      const int n = (wave * NBW + t) * 32 + c;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = 8 * (r >> 2) + 4 * g + (r & 3);
+        if (row < rows) {
+          const int off = row * Q + n;
+          float unew = S[off] + a.hs * act_fn(acc[0][t][r] + bv[t], a.act);
+          if (gp) unew += gp[off];
+          S[off] = unew;                                   // to global memory in the pass below
+        }
+      }
+    }
+    __syncthreads();                                       // S of step k complete
+#ifdef MGRIT_TIMING
+    const long long t_k2 = __builtin_readcyclecounter();
+#endif
+    flush_and_build(xo, k < a.nsteps, k < a.nsteps ? layer_of(k + 1) : 0);
+#ifdef MGRIT_TIMING
+    // diagnostic build only: phase times in cycles overwrite the first values of the last state slice
+    const long long t_k3 = __builtin_readcyclecounter();
+    t_mma += t_k1 - t_k0; t_epi += t_k2 - t_k1; t_bld += t_k3 - t_k2;
+    __syncthreads();
+    if (k == a.nsteps && tid == 0) {
+      xo[0] = (float)(t_k0 - t_begin); xo[1] = (float)t_mma; xo[2] = (float)t_epi; xo[3] = (float)t_bld;
+    }
+#endif
+  }
+}
+
+static size_t sweep_smem_bytes(int q, int dtype) {
+  const size_t es = dtype == 0 ? 4 : 2, pad = dtype == 0 ? Op<float>::PAD : Op<__bf16>::PAD;
+  const size_t bk = dtype == 0 ? SweepOp<float>::BK : SweepOp<__bf16>::BK;
+  return (size_t)SWEEP_R * q * 4 + (size_t)SWEEP_R * (q + pad) * es + (size_t)2 * q * (bk + pad) * es;
+}
+bool sweep_supported(int q, int dtype) {
+  return (q == 128 || q == 256) && sweep_smem_bytes(q, dtype) <= (size_t)150 * 1024;
+}
+int sweep_blocks(int M, int nchains) { return ((M + SWEEP_R - 1) / SWEEP_R) * nchains; }
+
+template <typename WT, int NBW>
+static hipError_t launch_sweep_t(const SweepArgs& a, unsigned blocks, size_t smem, hipStream_t s) {
+  // weight slabs in flight in registers: as many as a layer has, at most 8
+  constexpr int NSLABS = 128 * NBW / SweepOp<WT>::BK;
+  constexpr int PF = NSLABS < 8 ? NSLABS : 8;
+  if (smem > 64 * 1024) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(dense_sweep_kernel<WT, NBW, PF>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL((dense_sweep_kernel<WT, NBW, PF>), dim3(blocks), dim3(NT), smem, s, a);
+  return hipGetLastError();
+}
+hipError_t launch_sweep(const SweepArgs& a, int dtype, hipStream_t s) {
+  if (a.nchains <= 0 || a.nsteps <= 0) return hipSuccess;
+  if (!sweep_supported(a.q, dtype) || a.M < 1) return hipErrorInvalidValue;
+  const size_t smem = sweep_smem_bytes(a.q, dtype);
+  const unsigned blocks = (unsigned)sweep_blocks(a.M, a.nchains);
+  const int nbw = a.q / 128;
+  trace_before(s);
+  hipError_t e = hipErrorInvalidValue;
+  if (dtype == 0) {
+    if (nbw == 1) e = launch_sweep_t<float, 1>(a, blocks, smem, s);
+    else if (nbw == 2) e = launch_sweep_t<float, 2>(a, blocks, smem, s);
+  } else {
+    if (nbw == 1) e = launch_sweep_t<__bf16, 1>(a, blocks, smem, s);
+    else if (nbw == 2) e = launch_sweep_t<__bf16, 2>(a, blocks, smem, s);
+  }
+  // algorithmic bytes per layer step: weights and bias, the act' factor, the right-hand side, the state out
+  // (the state in is read once per chain)
+  const double es = dtype == 0 ? 4.0 : 2.0;
+  const double per = (double)a.wsize * es + (a.bias ? 4.0 * a.q : 0.0) + (a.Dm ? es : 0.0) * (double)a.E +
+                     (a.G ? 4.0 : 0.0) * (double)a.E + 4.0 * (double)a.E;
+  trace_after(s, dtype == 0 ? TRACE_SWEEP_F32 : TRACE_SWEEP_BF16, (long long)a.nchains * a.nsteps,
+              (double)a.nchains * (a.nsteps * per + 4.0 * (double)a.E));
+  return e;
+}
+
 hipError_t launch_grad(const GradArgs& a_in, int layer_kind, int dtype, int groups, hipStream_t s) {
   if (groups <= 0) return hipSuccess;
   GradArgs a = a_in;

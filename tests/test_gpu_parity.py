@@ -85,8 +85,8 @@ DENSE_CASES = [
     I.reduced(I.cfg2(1), name="dense_fp32_q136_B130_N128_m2_bigtile", q=136, B=130, N=128, m=2, max_levels=2),
 ]
 
-# widths the temporally fused chain kernels take (q a multiple of 128, at most 512); each case
-# also runs with the chain path switched off, i.e. through the lockstep kernels
+# widths that are multiples of 128 (the fused sweep kernel's block width) at launch sizes below its threshold:
+# these run through the lockstep launches
 CHAIN_CASES = [
     I.reduced(I.cfg2(3), name="chain_fp32_q128_B37_N64_L3_FCF", q=128, B=37, N=64),
     I.reduced(I.cfg2(2), name="chain_fp32_q256_B70_N32_L2_F", q=256, B=70, N=32, max_levels=2, relax=I.RELAX_F,
@@ -101,8 +101,6 @@ CHAIN_CASES = [
 
 @pytest.mark.parametrize("wl", CHAIN_CASES, ids=lambda w: w.name)
 def test_dense_forward_chain_widths(wl):
-    # The fused chain kernels are switched off in the library (their first GPU run faulted and the cause
-    # is not known yet), so these widths currently run through the lockstep kernels.
     _check_forward(wl)
 
 
@@ -242,7 +240,7 @@ ADJ_CASES = [
     I.reduced(I.cfg5(2), name="adj_dense_bf16_q136_B50_N64_m4", q=136, B=50, N=64, m=4),
     I.reduced(I.cfg5(2), name="adj_dense_fp32_relu_F_L2", q=40, B=12, N=32, m=4, dtype=I.FP32, act=I.RELU,
               max_levels=2, relax=I.RELAX_F),
-    # chain-kernel widths
+    # widths that are multiples of 128
     I.reduced(I.cfg5(3), name="adj_chain_fp32_q128_B37_N64_m4", q=128, B=37, N=64, m=4, dtype=I.FP32),
     I.reduced(I.cfg5(2), name="adj_chain_bf16_q256_B50_N64_m4", q=256, B=50, N=64, m=4),
     I.reduced(I.cfg5(2), name="adj_chain_fp32_q256_relu_F_L2", q=256, B=12, N=32, m=4, dtype=I.FP32, act=I.RELU,
@@ -388,3 +386,80 @@ def test_maximum_layer_count_forward_and_adjoint():
     # the float64 oracle does not have (the 1e-5 bar is set at the benchmark depths, N <= 1024); a layer's
     # gradient is a sum of B = 2 terms of either sign, which amplifies that relative error a few times
     assert eL <= 3e-5 and eW <= 1e-4 and eb <= 1e-4, (eL, eW, eb)
+
+
+# ------------------------------------------------------------------ fused F-relaxation sweeps (dense layers)
+# Shapes on which the library fuses the steps of an F-relaxation sweep into one launch (width 128 or 256;
+# at least 128 (interval, 32-row slice) workgroups; m >= 3); each also runs with the fused
+# launches switched off (MGRIT_NO_SWEEP=1), i.e. through the lockstep launches, and the two must agree with the
+# oracle alike.
+SWEEP_CASES = [
+    I.reduced(I.cfg2(2), name="sweep_fp32_q128_B37_N256_m4_L3_FCF", q=128, B=37, N=256),
+    I.reduced(I.cfg2(1), name="sweep_fp32_q256_B70_N192_m4_L2_F_tanh_bias", q=256, B=70, N=192, max_levels=2,
+              relax=I.RELAX_F, bias_var=0.1, act=I.TANH),
+    I.reduced(I.cfg5(1), name="sweep_bf16_q256_B40_N192_m3", q=256, B=40, N=192, m=3, max_levels=2, head_classes=0),
+    I.reduced(I.cfg5(1), name="sweep_bf16_q128_B512_N128_m16", q=128, B=512, N=128, m=16, max_levels=2,
+              head_classes=0),
+]
+
+
+@pytest.mark.parametrize("fused", [True, False], ids=["fused", "lockstep"])
+@pytest.mark.parametrize("wl", SWEEP_CASES, ids=lambda w: w.name)
+def test_dense_forward_fused_sweeps(wl, fused, monkeypatch):
+    import paper_2007_07336_amd as M
+    if not fused:
+        monkeypatch.setenv("MGRIT_NO_SWEEP", "1")
+    _announce(f"{wl.name} fused={fused}")
+    data = I.generate(wl)
+    gp = GpuProblem(wl, data)
+    M.mgrit_trace_begin()
+    rc, U, hist, it = gp.forward()
+    tr = M.mgrit_trace_end()
+    assert any(k.startswith("dense_sweep_kernel") for k in tr) == fused, tr      # the path under test did run
+    Uo, hist_o, it_o = oracle_forward(wl, data)
+    assert rel_l2_per_state(U, Uo) <= TOL[wl.dtype]
+    assert it == it_o
+    for a, b in zip(hist, hist_o):
+        assert abs(a - b) <= (1e-3 if wl.dtype == I.FP32 else 5e-2) * max(b, 1e-6)
+
+
+def test_dense_fused_sweeps_nested_start_three_levels():
+    wl = I.reduced(I.cfg2(2), name="sweep_fp32_q128_B64_N256_nested", q=128, B=64, N=256, bias_var=0.1, act=I.TANH)
+    _announce(wl.name)
+    data = I.generate(wl)
+    gp = GpuProblem(wl, data, init=3)
+    rc, U, hist, it = gp.forward()
+    Uo, hist_o, _ = oracle_forward(wl, data, init=3)
+    assert rel_l2_per_state(U, Uo) <= 1e-5
+
+
+SWEEP_ADJ_CASES = [
+    I.reduced(I.cfg5(2), name="adj_sweep_fp32_q128_B37_N256_m4_L3", q=128, B=37, N=256, m=4, max_levels=3, dtype=I.FP32),
+    I.reduced(I.cfg5(1), name="adj_sweep_bf16_q256_B70_N192_m4_relu", q=256, B=70, N=192, m=4, max_levels=2, act=I.RELU),
+    I.reduced(I.cfg5(1), name="adj_sweep_fp32_q256_B100_N96_m3_F", q=256, B=100, N=96, m=3, max_levels=2, dtype=I.FP32,
+              relax=I.RELAX_F),
+]
+
+
+@pytest.mark.parametrize("fused", [True, False], ids=["fused", "lockstep"])
+@pytest.mark.parametrize("wl", SWEEP_ADJ_CASES, ids=lambda w: w.name)
+def test_dense_adjoint_fused_sweeps(wl, fused, monkeypatch):
+    import paper_2007_07336_amd as M
+    if not fused:
+        monkeypatch.setenv("MGRIT_NO_SWEEP", "1")
+    _announce(f"{wl.name} fused={fused}")
+    data = I.generate(wl)
+    Uo, _, _ = oracle_forward(wl, data, max_iter=2)
+    U = Uo.astype(np.float32)
+    if wl.dtype == I.BF16 and wl.act == I.RELU:
+        U = I.round_to_bf16(U)          # both sides take the ReLU' decision on the same bf16 operand
+    lamN = I.terminal_adjoint(wl, data, U[-1])
+    gp = GpuProblem(wl, data)
+    M.mgrit_trace_begin()
+    Lam, dW, db, hist, it = gp.adjoint(U, lamN)
+    tr = M.mgrit_trace_end()
+    assert any(k.startswith("dense_sweep_kernel") for k in tr) == fused, tr
+    Lo, dWo, dbo, hist_o, it_o = oracle_adjoint(wl, data, U, lamN)
+    tol = TOL[wl.dtype]
+    eL, eW, eb = rel_l2_per_state(Lam, Lo), rel_l2_per_state(dW, dWo), rel_l2_per_state(db, dbo)
+    assert eL <= tol and eW <= tol and eb <= tol, (eL, eW, eb)
