@@ -1669,7 +1669,8 @@ static hipError_t launch_conv_grad(const GradArgs& a, unsigned blocks, size_t sm
 // copy A (Dm .* S in the operand type) stay in LDS, the weights of each layer stream through two LDS
 // slabs of BK values of k (coalesced 16-byte loads into a register ring of PF slabs, running ahead
 // across layer boundaries; while one slab is multiplied the next is written to the other buffer, one
-// barrier per slab).  Wavefront w owns the column blocks w*NBW .. w*NBW + NBW - 1 of 32 columns;
+// barrier per slab).  The raw sums of a step go through the slab buffer that has just become free, so that
+// the update -- new state to LDS and to global memory, next operand -- is one float4 pass over whole rows.  Wavefront w owns the column blocks w*NBW .. w*NBW + NBW - 1 of 32 columns;
 // q = 128 * NBW.
 // ------------------------------------------------------------------------------------------
 constexpr int SWEEP_R = 32;
@@ -1737,23 +1738,21 @@ __global__ __launch_bounds__(NT) void dense_sweep_kernel(SweepArgs a) {
       *reinterpret_cast<float4*>(S + row * Q + c4) = v;
     }
   }
-  // One pass over the state slice in LDS, a float4 per thread and piece: the finished state goes to global
-  // memory (out, whole 16-byte pieces of coalesced rows; null: nothing to write), and the operand of the next
-  // step, (Dm[layer] .* S) in the matrix-core type, is built (build = false after the last step)
-  auto flush_and_build = [&](float* out, bool build, long long layer) {
-    const WT* dp = (Dall && build) ? Dall + layer * a.E + slice_off : nullptr;
+  // The column group of a thread in the float4 passes over the slice is the same for all its pieces
+  // (256 threads are a multiple of the Q/4 pieces of a row)
+  const int c4t = (tid % Q4) * 4;
+  // operand of a step from the state slice: (Dm[layer] .* S) in the matrix-core type
+  auto build_operand = [&](long long layer) {
+    const WT* dp = Dall ? Dall + layer * a.E + slice_off : nullptr;
 #pragma unroll
     for (int i = 0; i < R * Q4 / NT; ++i) {
-      const int p = tid + NT * i, row = p / Q4, c4 = (p % Q4) * 4;
-      float4 v = *reinterpret_cast<const float4*>(S + row * Q + c4);
-      if (out && row < rows) *reinterpret_cast<float4*>(out + row * Q + c4) = v;
-      if (build) {
-        if (dp) {
-          const float4 d = d4_to_f4(ld_d4(dp + (row < rows ? row * Q + c4 : 0)));
-          v.x *= d.x; v.y *= d.y; v.z *= d.z; v.w *= d.w;     // rows past the end hold 0 in S
-        }
-        cvt_store4(&A[row * AST + c4], v);
+      const int row = (tid + NT * i) / Q4;
+      float4 v = *reinterpret_cast<const float4*>(S + row * Q + c4t);
+      if (dp) {
+        const float4 d = d4_to_f4(ld_d4(dp + (row < rows ? row * Q + c4t : 0)));
+        v.x *= d.x; v.y *= d.y; v.z *= d.z; v.w *= d.w;       // rows past the end hold 0 in S
       }
+      cvt_store4(&A[row * AST + c4t], v);
     }
   };
 #ifdef MGRIT_TIMING
@@ -1761,7 +1760,7 @@ __global__ __launch_bounds__(NT) void dense_sweep_kernel(SweepArgs a) {
   const long long t_begin = __builtin_readcyclecounter();
 #endif
   __syncthreads();                                         // S complete
-  flush_and_build(nullptr, true, layer_of(1));
+  build_operand(layer_of(1));
   // slab j lives in ring slot j % PF and goes to LDS buffer j % 2; a slot is reloaded with slab j + PF as
   // soon as slab j has been written to LDS
   static_assert(NSL % PF == 0 && PF % 2 == 0, "ring slot and LDS buffer of a slab must be compile-time values");
@@ -1773,13 +1772,13 @@ __global__ __launch_bounds__(NT) void dense_sweep_kernel(SweepArgs a) {
     const long long t_k0 = __builtin_readcyclecounter();
 #endif
     floatx16 acc[1][NBW];
-    float bv[NBW];                                         // bias of this lane's columns: requested before the
-    const long long layer = layer_of(k);                   // contraction, its latency would otherwise open the epilogue
+    // bias of this thread's column group in the float4 pass: requested before the contraction, its latency
+    // would otherwise open the epilogue
+    const long long layer = layer_of(k);
+    float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (a.bias) bv = *reinterpret_cast<const float4*>(a.bias + layer * Q + c4t);
 #pragma unroll
-    for (int t = 0; t < NBW; ++t) {
-      acc[0][t] = zero16();
-      bv[t] = a.bias ? a.bias[layer * Q + (wave * NBW + t) * 32 + c] : 0.0f;
-    }
+    for (int t = 0; t < NBW; ++t) acc[0][t] = zero16();
     for (int sl0 = 0; sl0 < NSL; sl0 += PF) {
 #pragma unroll
       for (int sidx = 0; sidx < PF; ++sidx) {
@@ -1803,35 +1802,59 @@ __global__ __launch_bounds__(NT) void dense_sweep_kernel(SweepArgs a) {
 #ifdef MGRIT_TIMING
     const long long t_k1 = __builtin_readcyclecounter();
 #endif
-    // ---- epilogue of step k: lane holds rows 8*(r/4) + 4*g + r%4 of column n of each of its blocks
-    const float* gp = a.G ? a.G + (a.gb + ci * a.gs + k) * a.E + slice_off : nullptr;
-    float* xo = a.X + (a.xb + ci * a.xs + (long long)k * a.xk) * a.E + slice_off;
+    // ---- epilogue of step k.  The raw sums go through the weight buffer that the last slab has just left
+    // (the other one already holds the next layer's first slab), so that the update is one float4 pass over
+    // whole rows: new state to S and to global memory, and the next step's operand to A.
+    __syncthreads();                                       // every wavefront is done with that buffer and with A
+    constexpr int ZST = Q + 4;
+    float* Z = reinterpret_cast<float*>(Bs + ((NSL - 1) & 1) * (Q * ST));     // [R][ZST], fits: 144 Q >= 128 Q + 512 bytes
 #pragma unroll
-    for (int t = 0; t < NBW; ++t) {
-      const int n = (wave * NBW + t) * 32 + c;
+    for (int t = 0; t < NBW; ++t)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = 8 * (r >> 2) + 4 * g + (r & 3);
-        if (row < rows) {
-          const int off = row * Q + n;
-          float unew = S[off] + a.hs * act_fn(acc[0][t][r] + bv[t], a.act);
-          if (gp) unew += gp[off];
-          S[off] = unew;                                   // to global memory in the pass below
-        }
-      }
-    }
-    __syncthreads();                                       // S of step k complete
+      for (int r = 0; r < 16; ++r)                          // lane holds rows 8*(r/4) + 4*g + r%4 of column n
+        Z[(8 * (r >> 2) + 4 * g + (r & 3)) * ZST + (wave * NBW + t) * 32 + c] = acc[0][t][r];
+    __syncthreads();
 #ifdef MGRIT_TIMING
     const long long t_k2 = __builtin_readcyclecounter();
 #endif
-    flush_and_build(xo, k < a.nsteps, k < a.nsteps ? layer_of(k + 1) : 0);
+    {
+      const float* gp = a.G ? a.G + (a.gb + ci * a.gs + k) * a.E + slice_off : nullptr;
+      float* xo = a.X + (a.xb + ci * a.xs + (long long)k * a.xk) * a.E + slice_off;
+      const bool build = k < a.nsteps;
+      const WT* dp = (Dall && build) ? Dall + layer_of(k + 1) * a.E + slice_off : nullptr;
+#pragma unroll
+      for (int i = 0; i < R * Q4 / NT; ++i) {
+        const int row = (tid + NT * i) / Q4;
+        const bool ok = row < rows;
+        const int off = ok ? row * Q + c4t : 0;
+        const float4 z = *reinterpret_cast<const float4*>(Z + row * ZST + c4t);
+        float4 u = *reinterpret_cast<const float4*>(S + row * Q + c4t);
+        u.x += a.hs * act_fn(z.x + bv.x, a.act); u.y += a.hs * act_fn(z.y + bv.y, a.act);
+        u.z += a.hs * act_fn(z.z + bv.z, a.act); u.w += a.hs * act_fn(z.w + bv.w, a.act);
+        if (gp) {
+          const float4 gv = *reinterpret_cast<const float4*>(gp + off);
+          u.x += gv.x; u.y += gv.y; u.z += gv.z; u.w += gv.w;
+        }
+        if (!ok) u = make_float4(0.f, 0.f, 0.f, 0.f);       // rows past the batch end stay zero
+        *reinterpret_cast<float4*>(S + row * Q + c4t) = u;
+        if (ok) *reinterpret_cast<float4*>(xo + off) = u;
+        if (build) {
+          if (dp) {
+            const float4 d = d4_to_f4(ld_d4(dp + off));
+            u.x *= d.x; u.y *= d.y; u.z *= d.z; u.w *= d.w;
+          }
+          cvt_store4(&A[row * AST + c4t], u);
+        }
+      }
+    }
 #ifdef MGRIT_TIMING
     // diagnostic build only: phase times in cycles overwrite the first values of the last state slice
     const long long t_k3 = __builtin_readcyclecounter();
     t_mma += t_k1 - t_k0; t_epi += t_k2 - t_k1; t_bld += t_k3 - t_k2;
     __syncthreads();
     if (k == a.nsteps && tid == 0) {
-      xo[0] = (float)(t_k0 - t_begin); xo[1] = (float)t_mma; xo[2] = (float)t_epi; xo[3] = (float)t_bld;
+      float* xt = a.X + (a.xb + ci * a.xs + (long long)k * a.xk) * a.E + slice_off;
+      xt[0] = (float)(t_k0 - t_begin); xt[1] = (float)t_mma; xt[2] = (float)t_epi; xt[3] = (float)t_bld;
     }
 #endif
   }
@@ -1849,9 +1872,10 @@ int sweep_blocks(int M, int nchains) { return ((M + SWEEP_R - 1) / SWEEP_R) * nc
 
 template <typename WT, int NBW>
 static hipError_t launch_sweep_t(const SweepArgs& a, unsigned blocks, size_t smem, hipStream_t s) {
-  // weight slabs in flight in registers: as many as a layer has, at most 8
+  // weight slabs in flight in registers: as many as a layer has, at most 4 (eight measured no faster and
+  // take 256 registers of a lane)
   constexpr int NSLABS = 128 * NBW / SweepOp<WT>::BK;
-  constexpr int PF = NSLABS < 8 ? NSLABS : 8;
+  constexpr int PF = NSLABS < 4 ? NSLABS : 4;
   if (smem > 64 * 1024) {
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(dense_sweep_kernel<WT, NBW, PF>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
