@@ -1876,10 +1876,12 @@ static hipError_t launch_sweep_t(const SweepArgs& a, unsigned blocks, size_t sme
   // take 256 registers of a lane)
   constexpr int NSLABS = 128 * NBW / SweepOp<WT>::BK;
   constexpr int PF = NSLABS < 4 ? NSLABS : 4;
-  if (smem > 64 * 1024) {
+  static bool raised = false;                // opt in once to more than 64 KB of dynamic LDS
+  if (smem > 64 * 1024 && !raised) {
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(dense_sweep_kernel<WT, NBW, PF>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
+    raised = true;
   }
   hipLaunchKernelGGL((dense_sweep_kernel<WT, NBW, PF>), dim3(blocks), dim3(NT), smem, s, a);
   return hipGetLastError();

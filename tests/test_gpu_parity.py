@@ -463,3 +463,51 @@ def test_dense_adjoint_fused_sweeps(wl, fused, monkeypatch):
     tol = TOL[wl.dtype]
     eL, eW, eb = rel_l2_per_state(Lam, Lo), rel_l2_per_state(dW, dWo), rel_l2_per_state(db, dbo)
     assert eL <= tol and eW <= tol and eb <= tol, (eL, eW, eb)
+
+
+def test_fused_sweeps_repeat_bitwise_and_replay_from_a_hip_graph():
+    """The fused sweep launches are deterministic, and a forward + adjoint pair that uses them can be captured
+    into a HIP graph and replayed to the same bits."""
+    import torch
+    import paper_2007_07336_amd as M
+    wl = I.reduced(I.cfg2(2), name="sweep_fp32_q256_B64_N256_graph", q=256, B=64, N=256)
+    _announce(wl.name)
+    data = I.generate(wl)
+    gp = GpuProblem(wl, data)
+    lamN = torch.from_numpy(np.random.default_rng(4).standard_normal(wl.state_shape).astype(np.float32)).cuda()
+    Lam = torch.zeros_like(gp.U)
+    dW = torch.zeros(gp.W.shape, dtype=torch.float32, device="cuda")
+    db = torch.zeros_like(gp.b)
+    ws = torch.empty(M.mgrit_adjoint_workspace_bytes(gp.p), dtype=torch.uint8, device="cuda")
+
+    def pair():
+        M.mgrit_fas_forward(gp.p, gp.W, gp.b, gp.u0, gp.U, ws, want_hist=False)
+        M.mgrit_fas_adjoint(gp.p, gp.W, gp.b, gp.U, lamN, Lam, dW, db, ws, want_hist=False)
+
+    M.mgrit_trace_begin()
+    pair()
+    tr = M.mgrit_trace_end()
+    assert any(k.startswith("dense_sweep_kernel") for k in tr), tr
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in (gp.U, Lam, dW, db)]
+    for t in (gp.U, Lam, dW, db):
+        t.zero_()
+    pair()
+    torch.cuda.synchronize()
+    for t, r in zip((gp.U, Lam, dW, db), ref):
+        assert torch.equal(t, r)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            pair()
+    torch.cuda.synchronize()
+    for replay in range(3):
+        for t in (gp.U, Lam, dW, db):
+            t.fill_(float(replay + 1))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for t, r in zip((gp.U, Lam, dW, db), ref):
+            assert torch.equal(t, r), replay
