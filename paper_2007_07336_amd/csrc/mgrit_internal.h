@@ -40,6 +40,7 @@ struct StepArgs {
   int Nf;                          // features per row: q (dense) or C (conv)
   int K;                           // contraction length per output: q or 9*C
   int Himg, Wimg, TH;              // conv only: image size and rows of an output tile
+  unsigned wmagic;                 // conv only: ceil(2^20 / Wimg), filled in by the launch wrapper
   int tiles;                       // workgroups per group (filled in by the launch wrapper)
   int dbf16;                       // 1: Dm (input) and the output of MODE_DACT are bf16 arrays
   int wstream;                     // 1: all layers' weights together exceed the last-level cache, load them

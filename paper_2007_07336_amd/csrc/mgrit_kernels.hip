@@ -629,6 +629,8 @@ __global__ __launch_bounds__(NT) void dense_ksplit_kernel(StepArgs a) {
 // N16 (float only, at most 16 channels): the output-channel side uses 16x16x4 MFMA blocks, so none of the
 // matrix-core work is spent on padding columns; a wavefront then owns 4 blocks of 16 pixels.
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+// p / w for 0 <= p < 4096 and 1 <= w <= 256 with magic = ceil(2^20 / w): exact because p * (magic * w - 2^20) < 2^20
+__device__ __forceinline__ int div_small(int p, unsigned magic) { return (int)(((unsigned)p * magic) >> 20); }
 template <typename WT, int TN, bool N16 = false>
 __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
   static_assert(!N16 || (sizeof(WT) == 4 && TN == 1), "the 16-wide variant is float only");
@@ -642,7 +644,7 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, c = lane & 31;
   const int C = a.Nf, H = a.Himg, Wd = a.Wimg, TH = a.TH;
-  const int Cp = (C + KSTEP - 1) / KSTEP * KSTEP;
+  const int Cp = N16 ? 16 : (C + KSTEP - 1) / KSTEP * KSTEP;   // a compile-time value in the 16-wide variant (C <= 16)
   const int CS = Cp + PAD;
   const int PW = Wd + 2;
   WT* patch = reinterpret_cast<WT*>(smem_raw);
@@ -743,7 +745,8 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
           float4 w = xreg[i];
           if (Dp) { const float4 dd = d4_to_f4(dreg[h]); w.x *= dd.x; w.y *= dd.y; w.z *= dd.z; w.w *= dd.w; }
           if (!((okm >> i) & 1u)) w = make_float4(0.f, 0.f, 0.f, 0.f);
-          cvt_store4(&patch[((p / Wd + 1) * PW + p % Wd + 1) * CS + colq], w);
+          const int py = div_small(p, a.wmagic);           // p / Wd without the division sequence
+          cvt_store4(&patch[((py + 1) * PW + (p - py * Wd) + 1) * CS + colq], w);
         }
       }
     }
@@ -792,7 +795,8 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
   for (int i = 0; i < NA; ++i) {
     int p = N16 ? wave * 64 + 16 * i + r16 : (wave * TM + i) * 32 + c;
     if (p >= npx) p = 0;                      // masked rows compute on pixel 0 and are dropped
-    aoff[i] = ((p / Wd) * PW + (p % Wd)) * CS;
+    const int py = div_small(p, a.wmagic);
+    aoff[i] = (py * PW + (p - py * Wd)) * CS;
   }
 
   floatx16 acc[TM][TN];
@@ -961,6 +965,7 @@ hipError_t launch_step(const StepArgs& a_in, int layer_kind, int dtype, int grou
   trace_before(s);
   int cls;
   if (layer_kind == 1) {
+    a.wmagic = ((1u << 20) + (unsigned)a.Wimg - 1u) / (unsigned)a.Wimg;
     const size_t smem = conv_smem_bytes(a, dtype);
     cls = dtype == 0 ? TRACE_CONV_F32 : TRACE_CONV_BF16;
     if (conv_uses_n16(a, dtype)) {
