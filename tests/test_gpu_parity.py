@@ -400,6 +400,8 @@ SWEEP_CASES = [
     I.reduced(I.cfg5(1), name="sweep_bf16_q256_B40_N192_m3", q=256, B=40, N=192, m=3, max_levels=2, head_classes=0),
     I.reduced(I.cfg5(1), name="sweep_bf16_q128_B512_N128_m16", q=128, B=512, N=128, m=16, max_levels=2,
               head_classes=0),
+    # deep enough that the middle level's sweeps are fused too: they carry the FAS right-hand side
+    I.reduced(I.cfg2(1), name="sweep_fp32_q128_B37_N1024_m4_L3_rhs", q=128, B=37, N=1024, bias_var=0.1, act=I.TANH),
 ]
 
 
@@ -438,6 +440,7 @@ SWEEP_ADJ_CASES = [
     I.reduced(I.cfg5(1), name="adj_sweep_bf16_q256_B70_N192_m4_relu", q=256, B=70, N=192, m=4, max_levels=2, act=I.RELU),
     I.reduced(I.cfg5(1), name="adj_sweep_fp32_q256_B100_N96_m3_F", q=256, B=100, N=96, m=3, max_levels=2, dtype=I.FP32,
               relax=I.RELAX_F),
+    I.reduced(I.cfg5(1), name="adj_sweep_bf16_q128_B40_N1024_m4_L3_rhs", q=128, B=40, N=1024, m=4, max_levels=3),
 ]
 
 
