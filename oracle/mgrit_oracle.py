@@ -32,14 +32,17 @@ j c^l and uses theta^{j c^l}.  (The paper writes the coarsening factor as c; the
 interface of this project calls it m.)
 
 Pins (tests/test_oracle_pins.py): two-level exactness after N/c cycles, fixed point at the
-serial solution, linear-F closed forms and the dense two-grid operator, brute-force coarse
+serial solution, linear-F closed forms and the dense two-grid and three-grid operators, brute-force coarse
 equation check, layer steps against an independent float64 library routine, gradients
 against finite differences and automatic differentiation, level maps against enumeration;
 the nested-iteration start against hand-written coarse forward-Euler loops, its exactness for a
 layer-independent constant F, and the unchanged fixed point; the fully connected kind and mixed
 stacks against the float64 library routines, automatic differentiation and two-level exactness.
-Parity unpinned: the value of a multilevel (3+ level) iterate at a fixed finite cycle count
-is pinned only through its limit, its fixed point and its agreement with the two-level case.
+A multilevel (3+ level) iterate at a fixed finite cycle count is pinned for linear F by the dense
+three-grid correction scheme (relax, restrict, one two-grid cycle on the middle level, correct);
+for nonlinear F it rests on that pin of the recursion together with the two-level pins of the
+nonlinear pieces, its limit and its fixed point -- no independent value of a nonlinear
+three-level iterate exists to compare with.
 """
 from __future__ import annotations
 

@@ -211,6 +211,75 @@ def test_linear_two_level_equals_dense_two_grid(relax):
     assert abs(hist[0] - rnorm) < 1e-12 * max(1.0, rnorm)
 
 
+@pytest.mark.parametrize("relax", [O.RELAX_F, O.RELAX_FCF])
+def test_linear_three_level_equals_dense_three_grid(relax):
+    """A multilevel iterate at a fixed cycle count: for linear F one three-level V-cycle equals the three-grid
+    correction scheme assembled from dense matrices -- relax, restrict the residual by injection, solve the
+    level-1 correction equation approximately by ONE two-grid cycle from a zero guess (relax, restrict, exact
+    solve on level 2, correct, F-relax), correct, F-relax (Sec. III-A applied recursively)."""
+    rng = np.random.default_rng(17)
+    N, m, q, h = 16, 2, 2, 0.15          # 4 intervals on level 1: one FCF cycle there is not yet exact
+    W, b, u0 = _dense_problem(rng, N, q, 1, bias=False, scale=1.5)
+
+    def system(steps, stride, hs):        # block bidiagonal L with -(I + hs W[j * stride]) below the diagonal
+        Phi = [np.eye(q) + hs * W[j * stride] for j in range(steps)]
+        A = np.eye((steps + 1) * q)
+        for j in range(steps):
+            A[(j + 1) * q:(j + 2) * q, j * q:(j + 1) * q] = -Phi[j]
+        return A, Phi
+
+    A0, Phi0 = system(N, 1, h)
+    A1, Phi1 = system(N // m, m, m * h)
+    A2, _ = system(N // m // m, m * m, m * m * h)
+
+    def blk(j):
+        return slice(j * q, (j + 1) * q)
+
+    def cidx(steps):                      # entries of the C-points 0, m, 2m, ... of a level with `steps` steps
+        return np.concatenate([np.arange(i * m * q, i * m * q + q) for i in range(steps // m + 1)])
+
+    def relax_level(x, rhs, Phi, steps, kind):
+        def f_rel(x):
+            x = x.copy()
+            for i in range(steps // m):
+                for k in range(1, m):
+                    j = i * m + k
+                    x[blk(j)] = Phi[j - 1] @ x[blk(j - 1)] + rhs[blk(j)]
+            return x
+
+        def c_rel(x):
+            x = x.copy()
+            for i in range(1, steps // m + 1):
+                j = i * m
+                x[blk(j)] = Phi[j - 1] @ x[blk(j - 1)] + rhs[blk(j)]
+            return x
+        x = f_rel(x)
+        if kind == O.RELAX_FCF:
+            x = f_rel(c_rel(x))
+        return x
+
+    f = np.zeros((N + 1) * q)
+    f[:q] = u0[0]
+    Uinit = rng.standard_normal((N + 1, 1, q))
+    x = Uinit.reshape(-1).copy()
+    x[:q] = u0[0]
+    x = relax_level(x, f, Phi0, N, relax)
+    r0 = (f - A0 @ x)[cidx(N)]                                   # level-1 right-hand side of the correction equation
+    d1 = relax_level(np.zeros_like(r0), r0, Phi1, N // m, relax)  # zero guess; its point-0 row: d1[0] = r0[0] = 0
+    r1 = (r0 - A1 @ d1)[cidx(N // m)]
+    d1[cidx(N // m)] += np.linalg.solve(A2, r1)
+    d1 = relax_level(d1, r0, Phi1, N // m, O.RELAX_F)
+    x[cidx(N)] += d1
+    x = relax_level(x, f, Phi0, N, O.RELAX_F)
+
+    U, hist, _ = O.fas_forward(W, b, u0, h, m, 3, 1, relax, 1, DENSE, IDENT, init=2, U_init=Uinit)
+    np.testing.assert_allclose(U.reshape(-1), x, rtol=1e-11, atol=1e-12)
+    assert abs(hist[0] - np.linalg.norm(r0)) < 1e-12 * max(1.0, np.linalg.norm(r0))
+    # and it is a different iterate from the two-level one (the pin would not notice a skipped level otherwise)
+    U2, _, _ = O.fas_forward(W, b, u0, h, m, 2, 1, relax, 1, DENSE, IDENT, init=2, U_init=Uinit)
+    assert np.abs(U2 - U).max() > 1e-6
+
+
 # ---------------------------------------------------------------------------------------
 # Brute force on a tiny nonlinear scalar instance: an independent pure-Python evaluation of the
 # system rows checks the coarse equation L_H(V) = L_H(Ubar) + R_H and the residual norm
