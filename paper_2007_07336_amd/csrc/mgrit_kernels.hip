@@ -664,6 +664,24 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
   const WT* Wp = reinterpret_cast<const WT*>(a.W) + layer * a.wsize;
   typedef typename DRaw<WT>::type DR;
 
+  // 16-wide variant: the nine [C_out][C_in] slices are 9 x 16 x 16 floats in all.  They are requested first (their
+  // latency hides behind the patch loads), written to LDS once, and the taps run without a weight ring and
+  // without barriers between them.
+  constexpr int WALL = N16 ? 3 : 1;           // 16-byte pieces per thread: 9 taps x 16 rows x 4 pieces = 576 <= 3 x 256
+  uint4 wall[WALL];
+  unsigned wallmask = 0;
+  if constexpr (N16) {
+#pragma unroll
+    for (int i = 0; i < WALL; ++i) {
+      const int p = tid + NT * i;
+      const int tap = p >> 6, row = (p >> 2) & 15, kc = (p & 3) * 4;
+      const bool ok = p < 576 && row < C && kc < C;
+      const unsigned off = ok ? (unsigned)((row * 9 + tap) * C + kc) : 0u;
+      wallmask |= ok ? (1u << i) : 0u;
+      wall[i] = *reinterpret_cast<const uint4*>(Wp + off);
+    }
+  }
+
   // ---- input patch -> LDS (converted to the operand type).  The tile's own pixels are loaded in the
   // arrangement of the epilogue (lane -> 4 channels of a pixel row, NIT rows per 32-pixel block), so the
   // float values stay in registers as the skip-connection operand and the state is read from memory once;
@@ -687,7 +705,7 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
     // halo: patch rows 0 and TH+1 (image rows y0-1 and y0+TH), interior columns only
     const int cq = Cp / 4;
     const int htotal = 2 * Wd * cq;
-    constexpr int HU = 4;
+    constexpr int HU = N16 ? 1 : 4;          // the 16-wide variant has small halos: one piece per thread and pass
     for (int p0 = tid; p0 < htotal; p0 += NT * HU) {
       float4 v[HU];
       DR d[HU];
@@ -783,8 +801,10 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
       }
     }
   };
-  load_w(wreg[0], wmask[0], 0);
-  load_w(wreg[1], wmask[1], 1);
+  if constexpr (!N16) {
+    load_w(wreg[0], wmask[0], 0);
+    load_w(wreg[1], wmask[1], 1);
+  }
 
   // A-operand rows of this lane: 32x32 blocks -> pixel (wave*TM + i)*32 + lane%32;
   // 16x16 blocks -> pixel wave*64 + 16*b + lane%16 (k group lane/16)
@@ -809,35 +829,55 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
   for (int i = 0; i < 4; ++i) acc16[i] = floatx4{0.f, 0.f, 0.f, 0.f};
 
   const bool wave_active = (wave * TM) * 32 < npx;
-  WT* wbuf[2] = {wts, wts + CW * CS};
-  store_w(wreg[0], wmask[0], wbuf[0]);
-  load_w(wreg[0], wmask[0], 2);
-  __syncthreads();                            // patch and tap 0 are in LDS
-  for (int tap0 = 0; tap0 < 9; tap0 += 2) {
+  if constexpr (N16) {
+    // all nine slices to LDS: [tap][C_out][CS]
 #pragma unroll
-    for (int sidx = 0; sidx < 2; ++sidx) {
-      const int tap = tap0 + sidx;
-      if (tap < 9) {
-        // buffer sidx holds tap; register set 1-sidx holds tap+1, set sidx has tap+2 in flight
-        if (tap + 1 < 9) store_w(wreg[1 - sidx], wmask[1 - sidx], wbuf[1 - sidx]);
-        if (tap + 3 < 9) load_w(wreg[1 - sidx], wmask[1 - sidx], tap + 3);
-        if (wave_active) {
-          const int toff = ((tap / 3) * PW + (tap % 3)) * CS;
-          const WT* wt = wbuf[sidx];
-          for (int ks = 0; ks < Cp; ks += KSTEP) {
-            if constexpr (N16) {
-              // lane (r16, kq) feeds k = ks + 4 kq .. + 3, one value per instruction (any fixed pairing of
-              // the lanes' k values is a valid order of the sum)
-              const float4 bf = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(wt) + r16 * CS + ks + 4 * kq);
+    for (int i = 0; i < WALL; ++i) {
+      const int p = tid + NT * i;
+      if (p < 576) {
+        const int tap = p >> 6, row = (p >> 2) & 15, kc = (p & 3) * 4;
+        uint4 v = wall[i];
+        if (!((wallmask >> i) & 1u)) v = make_uint4(0, 0, 0, 0);
+        *reinterpret_cast<uint4*>(&wts[(tap * 16 + row) * CS + kc]) = v;
+      }
+    }
+    __syncthreads();                          // patch and weights are in LDS
+    if (wave_active) {
+      const float* pf = reinterpret_cast<const float*>(patch);
+      const float* wf = reinterpret_cast<const float*>(wts);
 #pragma unroll
-              for (int i = 0; i < 4; ++i) {
-                const float4 af = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(patch) + aoff[i] + toff + ks + 4 * kq);
-                acc16[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.x, bf.x, acc16[i], 0, 0, 0);
-                acc16[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.y, bf.y, acc16[i], 0, 0, 0);
-                acc16[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.z, bf.z, acc16[i], 0, 0, 0);
-                acc16[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.w, bf.w, acc16[i], 0, 0, 0);
-              }
-            } else {
+      for (int tap = 0; tap < 9; ++tap) {
+        const int toff = ((tap / 3) * PW + (tap % 3)) * CS;
+        // lane (r16, kq) feeds k = 4 kq .. + 3, one value per instruction (any fixed pairing of the lanes'
+        // k values is a valid order of the sum)
+        const float4 bf = *reinterpret_cast<const float4*>(wf + (tap * 16 + r16) * CS + 4 * kq);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float4 af = *reinterpret_cast<const float4*>(pf + aoff[i] + toff + 4 * kq);
+          acc16[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.x, bf.x, acc16[i], 0, 0, 0);
+          acc16[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.y, bf.y, acc16[i], 0, 0, 0);
+          acc16[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.z, bf.z, acc16[i], 0, 0, 0);
+          acc16[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.w, bf.w, acc16[i], 0, 0, 0);
+        }
+      }
+    }
+  } else {
+    WT* wbuf[2] = {wts, wts + CW * CS};
+    store_w(wreg[0], wmask[0], wbuf[0]);
+    load_w(wreg[0], wmask[0], 2);
+    __syncthreads();                            // patch and tap 0 are in LDS
+    for (int tap0 = 0; tap0 < 9; tap0 += 2) {
+#pragma unroll
+      for (int sidx = 0; sidx < 2; ++sidx) {
+        const int tap = tap0 + sidx;
+        if (tap < 9) {
+          // buffer sidx holds tap; register set 1-sidx holds tap+1, set sidx has tap+2 in flight
+          if (tap + 1 < 9) store_w(wreg[1 - sidx], wmask[1 - sidx], wbuf[1 - sidx]);
+          if (tap + 3 < 9) load_w(wreg[1 - sidx], wmask[1 - sidx], tap + 3);
+          if (wave_active) {
+            const int toff = ((tap / 3) * PW + (tap % 3)) * CS;
+            const WT* wt = wbuf[sidx];
+            for (int ks = 0; ks < Cp; ks += KSTEP) {
               const WT* ap[TM];
               const WT* bp[TN];
 #pragma unroll
@@ -847,8 +887,8 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
               mma_step<TM, TN>(ap, bp, acc, g);
             }
           }
+          __syncthreads();                      // tap+1 visible; everyone is done with this buffer
         }
-        __syncthreads();                      // tap+1 visible; everyone is done with this buffer
       }
     }
   }
@@ -884,7 +924,8 @@ int conv_tile_rows(int Himg, int Wimg, int C, int dtype) {
   const int kstep = n16 ? 16 : dtype == 0 ? 8 : 16, pad = dtype == 0 ? 4 : 8, es = dtype == 0 ? 4 : 2;
   const int Cp = (C + kstep - 1) / kstep * kstep, CS = Cp + pad;
   const int cw = n16 ? 16 : C <= 32 ? 32 : 64;
-  while (thmax > 1 && ((size_t)(thmax + 2) * (Wimg + 2) + 2 * cw) * CS * es > 72 * 1024) --thmax;
+  const int wslices = n16 ? 9 : 2;              // weight slices resident in LDS
+  while (thmax > 1 && ((size_t)(thmax + 2) * (Wimg + 2) + wslices * cw) * CS * es > 72 * 1024) --thmax;
   const int ntiles = (Himg + thmax - 1) / thmax;
   return (Himg + ntiles - 1) / ntiles;        // balanced tile height
 }
@@ -895,7 +936,7 @@ static size_t conv_smem_bytes(const StepArgs& a, int dtype) {
   const int kstep = n16 ? 16 : dtype == 0 ? 8 : 16, pad = dtype == 0 ? 4 : 8, es = dtype == 0 ? 4 : 2;
   const int Cp = (a.Nf + kstep - 1) / kstep * kstep, CS = Cp + pad;
   const int cw = n16 ? 16 : a.Nf <= 32 ? 32 : 64;
-  const size_t main_loop = ((size_t)(a.TH + 2) * (a.Wimg + 2) + 2 * cw) * CS * es;   // patch + 2 tap buffers
+  const size_t main_loop = ((size_t)(a.TH + 2) * (a.Wimg + 2) + (n16 ? 9 : 2) * cw) * CS * es;   // patch + weight slices
   const size_t staging = (size_t)4 * 32 * (cw + 4) * 4;             // epilogue staging buffer
   return main_loop > staging ? main_loop : staging;
 }
