@@ -19,6 +19,10 @@
  * no host outputs) consists of kernel launches only, so it may be recorded into a HIP graph by
  * stream capture and replayed.
  *
+ * Environment.  MGRIT_NO_SWEEP=1 makes the library use one launch per layer step also where it would
+ * fuse the steps of an F-relaxation sweep into one launch (dense layers of width 128 or 256 with many
+ * coarse intervals); results agree with the fused path to rounding.  Read at every call; diagnostic.
+ *
  * Layouts (all row-major, last index fastest):
  *   dense: state [B][q] float;  W [N][q_out][q_in];  b [N][q] float
  *   conv : state [B][Himg][Wimg][C] float (NHWC);  W [N][C_out][3][3][C_in];  b [N][C] float
