@@ -44,13 +44,14 @@ def layer_steps_per_solve(sizes, m, relax, iters):
         if l == L - 1:
             return sizes[l]
         Nc = sizes[l + 1]
-        n = (m - 1) * Nc if opening else 0
+        nF = sizes[l] - Nc           # F-points: (m - 1) per interval and the trailing ones
+        n = nF if opening else 0
         if relax == 1:
-            n += Nc + (m - 1) * Nc
+            n += Nc + nF
         n += Nc                      # C-point residual
         n += Nc                      # FAS right-hand side (coarse step)
         n += cyc(l + 1, True)
-        n += (m - 1) * Nc            # F-relaxation after the correction
+        n += nF                      # F-relaxation after the correction
         return n
 
     return sum(cyc(0, k == 0) for k in range(iters))

@@ -51,8 +51,7 @@ extern "C" {
 enum {
   MGRIT_OK = 0,
   MGRIT_ERR_POINTER = -1,     /* required pointer NULL or not 256-byte aligned              */
-  MGRIT_ERR_PROBLEM = -2,     /* invalid problem: N < 1, m < 2, bad enum, a level that must
-                                 be coarsened is not divisible by m, sizes <= 0, ...         */
+  MGRIT_ERR_PROBLEM = -2,     /* invalid problem: N < 1, m < 2, bad enum, sizes <= 0, ...    */
   MGRIT_ERR_WORKSPACE = -3,   /* workspace smaller than mgrit_*_workspace_bytes()            */
   MGRIT_ERR_UNSUPPORTED = -4, /* valid request that this build does not implement            */
   MGRIT_ERR_NONFINITE = -5,   /* a residual norm came out NaN or Inf                         */
@@ -97,7 +96,13 @@ typedef struct mgrit_problem {
 } mgrit_problem_t;
 
 /* Level hierarchy (Sec. III-C: every m-th layer of a level is also a member of the next
- * coarser level).  Host only, integer only.  n_levels <- number of levels L; N_l[l] <- steps
+ * coarser level).  Coarsening goes on while fewer than max_levels levels exist and the level
+ * has more than min_coarse steps and at least m of them; N_{l+1} = floor(N_l / m), and a level
+ * whose size is not a multiple of m ends in N_l mod m trailing F-points, which F-relaxation
+ * updates behind the last C-point (a case the paper does not treat).  This is the hierarchy of
+ * the forward solve; the adjoint solve uses the mirror image, counted from layer N (its
+ * level-l points are the fine points N - j m^l).
+ * Host only, integer only.  n_levels <- number of levels L; N_l[l] <- steps
  * on level l (array of MGRIT_MAX_LEVELS entries); fine_index <- concatenation over levels of
  * the fine point index of every point, sum_l (N_l + 1) entries.  N_l and fine_index may be
  * NULL (then only the count is returned).  Errors: MGRIT_ERR_PROBLEM. */

@@ -214,14 +214,15 @@ def parameter_gradient(W, b, U, Lam, h, layer, kind):
 # ----------------------------------------------------------------------------------------
 def level_sizes(N, m, max_levels, min_coarse):
     """Number of steps on each level.  Coarsening continues while fewer than max_levels levels
-    exist and the current level has more than min_coarse steps; a level that must be
-    coarsened but is not divisible by m is an error."""
+    exist and the current level has more than min_coarse steps and at least one whole coarse
+    interval (m steps).  The C-points of a level are its points 0, m, 2m, ...; a level whose size
+    is not a multiple of m ends in fewer than m trailing F-points behind its last C-point (the
+    paper does not treat this case; every m-th layer is coarse, Sec. III-C, so the rest can only
+    be fine), and the next level has floor(N_l / m) steps."""
     if N < 1 or m < 2 or max_levels < 1:
         raise ValueError("invalid hierarchy parameters")
     sizes = [N]
-    while len(sizes) < max_levels and sizes[-1] > max(min_coarse, 1):
-        if sizes[-1] % m != 0:
-            raise ValueError("level size not divisible by the coarsening factor")
+    while len(sizes) < max_levels and sizes[-1] > max(min_coarse, 1) and sizes[-1] >= m:
         sizes.append(sizes[-1] // m)
     return sizes
 
@@ -238,11 +239,14 @@ def level_map(N, m, max_levels, min_coarse):
 # solve are the same code.  phi(l, j, u) maps the state at point j of level l to point j+1.
 # ----------------------------------------------------------------------------------------
 def _f_relax(l, U, g, m, phi):
-    n_int = (U.shape[0] - 1) // m
+    Nl = U.shape[0] - 1
+    n_int = Nl // m
     for i in range(n_int):
         for k in range(1, m):
             j = i * m + k
             U[j] = phi(l, j - 1, U[j - 1]) + g[j]
+    for j in range(n_int * m + 1, Nl + 1):         # trailing F-points behind the last C-point
+        U[j] = phi(l, j - 1, U[j - 1]) + g[j]
 
 
 def _c_relax(l, U, g, m, phi):
@@ -358,9 +362,10 @@ def fas_adjoint(W, b, U, lamN, h, m, max_levels, min_coarse, relax, max_iter, la
                 tol=0.0, norm_kind=0, init=1, Lam_init=None):
     """Adjoint MGRIT-FAS solve linearised about the states U, then the parameter gradient.
 
-    The same cycle runs on the reversed layer axis: reversed point j' = N_l - j, so the sweep
-    j' -> j'+1 is the adjoint step from point j+1 to point j, which uses the state and
-    parameters of fine layer j c^l (the first layer of the coarse interval) and step h_l.
+    The same cycle runs on the reversed layer axis, whose level-l point j' is fine point
+    N - j' c^l: the sweep j' -> j'+1 is the adjoint step from fine point n + c^l to fine point
+    n = N - (j'+1) c^l, which uses the state and parameters of fine layer n (the first layer of
+    the coarse interval) and step h_l.
     Returns (Lam [N+1,...], dW, db, residual history, cycles done).
     """
     W = _f64(W)
@@ -371,8 +376,8 @@ def fas_adjoint(W, b, U, lamN, h, m, max_levels, min_coarse, relax, max_iter, la
     sizes = level_sizes(N, m, max_levels, min_coarse)
 
     def psi(l, jr, lam):
-        j = sizes[l] - (jr + 1)            # reversed sweep jr -> jr+1 lands on point j
-        n = j * m ** l
+        n = N - (jr + 1) * m ** l          # reversed sweep jr -> jr+1 lands on fine point n (the hierarchy of
+        #                                    the reversed axis counts from point N: its level-l point j is N - j c^l)
         return adjoint_step(lam, U[n], W[n], b[n], h * m ** l, _kind_of(layer, n), kind)
 
     Xi = None if Lam_init is None else np.asarray(Lam_init, np.float64)[::-1]

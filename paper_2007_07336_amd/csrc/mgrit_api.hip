@@ -42,15 +42,16 @@ struct Plan {
 };
 
 // Level hierarchy (Sec. III-C): coarsen by m while fewer than max_levels levels exist and the
-// current level has more than min_coarse steps.
+// current level has more than min_coarse steps and at least one whole coarse interval.  Points
+// 0, m, 2m, .. of a level are its C-points; a level whose size is not a multiple of m ends in
+// fewer than m trailing F-points, and the next level has floor(N_l / m) steps.
 int build_levels(const mgrit_problem_t* p, int* L, int* Nl) {
   if (!p) return MGRIT_ERR_POINTER;
   if (p->N < 1 || p->m < 2 || p->max_levels < 1 || p->max_levels > MGRIT_MAX_LEVELS) return MGRIT_ERR_PROBLEM;
   const int minc = p->min_coarse < 1 ? 1 : p->min_coarse;
   int n = 1;
   Nl[0] = p->N;
-  while (n < p->max_levels && Nl[n - 1] > minc) {
-    if (Nl[n - 1] % p->m != 0) return MGRIT_ERR_PROBLEM;
+  while (n < p->max_levels && Nl[n - 1] > minc && Nl[n - 1] >= p->m) {
     Nl[n] = Nl[n - 1] / p->m;
     ++n;
   }
@@ -141,8 +142,9 @@ int make_plan(const mgrit_problem_t* p, Plan* pl, int fcP = 0) {
 
 // The cycle is written once, in "sweep order": sweep point 0 carries the known value and the
 // sweep advances to sweep point N_l.  The forward solve sweeps up the layer axis; the adjoint
-// solve sweeps down it, so sweep point js of its fine level is natural point N - js.  Only the
-// caller's fine-level array is stored in natural order; all workspace arrays are in sweep order.
+// solve sweeps down it, so sweep point js of its level l is natural fine point N - js m^l (its
+// hierarchy counts from layer N, whatever N mod m is).  Only the caller's fine-level array is
+// stored in natural order; all workspace arrays are in sweep order.
 struct Solver {
   const mgrit_problem_t* p;
   Plan pl;
@@ -170,7 +172,7 @@ struct Solver {
   }
   // layer index used by the sweep step that lands on sweep point js of level l
   PtMap layer_map(int l, long long js0, long long jstride) const {
-    if (adjoint) return PtMap{(pl.Nl[l] - js0) * pl.mpow[l], -jstride * pl.mpow[l]};
+    if (adjoint) return PtMap{p->N - js0 * pl.mpow[l], -jstride * pl.mpow[l]};
     return PtMap{(js0 - 1) * pl.mpow[l], jstride * pl.mpow[l]};
   }
   StepArgs base_args(int l, long long js0, long long jstride) const {
@@ -257,6 +259,8 @@ struct Solver {
     return sweep_blocks(pl.M, pl.Nl[l + 1]) >= 128;
   }
   void f_relax(int l) {                                        // Sec. III-C, Fig. 3
+    const int Nc = pl.Nl[l + 1];
+    const int tail = pl.Nl[l] - Nc * p->m;                     // F-points behind the last C-point (< m)
     if (use_sweep(l)) {
       SweepArgs a;
       memset(&a, 0, sizeof(a));
@@ -266,14 +270,15 @@ struct Solver {
       a.X = X[l]; a.xb = unit.base; a.xs = unit.stride * p->m; a.xk = unit.stride;
       if (g[l] && !plain_rhs) { a.G = g[l]; a.gb = 0; a.gs = p->m; }
       a.W = W; a.bias = bias; a.Dm = Dm;
-      if (adjoint) { a.lb = (pl.Nl[l] - 1) * mp; a.ls = -(long long)p->m * mp; a.lk = -mp; }
+      if (adjoint) { a.lb = p->N - mp;           a.ls = -(long long)p->m * mp; a.lk = -mp; }
       else         { a.lb = 0;                   a.ls = (long long)p->m * mp;  a.lk = mp; }
-      a.hs = pl.hl[l]; a.act = act; a.nsteps = p->m - 1; a.nchains = pl.Nl[l + 1];
+      a.hs = pl.hl[l]; a.act = act; a.nsteps = p->m - 1; a.nchains = Nc;
       a.M = pl.M; a.q = pl.Nf; a.E = pl.E; a.wsize = pl.wsize;
       if (err == hipSuccess) chk(launch_sweep(a, p->dtype, s));
+      for (int k = 1; k <= tail; ++k) propagate(l, (long long)Nc * p->m + k, p->m, 1);
       return;
     }
-    for (int k = 1; k < p->m; ++k) propagate(l, k, p->m, pl.Nl[l + 1]);
+    for (int k = 1; k < p->m; ++k) propagate(l, k, p->m, Nc + (k <= tail ? 1 : 0));
   }
   void c_relax(int l) { propagate(l, p->m, p->m, pl.Nl[l + 1]); }
 

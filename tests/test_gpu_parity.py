@@ -83,6 +83,11 @@ DENSE_CASES = [
     I.reduced(I.cfg5(1), name="dense_bf16_q264_B260_N128_m2_bigtile", q=264, B=260, N=128, m=2, max_levels=2,
               head_classes=0),
     I.reduced(I.cfg2(1), name="dense_fp32_q136_B130_N128_m2_bigtile", q=136, B=130, N=128, m=2, max_levels=2),
+    # level sizes that are no multiples of m: trailing F-points behind the last C-point (79 -> 19 -> 4, 23 -> 11 -> 5)
+    I.reduced(I.cfg2(3), name="dense_fp32_q72_B37_N79_m4_L3_trailing", q=72, B=37, N=79, bias_var=0.1),
+    I.reduced(I.cfg2(2), name="dense_fp32_q40_B9_N23_m2_L3_F_trailing", q=40, B=9, N=23, m=2, relax=I.RELAX_F, act=I.TANH),
+    I.reduced(I.cfg5(2), name="dense_bf16_q136_B50_N70_m4_trailing", q=136, B=50, N=70, m=4, head_classes=0),
+    I.reduced(I.cfg2(1), name="dense_fp32_q16_N3_m4_too_short_to_coarsen", q=16, B=3, N=3, m=4),
 ]
 
 # widths that are multiples of 128 (the fused sweep kernel's block width) at launch sizes below its threshold:
@@ -116,6 +121,8 @@ CONV_CASES = [
     I.reduced(I.cfg3(1), name="conv_fp32_c40_9x7_B2_N8", B=2, C=40, Himg=9, Wimg=7, N=8, m=2, lifted_input=False),
     I.reduced(I.cfg4(2), name="conv_bf16_c64_12x10_B2_N64_L3", B=2, Himg=12, Wimg=10, N=64),
     I.reduced(I.cfg4(1), name="conv_bf16_c24_32x32_B1_N16_m4", B=1, C=24, N=16, m=4, max_levels=2),
+    I.reduced(I.cfg3(2), name="conv_fp32_c16_14x12_B3_N19_m4_trailing", B=3, Himg=14, Wimg=12, N=19),
+    I.reduced(I.cfg4(2), name="conv_bf16_c64_12x10_B2_N45_m3_L3_trailing", B=2, Himg=12, Wimg=10, N=45, m=3),
 ]
 
 
@@ -141,6 +148,8 @@ NESTED_CASES = [
     I.reduced(I.cfg2(1), name="nested_dense_fp32_q16_N16_m2_deep", q=16, B=3, N=16, m=2, max_levels=16, bias_var=0.1),
     I.reduced(I.cfg3(1), name="nested_conv_fp32_c16_10x9_B2_N16_L3", B=2, Himg=10, Wimg=9, N=16, m=2, max_levels=3),
     I.reduced(I.cfg4(1), name="nested_conv_bf16_c64_8x8_B3_N16_m4", B=3, Himg=8, Wimg=8, N=16, m=4, max_levels=2),
+    I.reduced(I.cfg2(2), name="nested_dense_fp32_q72_B37_N79_L3_trailing", q=72, B=37, N=79, bias_var=0.1),
+    I.reduced(I.cfg3(1), name="nested_conv_fp32_c16_10x9_B2_N23_m2_L3_trailing", B=2, Himg=10, Wimg=9, N=23, m=2, max_levels=3),
 ]
 
 
@@ -154,6 +163,7 @@ def test_nested_iteration_start_forward(wl):
     I.reduced(I.cfg5(2), name="nested_adj_dense_fp32_q72_B37_N64_m4", q=72, B=37, N=64, m=4, dtype=I.FP32),
     I.reduced(I.cfg5(1), name="nested_adj_dense_bf16_q136_B50_N64_m4", q=136, B=50, N=64, m=4),
     I.reduced(I.cfg3(1), name="nested_adj_conv_fp32_c16_10x9_B2_N16", B=2, Himg=10, Wimg=9, N=16, act=I.TANH),
+    I.reduced(I.cfg5(2), name="nested_adj_dense_fp32_q72_B37_N79_m4_trailing", q=72, B=37, N=79, m=4, dtype=I.FP32),
 ], ids=lambda w: w.name)
 def test_nested_iteration_start_adjoint(wl):
     _announce(wl.name)
@@ -246,6 +256,11 @@ ADJ_CASES = [
     I.reduced(I.cfg5(2), name="adj_chain_fp32_q256_relu_F_L2", q=256, B=12, N=32, m=4, dtype=I.FP32, act=I.RELU,
               max_levels=2, relax=I.RELAX_F),
     I.reduced(I.cfg5(1), name="adj_fp32_q512_B8_N16_m4", q=512, B=8, N=16, m=4, dtype=I.FP32),
+    # level sizes that are no multiples of m: the adjoint hierarchy counts from layer N, its trailing F-points end at layer 0
+    I.reduced(I.cfg5(3), name="adj_dense_fp32_q72_B37_N79_m4_L3_trailing", q=72, B=37, N=79, m=4, max_levels=3, dtype=I.FP32),
+    I.reduced(I.cfg5(2), name="adj_dense_bf16_q136_B50_N70_m4_trailing", q=136, B=50, N=70, m=4),
+    I.reduced(I.cfg5(2), name="adj_dense_fp32_q40_N23_m2_L3_relu_F_trailing", q=40, B=12, N=23, m=2, max_levels=3,
+              dtype=I.FP32, act=I.RELU, relax=I.RELAX_F),
 ]
 
 
@@ -291,6 +306,8 @@ CONV_ADJ_CASES = [
               lifted_input=False, act=I.TANH),
     I.reduced(I.cfg3(1), name="adj_conv_fp32_c16_7x1_B2_N4", B=2, C=16, Himg=7, Wimg=1, N=4, m=2,
               lifted_input=False, act=I.TANH),
+    I.reduced(I.cfg3(2), name="adj_conv_fp32_c16_10x9_B2_N19_m4_trailing", B=2, Himg=10, Wimg=9, N=19, act=I.TANH),
+    I.reduced(I.cfg4(1), name="adj_conv_bf16_c64_8x8_B3_N22_m3_L3_trailing", B=3, Himg=8, Wimg=8, N=22, m=3, max_levels=3),
 ]
 
 
@@ -402,6 +419,11 @@ SWEEP_CASES = [
               head_classes=0),
     # deep enough that the middle level's sweeps are fused too: they carry the FAS right-hand side
     I.reduced(I.cfg2(1), name="sweep_fp32_q128_B37_N1024_m4_L3_rhs", q=128, B=37, N=1024, bias_var=0.1, act=I.TANH),
+    # trailing F-points: the fused launch covers the whole intervals, single-group launches the rest
+    # (190 -> 47, two trailing points; 1030 -> 257 -> 64, two on the fine and one on the middle level)
+    I.reduced(I.cfg2(2), name="sweep_fp32_q256_B70_N190_m4_L2_trailing", q=256, B=70, N=190, max_levels=2, bias_var=0.1),
+    I.reduced(I.cfg5(1), name="sweep_bf16_q128_B40_N1030_m4_L3_trailing", q=128, B=40, N=1030, m=4, max_levels=3,
+              head_classes=0),
 ]
 
 
@@ -441,6 +463,9 @@ SWEEP_ADJ_CASES = [
     I.reduced(I.cfg5(1), name="adj_sweep_fp32_q256_B100_N96_m3_F", q=256, B=100, N=96, m=3, max_levels=2, dtype=I.FP32,
               relax=I.RELAX_F),
     I.reduced(I.cfg5(1), name="adj_sweep_bf16_q128_B40_N1024_m4_L3_rhs", q=128, B=40, N=1024, m=4, max_levels=3),
+    I.reduced(I.cfg5(2), name="adj_sweep_fp32_q256_B70_N190_m4_trailing", q=256, B=70, N=190, m=4, max_levels=2, dtype=I.FP32),
+    I.reduced(I.cfg5(1), name="adj_sweep_fp32_q128_B40_N1030_m4_L3_trailing", q=128, B=40, N=1030, m=4, max_levels=3,
+              dtype=I.FP32),
 ]
 
 

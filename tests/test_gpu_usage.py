@@ -143,13 +143,14 @@ def test_gradient_descent_with_early_stopped_multigrid(layer):
     assert eW <= 1e-2
 
 
+@pytest.mark.parametrize("N", [64, 79])
 @pytest.mark.parametrize("relax,levels,cycles", [(I.RELAX_F, 2, 1), (I.RELAX_FCF, 3, 2), (I.RELAX_FCF, 2, 3)])
-def test_layer_step_count_of_the_benchmark_matches_the_launch_schedule(relax, levels, cycles):
+def test_layer_step_count_of_the_benchmark_matches_the_launch_schedule(relax, levels, cycles, N):
     """bench.py's throughput numerator (layer steps per solve, from a closed formula) equals what the library
     actually launches: the launch trace counts one unit per group of every step launch."""
     import paper_2007_07336_amd as M
     import bench
-    wl = I.reduced(I.cfg2(cycles), name="dense_fp32_step_count", q=64, B=8, N=64, m=4, max_levels=levels, relax=relax)
+    wl = I.reduced(I.cfg2(cycles), name="dense_fp32_step_count", q=64, B=8, N=N, m=4, max_levels=levels, relax=relax)
     _say(f"{wl.name} relax={relax} levels={levels} cycles={cycles}")
     data = I.generate(wl)
     gp = GpuProblem(wl, data)

@@ -96,8 +96,13 @@ def test_forward_argument_validation():
     assert _fwd(p, ws_bytes=M.mgrit_workspace_bytes(p) - 1) == Bd.MGRIT_ERR_WORKSPACE
     for bad in (dict(N=0), dict(m=1), dict(max_levels=0), dict(max_levels=17), dict(relax=2), dict(cycle=1),
                 dict(max_iter=0), dict(norm_kind=2), dict(layer=2), dict(act=5), dict(dtype=3), dict(init=4), dict(init=-1),
-                dict(h=0.0), dict(B=0), dict(q=0), dict(N=18, m=4), dict(N=24, m=4, max_levels=3)):
+                dict(h=0.0), dict(B=0), dict(q=0)):
         assert _fwd(_problem(**bad)) == Bd.MGRIT_ERR_PROBLEM, bad
+    for ragged in (dict(N=18, m=4), dict(N=24, m=4, max_levels=3), dict(N=3, m=4)):   # level sizes that are no multiples of m are valid
+        assert _fwd(_problem(**ragged)) == Bd.MGRIT_ERR_WORKSPACE, ragged
+    assert M.mgrit_level_map(_problem(N=18, m=4))[0] == [18, 4]
+    assert M.mgrit_level_map(_problem(N=24, m=4, max_levels=3))[0] == [24, 6, 1]
+    assert M.mgrit_level_map(_problem(N=3, m=4))[0] == [3]
     for uns in (dict(q=12), dict(N=65536, m=2, max_levels=2), dict(layer=1, C=12, Himg=4, Wimg=4), dict(layer=1, C=128, Himg=4, Wimg=4),
                 dict(layer=1, C=16, Himg=4, Wimg=300)):
         assert _fwd(_problem(**uns)) == Bd.MGRIT_ERR_UNSUPPORTED, uns

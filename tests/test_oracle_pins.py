@@ -106,11 +106,12 @@ def test_linear_product_of_propagators():
 # Two-level exactness (Sec. III-C, Alg. 1): with F-relaxation the first k coarse intervals
 # are exact after k cycles, for any initial guess; FCF advances two intervals per cycle.
 # ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("N", [12, 13, 14])            # 13, 14: trailing F-points behind the last C-point
 @pytest.mark.parametrize("layer", [DENSE, CONV])
 @pytest.mark.parametrize("relax,per_cycle", [(O.RELAX_F, 1), (O.RELAX_FCF, 2)])
-def test_two_level_exact_after_enough_cycles(layer, relax, per_cycle):
+def test_two_level_exact_after_enough_cycles(layer, relax, per_cycle, N):
     rng = np.random.default_rng(5)
-    N, m = 12, 3
+    m = 3
     h = 1.0 / N
     if layer == DENSE:
         W, b, u0 = _dense_problem(rng, N, 5, 3, scale=2.0)
@@ -124,7 +125,7 @@ def test_two_level_exact_after_enough_cycles(layer, relax, per_cycle):
         exact_upto = min(N, (per_cycle * k + 1) * m - 1)     # all points of the exact intervals
         err = np.abs(U[:exact_upto + 1] - Us[:exact_upto + 1]).max()
         assert err < 1e-12, (k, err)
-        if per_cycle * k * m < N:                            # and the rest is NOT yet exact
+        if (per_cycle * k + 1) * m <= N:                     # and the rest is NOT yet exact
             assert np.abs(U[-1] - Us[-1]).max() > 1e-8
     assert np.abs(U - Us).max() < 1e-12
 
@@ -159,10 +160,11 @@ def test_fixed_point(levels, relax):
 # Linear F: one two-level FAS cycle equals the textbook linear two-grid correction scheme
 # assembled as dense matrices (Sec. III-A, Eq. (9)-(11))
 # ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("N,m", [(8, 2), (9, 2), (11, 3), (7, 4)])   # the last three end in F-points
 @pytest.mark.parametrize("relax", [O.RELAX_F, O.RELAX_FCF])
-def test_linear_two_level_equals_dense_two_grid(relax):
+def test_linear_two_level_equals_dense_two_grid(relax, N, m):
     rng = np.random.default_rng(7)
-    N, m, q, h = 8, 2, 2, 0.3
+    q, h = 2, 0.3
     W, b, u0 = _dense_problem(rng, N, q, 1, bias=False, scale=1.5)
     n = (N + 1) * q
     Phi = [np.eye(q) + h * W[k] for k in range(N)]
@@ -183,9 +185,8 @@ def test_linear_two_level_equals_dense_two_grid(relax):
 
     def f_relax(x):                       # exact solve of the F-rows given the C-values
         x = x.copy()
-        for i in range(Nc):
-            for k in range(1, m):
-                j = i * m + k
+        for j in range(1, N + 1):
+            if j % m:                     # every point that is not a multiple of m is an F-point
                 x[j * q:(j + 1) * q] = Phi[j - 1] @ x[(j - 1) * q:j * q]
         return x
 
@@ -348,6 +349,73 @@ def test_three_level_converges_to_serial(layer):
     assert all(hist[i + 1] < hist[i] for i in range(len(hist) - 1))
 
 
+@pytest.mark.parametrize("N,m", [(23, 2), (30, 4), (27, 3), (31, 3)])
+def test_three_level_with_trailing_f_points_converges_to_serial_forward_and_adjoint(N, m):
+    """Level sizes that are not multiples of m (23 -> 11 -> 5, 30 -> 7 -> 1, 27 -> 9 -> 3, 31 -> 10 -> 3):
+    the limit is still serial propagation and its gradient, and a converged solve is a fixed point."""
+    rng = np.random.default_rng(90 + N)
+    W, b, u0 = _dense_problem(rng, N, 5, 3)
+    h = 1.0 / N
+    assert O.level_sizes(N, m, 3, 1) == [N, N // m, N // m // m]
+    Us = O.serial_forward(W, b, u0, h, DENSE, TANH)
+    U, hist, it = O.fas_forward(W, b, u0, h, m, 3, 1, O.RELAX_FCF, 40, DENSE, TANH, tol=1e-13)
+    assert it < 40 and np.abs(U - Us).max() < 1e-11
+    U2, hist2, _ = O.fas_forward(W, b, u0, h, m, 3, 1, O.RELAX_F, 1, DENSE, TANH, init=2, U_init=Us)
+    assert np.abs(U2 - Us).max() < 1e-13 and hist2[0] < 1e-13
+    lamN = rng.standard_normal(u0.shape)
+    Ls, dWs, dbs = O.serial_backward(W, b, Us, lamN, h, DENSE, TANH)
+    Lam, dW, db, hist, it = O.fas_adjoint(W, b, Us, lamN, h, m, 3, 1, O.RELAX_FCF, 40, DENSE, TANH, tol=1e-13)
+    assert it < 40
+    np.testing.assert_allclose(Lam, Ls, atol=1e-11)
+    np.testing.assert_allclose(dW, dWs, atol=1e-11)
+    np.testing.assert_allclose(db, dbs, atol=1e-11)
+
+
+def test_adjoint_two_grid_with_trailing_f_points_equals_dense_two_grid_of_the_reversed_system():
+    """Linear layers, N = 7, m = 3: one adjoint cycle is the dense two-grid step for the system
+    lam^n - (I + h W^n)^T lam^{n+1} = 0, lam^N given, whose C-points are counted from layer N
+    (N, N-m, ...) and whose coarse step over [n, n+m] uses layer n with step m h."""
+    rng = np.random.default_rng(77)
+    N, m, q, h = 7, 3, 2, 0.3
+    W, b, u0 = _dense_problem(rng, N, q, 1, bias=False, scale=1.5)
+    U = np.zeros((N + 1, 1, q))
+    lamN = rng.standard_normal((1, q))
+    n = (N + 1) * q
+    PhiT = [(np.eye(q) + h * W[k]).T for k in range(N)]
+    A = np.eye(n)                                    # unknowns ordered by fine layer index
+    for k in range(N):
+        A[k * q:(k + 1) * q, (k + 1) * q:(k + 2) * q] = -PhiT[k]
+    f = np.zeros(n)
+    f[N * q:] = lamN[0]
+    Nc = N // m
+    cpts = [N - i * m for i in range(Nc + 1)]        # 7, 4, 1
+    AH = np.eye((Nc + 1) * q)                        # coarse unknown i sits at fine point N - i m
+    for i in range(Nc):
+        lo = N - (i + 1) * m
+        AH[(i + 1) * q:(i + 2) * q, i * q:(i + 1) * q] = -(np.eye(q) + m * h * W[lo]).T
+    cidx = np.concatenate([np.arange(c * q, c * q + q) for c in cpts])
+    Linit = rng.standard_normal((N + 1, 1, q))
+    x = Linit.reshape(-1).copy()
+    x[N * q:] = lamN[0]
+
+    def f_relax(x):
+        x = x.copy()
+        for j in range(N - 1, -1, -1):
+            if j not in cpts:
+                x[j * q:(j + 1) * q] = PhiT[j] @ x[(j + 1) * q:(j + 2) * q]
+        return x
+
+    x = f_relax(x)
+    r = f - A @ x
+    assert np.abs(np.delete(r, cidx)).max() < 1e-13
+    x[cidx] += np.linalg.solve(AH, r[cidx])
+    x = f_relax(x)
+    Lam, dW, db, hist, _ = O.fas_adjoint(W, b, U, lamN, h, m, 2, 1, O.RELAX_F, 1, DENSE, IDENT,
+                                         init=2, Lam_init=Linit)
+    np.testing.assert_allclose(Lam.reshape(-1), x, rtol=1e-11, atol=1e-12)
+    assert abs(hist[0] - np.linalg.norm(r[cidx])) < 1e-12
+
+
 def test_three_levels_with_coarsest_of_full_depth_equals_two_level():
     """max_levels=3 but min_coarse stops coarsening after one level -> identical to two-level."""
     rng = np.random.default_rng(10)
@@ -439,11 +507,12 @@ def test_serial_gradient_vs_autograd(layer, kind):
 # ---------------------------------------------------------------------------------------
 # Adjoint multigrid: mirror of the forward exactness; its limit is the serial gradient
 # ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("N", [12, 13, 14])            # 13, 14: the reversed axis ends in F-points at layer 0
 @pytest.mark.parametrize("layer", [DENSE, CONV])
 @pytest.mark.parametrize("relax,per_cycle", [(O.RELAX_F, 1), (O.RELAX_FCF, 2)])
-def test_adjoint_two_level_exactness(layer, relax, per_cycle):
+def test_adjoint_two_level_exactness(layer, relax, per_cycle, N):
     rng = np.random.default_rng(14)
-    N, m = 12, 3
+    m = 3
     h = 1.0 / N
     if layer == DENSE:
         W, b, u0 = _dense_problem(rng, N, 5, 3, scale=2.0)
@@ -459,7 +528,7 @@ def test_adjoint_two_level_exactness(layer, relax, per_cycle):
                                               init=2, Lam_init=Linit)
         lo = max(0, N - ((per_cycle * k + 1) * m - 1))    # exact from the top down to point lo
         assert np.abs(Lam[lo:] - Ls[lo:]).max() < 1e-12, k
-        if per_cycle * k * m < N:
+        if (per_cycle * k + 1) * m <= N:
             assert np.abs(Lam[0] - Ls[0]).max() > 1e-8
     np.testing.assert_allclose(Lam, Ls, atol=1e-12)
     np.testing.assert_allclose(dW, dWs, atol=1e-12)
@@ -502,18 +571,14 @@ def test_level_map_vs_enumeration():
             for max_levels in (1, 2, 3, 5):
                 for min_coarse in (1, 8):
                     # enumeration: level l holds every fine index divisible by m^l
-                    exp_sizes, ok = [N], True
-                    while len(exp_sizes) < max_levels and exp_sizes[-1] > min_coarse:
-                        if exp_sizes[-1] % m:
-                            ok = False
-                            break
-                        exp_sizes.append(exp_sizes[-1] // m)
-                    if not ok:
-                        with pytest.raises(ValueError):
-                            O.level_map(N, m, max_levels, min_coarse)
-                        continue
+                    # (a level with fewer than m steps has no whole coarse interval and is the coarsest)
                     sizes, fidx = O.level_map(N, m, max_levels, min_coarse)
-                    assert sizes == exp_sizes
+                    for l in range(len(sizes)):
+                        assert sizes[l] == len([n for n in range(1, N + 1) if n % (m ** l) == 0])
+                        if l + 1 < len(sizes):
+                            assert sizes[l] > min_coarse and sizes[l] >= m
+                    last = sizes[-1]
+                    assert len(sizes) == max_levels or last <= max(min_coarse, 1) or last < m
                     for l, idx in enumerate(fidx):
                         brute = [n for n in range(N + 1) if n % (m ** l) == 0]
                         assert list(idx) == brute
@@ -589,6 +654,22 @@ def test_nested_start_three_level_brute_force():
         n = 4 * j2
         f_point = _euler_dense(lvl2[j2], W[n], b[n], 2 * h, TANH)
         assert np.abs(U[n + 2] - f_point).max() < 1e-14
+
+
+def test_nested_start_three_level_brute_force_with_trailing_f_points():
+    """N = 7, m = 2: levels of 7, 3 and 1 steps.  Level 2 holds fine layers 0 and 4; on level 1 point 2
+    (fine layer 4) is injected, point 1 (layer 2) follows layer 0 and the trailing point 3 (layer 6)
+    follows layer 4, each by one step of 2h."""
+    rng = np.random.default_rng(33)
+    N, m, q, h = 7, 2, 3, 0.3
+    W, b, u0 = _dense_problem(rng, N, q, 2, scale=1.5)
+    U, _, _ = O.fas_forward(W, b, u0, h, m, 3, 1, O.RELAX_FCF, 0, DENSE, TANH, init=3)
+    u4 = _euler_dense(u0, W[0], b[0], 4 * h, TANH)
+    u2 = _euler_dense(u0, W[0], b[0], 2 * h, TANH)
+    u6 = _euler_dense(u4, W[4], b[4], 2 * h, TANH)
+    for n, ref in ((0, u0), (2, u2), (4, u4), (6, u6)):
+        assert np.abs(U[n] - ref).max() < 1e-14
+    assert np.abs(U[1::2]).max() == 0.0               # fine F-points are left for the first relaxation
 
 
 def test_nested_start_exact_for_layer_independent_constant_F():
