@@ -189,7 +189,10 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
   __syncthreads();
   if ((threadIdx.x & 63) == 0) red[w] = v;
   __syncthreads();
-  return (red[0] + red[1]) + (red[2] + red[3]);
+  // fixed order over the wavefronts of the workgroup (4, or 8 in the staged k-split kernel), two at a time
+  float s = (red[0] + red[1]) + (red[2] + red[3]);
+  for (int i = 4; i < (int)(blockDim.x >> 6); i += 2) s += red[i] + red[i + 1];
+  return s;
 }
 
 // XCD-aware workgroup order: hardware deals consecutive workgroup ids round-robin to the 8
@@ -486,6 +489,14 @@ __global__ __launch_bounds__(NT) void dense_step_kernel(StepArgs a) {
 // global memory into the MFMA source registers -- no LDS staging, no barrier in the k loop --
 // and the operands of the fused epilogue are requested before the k loop starts.  The four
 // partial tiles are summed through LDS in a fixed order.
+// STAGED (long contractions with at most 32 rows, e.g. a fully connected layer on 32 flattened images: such
+// a step only streams its weights): the direct fragment loads touch 32 cache lines per instruction and use
+// 32 bytes of each, which is fine for a few chunks but not for a 4096-long row.  Here a wavefront loads its
+// pieces of both operands with whole-line accesses (8 lanes per 128-byte row piece), passes them through an
+// LDS area of its own (no workgroup barrier in the k loop either) and reads the fragments from there; the
+// loads of its next two pieces are in flight meanwhile.  NW = 8 wavefronts split the contraction when the launch has
+// fewer workgroups than the chip has CUs: the time of such a launch is the number of chunks a wavefront walks
+// through times the memory latency.
 // ------------------------------------------------------------------------------------------
 template <typename WT> struct KsOp;
 template <> struct KsOp<float>  { static constexpr int KC = 64;  };   // 8 x (4 k per lane group) x 2 groups
@@ -516,13 +527,33 @@ __device__ __forceinline__ void ks_mma(const float4 (&af)[8], const float4 (&ag)
   }
 }
 
-template <typename WT, bool WS>
-__global__ __launch_bounds__(NT) void dense_ksplit_kernel(StepArgs a) {
+__device__ __forceinline__ void ks_piece(const float* ap, const float* bp, floatx16& acc) {
+  const float4 av = *reinterpret_cast<const float4*>(ap), bv = *reinterpret_cast<const float4*>(bp);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av.x, bv.x, acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av.y, bv.y, acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av.z, bv.z, acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av.w, bv.w, acc, 0, 0, 0);
+}
+__device__ __forceinline__ void ks_piece(const __bf16* ap, const __bf16* bp, floatx16& acc) {
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(ap), *reinterpret_cast<const bf16x8*>(bp),
+                                                acc, 0, 0, 0);
+}
+// LDS of the staged variant: per wavefront one [32][KC / 2 + PAD] area for each operand (144-byte rows)
+template <typename WT> constexpr size_t ksplit_staged_smem(int nw) {
+  return (size_t)nw * 2 * 32 * (KsOp<WT>::KC / 2 + Op<WT>::PAD) * sizeof(WT);
+}
+
+template <typename WT, bool WS, bool STAGED, int NW = 4>
+__global__ __launch_bounds__(NW * 64) void dense_ksplit_kernel(StepArgs a) {
+  static_assert(NW == 4 || (STAGED && NW == 8), "eight wavefronts only in the staged variant");
   constexpr int KC = KsOp<WT>::KC;
   constexpr bool BF = sizeof(WT) == 2;
   constexpr int KL = BF ? 8 : 4;                    // consecutive k a lane feeds per piece
-  __shared__ __attribute__((aligned(16))) float part[4][32][36];
-  __shared__ float red[4];
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];   // STAGED: the wavefronts' staging areas
+  __shared__ __attribute__((aligned(16))) float part_static[STAGED ? 1 : 4][32][36];
+  static_assert(!STAGED || ksplit_staged_smem<WT>(NW) >= sizeof(float) * NW * 32 * 36, "the partial tiles reuse the staging areas");
+  float (*part)[32][36] = STAGED ? reinterpret_cast<float (*)[32][36]>(smem_raw) : part_static;   // [NW][32][36]
+  __shared__ float red[NW];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, c = lane & 31;
   const int tiles_n = (a.Nf + 31) / 32;
   const int L = logical_block();
@@ -536,9 +567,10 @@ __global__ __launch_bounds__(NT) void dense_ksplit_kernel(StepArgs a) {
   typedef typename DRaw<WT>::type DR;
   const EpiPtrs e = epi_ptrs(a, gi, layer);
 
-  // ---- epilogue operands first (one float4 per thread: row tid/8, columns 4*(tid%8)..+3)
-  const int erow = m0 + (tid >> 3), ecol = n0 + 4 * (tid & 7);
-  const bool eok = erow < a.M && ecol < a.Nf;
+  // ---- epilogue operands first (one float4 per thread of the first four wavefronts: row tid/8, columns
+  // 4*(tid%8)..+3)
+  const int erow = m0 + ((tid & 255) >> 3), ecol = n0 + 4 * (tid & 7);
+  const bool eok = (NW == 4 || tid < 256) && erow < a.M && ecol < a.Nf;
   const unsigned eoff = eok ? (unsigned)(erow * a.Nf + ecol) : 0u;
   const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
   const bool dact = a.mode == MODE_DACT;
@@ -554,6 +586,84 @@ __global__ __launch_bounds__(NT) void dense_ksplit_kernel(StepArgs a) {
   const bool arow_ok = m0 + c < a.M, wrow_ok = n0 + c < a.Nf;
   const unsigned abase = arow_ok ? (unsigned)((m0 + c) * K) : 0u;
   const unsigned wbase = wrow_ok ? (unsigned)((n0 + c) * K) : 0u;
+  if constexpr (STAGED) {
+    // pieces of KH = KC / 2 values of k (128 bytes of a weight row): two of them are in flight in two register
+    // sets, so the loads of the next piece never wait for the current one to be consumed
+    constexpr int VEC = Op<WT>::VEC;
+    constexpr int KH = KC / 2;
+    constexpr int LST = KH + Op<WT>::PAD;           // LDS row stride in elements (144 bytes)
+    constexpr int WI = 4;                           // weight loads per piece: 8 rows x 8 lanes (128 bytes) each
+    constexpr int APR = KH / 4;                     // float4 parts of a state row per piece: 8 or 16
+    constexpr int ARI = 64 / APR;                   // state rows per load instruction: 8 or 4
+    constexpr int AI = 32 / ARI;                    // state loads per piece: 4 or 8
+    WT* Wl = reinterpret_cast<WT*>(smem_raw) + wave * (2 * 32 * LST);
+    WT* Al = Wl + 32 * LST;
+    const int wrl = lane >> 3, wkc = (lane & 7) * VEC;          // weights: row 8 i + wrl
+    const int arl = lane / APR, akc = (lane % APR) * 4;         // state: row ARI i + arl
+    uint4 wr[2][WI];
+    float4 ar[2][AI];
+    DR dr[2][AI];
+    unsigned wmask[2] = {0u, 0u}, amask[2] = {0u, 0u};
+    auto load_piece = [&](uint4 (&w)[WI], float4 (&x)[AI], DR (&d)[AI], unsigned& wm, unsigned& am, int k0) {
+      wm = 0; am = 0;
+#pragma unroll
+      for (int i = 0; i < WI; ++i) {
+        const int row = n0 + 8 * i + wrl, k = k0 + wkc;
+        const bool ok = row < a.Nf && k < K;         // K % 8 == 0: a 16-byte part is in or out as a whole
+        wm |= ok ? (1u << i) : 0u;
+        w[i] = ld_weights<WS>(Wp + (ok ? (unsigned)(row * K + k) : 0u));
+      }
+#pragma unroll
+      for (int i = 0; i < AI; ++i) {
+        const int row = m0 + ARI * i + arl, k = k0 + akc;
+        const bool ok = row < a.M && k < K;
+        const unsigned off = ok ? (unsigned)(row * K + k) : 0u;
+        am |= ok ? (1u << i) : 0u;
+        x[i] = *reinterpret_cast<const float4*>(Xp + off);
+        if (Dp) d[i] = ld_d4(Dp + off);
+      }
+    };
+    // one piece: registers -> this wavefront's LDS area -> MFMA fragments.  The area belongs to this wavefront
+    // alone, whose LDS operations execute in order; the fences only keep the compiler from moving the fragment
+    // reads across the stores.
+    auto consume_piece = [&](const uint4 (&w)[WI], const float4 (&x)[AI], const DR (&d)[AI], unsigned wm, unsigned am) {
+#pragma unroll
+      for (int i = 0; i < WI; ++i) {
+        uint4 v = w[i];
+        if (!((wm >> i) & 1u)) v = make_uint4(0, 0, 0, 0);
+        *reinterpret_cast<uint4*>(&Wl[(8 * i + wrl) * LST + wkc]) = v;
+      }
+#pragma unroll
+      for (int i = 0; i < AI; ++i) {
+        float4 v = x[i];
+        if (Dp) { const float4 dd = d4_to_f4(d[i]); v.x *= dd.x; v.y *= dd.y; v.z *= dd.z; v.w *= dd.w; }
+        if (!((am >> i) & 1u)) v = zero;
+        cvt_store4(&Al[(ARI * i + arl) * LST + akc], v);
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+      for (int j = 0; j < 4; ++j) ks_piece(&Al[c * LST + 2 * KL * j + KL * g], &Wl[c * LST + 2 * KL * j + KL * g], acc);
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
+    // piece h of the contraction starts at k = h * KH; this wavefront takes h = wave, wave + NW, ...
+    const int nh = (K + KH - 1) / KH;
+    int h = wave;
+    if (h < nh) load_piece(wr[0], ar[0], dr[0], wmask[0], amask[0], h * KH);
+    if (h + NW < nh) load_piece(wr[1], ar[1], dr[1], wmask[1], amask[1], (h + NW) * KH);
+    for (; h < nh; h += 2 * NW) {
+      consume_piece(wr[0], ar[0], dr[0], wmask[0], amask[0]);
+      if (h + 2 * NW < nh) load_piece(wr[0], ar[0], dr[0], wmask[0], amask[0], (h + 2 * NW) * KH);
+      if (h + NW < nh) {
+        consume_piece(wr[1], ar[1], dr[1], wmask[1], amask[1]);
+        if (h + 3 * NW < nh) load_piece(wr[1], ar[1], dr[1], wmask[1], amask[1], (h + 3 * NW) * KH);
+      }
+    }
+    __syncthreads();                                 // every wavefront has left its staging area: the partial tiles go there
+  } else
   for (int k0 = wave * KC; k0 < K; k0 += 4 * KC) {
     float4 af[8], ag[8];
     DR df[8], dg[8];
@@ -590,10 +700,10 @@ __global__ __launch_bounds__(NT) void dense_ksplit_kernel(StepArgs a) {
 #pragma unroll
   for (int r = 0; r < 16; ++r) part[wave][8 * (r >> 2) + 4 * g + (r & 3)][c] = acc[r];
   __syncthreads();
-  const int pr = tid >> 3, pc = 4 * (tid & 7);
+  const int pr = (tid & 255) >> 3, pc = 4 * (tid & 7);
   float4 z = *reinterpret_cast<const float4*>(&part[0][pr][pc]);
 #pragma unroll
-  for (int w = 1; w < 4; ++w) {
+  for (int w = 1; w < NW; ++w) {
     const float4 t = *reinterpret_cast<const float4*>(&part[w][pr][pc]);
     z.x += t.x; z.y += t.y; z.z += t.z; z.w += t.w;
   }
@@ -945,9 +1055,12 @@ static size_t conv_smem_bytes(const StepArgs& a, int dtype) {
 //   0: 64x64   1: 128x128 (two workgroups per CU; a 256x256 bf16 tile with one workgroup per CU halves the
 //   L2 traffic but measured 8-19 % slower at every group count, its single wavefront per SIMD cannot keep
 //   enough loads in flight)
-//  -1: 32x32 with the contraction split over the four wavefronts (latency-bound small launches)
+//  -1: 32x32 with the contraction split over the four wavefronts (latency-bound small launches; also every
+//      long contraction with at most 32 rows, through its staged variant)
+static bool ksplit_staged(const StepArgs& a) { return a.M <= 32 && a.K >= 2048; }
 static int dense_tile_class(const StepArgs& a, int dtype, int groups) {
   auto wgs = [&](int t) { return (long long)((a.M + t - 1) / t) * ((a.Nf + t - 1) / t) * groups; };
+  if (ksplit_staged(a)) return -1;
   if (wgs(128) >= 256) return 1;
   if (wgs(64) < 256) return -1;      // fewer 64x64 tiles than CUs (measured: at 256 the tiled kernel already wins)
   return 0;
@@ -981,10 +1094,27 @@ static void launch_dense(dim3 grid, hipStream_t s, const StepArgs& a) {
   if (a.wstream) launch_dense_ws<WT, BM, BN, BK, PF, true>(grid, s, a);
   else           launch_dense_ws<WT, BM, BN, BK, PF, false>(grid, s, a);
 }
+template <typename WT, bool WS, int NW>
+static void launch_ksplit_staged(dim3 grid, hipStream_t s, const StepArgs& a) {
+  constexpr size_t smem = ksplit_staged_smem<WT>(NW);
+  static bool raised = false;              // opt in once to more than 64 KB of dynamic LDS
+  if (smem > 64 * 1024 && !raised) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(dense_ksplit_kernel<WT, WS, true, NW>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    raised = true;
+  }
+  hipLaunchKernelGGL((dense_ksplit_kernel<WT, WS, true, NW>), grid, dim3(NW * 64), smem, s, a);
+}
 template <typename WT>
-static void launch_ksplit(dim3 grid, hipStream_t s, const StepArgs& a) {
-  if (a.wstream) hipLaunchKernelGGL((dense_ksplit_kernel<WT, true>), grid, dim3(NT), 0, s, a);
-  else           hipLaunchKernelGGL((dense_ksplit_kernel<WT, false>), grid, dim3(NT), 0, s, a);
+static void launch_ksplit(dim3 grid, hipStream_t s, const StepArgs& a, bool staged) {
+  if (staged) {
+    const bool wide = grid.x < 256;          // fewer workgroups than CUs: eight wavefronts split the contraction
+    if (a.wstream) { if (wide) launch_ksplit_staged<WT, true, 8>(grid, s, a);  else launch_ksplit_staged<WT, true, 4>(grid, s, a); }
+    else           { if (wide) launch_ksplit_staged<WT, false, 8>(grid, s, a); else launch_ksplit_staged<WT, false, 4>(grid, s, a); }
+  } else {
+    if (a.wstream) hipLaunchKernelGGL((dense_ksplit_kernel<WT, true, false>), grid, dim3(NT), 0, s, a);
+    else           hipLaunchKernelGGL((dense_ksplit_kernel<WT, false, false>), grid, dim3(NT), 0, s, a);
+  }
 }
 
 template <typename WT, int TN, bool N16 = false>
@@ -1022,8 +1152,8 @@ hipError_t launch_step(const StepArgs& a_in, int layer_kind, int dtype, int grou
     const int tc = dense_tile_class(a, dtype, groups);
     if (tc == -1) {
       cls = dtype == 0 ? TRACE_DENSE_F32_KS : TRACE_DENSE_BF16_KS;
-      if (dtype == 0) launch_ksplit<float>(grid, s, a);
-      else            launch_ksplit<__bf16>(grid, s, a);
+      if (dtype == 0) launch_ksplit<float>(grid, s, a, ksplit_staged(a));
+      else            launch_ksplit<__bf16>(grid, s, a, ksplit_staged(a));
     } else if (tc == 1) {
       cls = dtype == 0 ? TRACE_DENSE_F32_128 : TRACE_DENSE_BF16_128;
       if (dtype == 0) launch_dense<float, 128, 128, 32, 2>(grid, s, a);

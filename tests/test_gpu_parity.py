@@ -83,6 +83,10 @@ DENSE_CASES = [
     I.reduced(I.cfg5(1), name="dense_bf16_q264_B260_N128_m2_bigtile", q=264, B=260, N=128, m=2, max_levels=2,
               head_classes=0),
     I.reduced(I.cfg2(1), name="dense_fp32_q136_B130_N128_m2_bigtile", q=136, B=130, N=128, m=2, max_levels=2),
+    # at most 32 rows and a long contraction: the 16-wavefront k-split kernel (ragged rows, bias, both operand types)
+    I.reduced(I.cfg2(1), name="dense_fp32_q2048_B20_N8_m2_deep_ksplit", q=2048, B=20, N=8, m=2, max_levels=2, bias_var=0.1),
+    I.reduced(I.cfg5(1), name="dense_bf16_q4096_B9_N4_m2_deep_ksplit", q=4096, B=9, N=4, m=2, max_levels=2, head_classes=0,
+              bias_var=0.1),
     # level sizes that are no multiples of m: trailing F-points behind the last C-point (79 -> 19 -> 4, 23 -> 11 -> 5)
     I.reduced(I.cfg2(3), name="dense_fp32_q72_B37_N79_m4_L3_trailing", q=72, B=37, N=79, bias_var=0.1),
     I.reduced(I.cfg2(2), name="dense_fp32_q40_B9_N23_m2_L3_F_trailing", q=40, B=9, N=23, m=2, relax=I.RELAX_F, act=I.TANH),
@@ -256,6 +260,9 @@ ADJ_CASES = [
     I.reduced(I.cfg5(2), name="adj_chain_fp32_q256_relu_F_L2", q=256, B=12, N=32, m=4, dtype=I.FP32, act=I.RELU,
               max_levels=2, relax=I.RELAX_F),
     I.reduced(I.cfg5(1), name="adj_fp32_q512_B8_N16_m4", q=512, B=8, N=16, m=4, dtype=I.FP32),
+    # the 16-wavefront k-split kernel with the act' operand and in the act' launch itself
+    I.reduced(I.cfg5(1), name="adj_dense_fp32_q2048_B20_N8_m2_deep_ksplit", q=2048, B=20, N=8, m=2, max_levels=2, dtype=I.FP32),
+    I.reduced(I.cfg5(1), name="adj_dense_bf16_q4096_B32_N4_m2_deep_ksplit", q=4096, B=32, N=4, m=2, max_levels=2),
     # level sizes that are no multiples of m: the adjoint hierarchy counts from layer N, its trailing F-points end at layer 0
     I.reduced(I.cfg5(3), name="adj_dense_fp32_q72_B37_N79_m4_L3_trailing", q=72, B=37, N=79, m=4, max_levels=3, dtype=I.FP32),
     I.reduced(I.cfg5(2), name="adj_dense_bf16_q136_B50_N70_m4_trailing", q=136, B=50, N=70, m=4),
