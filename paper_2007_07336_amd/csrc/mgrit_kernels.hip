@@ -189,7 +189,7 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
   __syncthreads();
   if ((threadIdx.x & 63) == 0) red[w] = v;
   __syncthreads();
-  // fixed order over the wavefronts of the workgroup (4, or 8 in the staged k-split kernel), two at a time
+  // fixed order over the wavefronts of the workgroup (4, or 8 in the k-split kernel), two at a time
   float s = (red[0] + red[1]) + (red[2] + red[3]);
   for (int i = 4; i < (int)(blockDim.x >> 6); i += 2) s += red[i] + red[i + 1];
   return s;
@@ -483,49 +483,23 @@ __global__ __launch_bounds__(NT) void dense_step_kernel(StepArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Dense step for SMALL launches (coarse levels, narrow layers), built for latency instead of
-// reuse: a workgroup owns a 32-row x 32-column output tile and its four wavefronts split the
-// contraction (chunks of KC values of k, round robin).  Operand fragments go straight from
-// global memory into the MFMA source registers -- no LDS staging, no barrier in the k loop --
-// and the operands of the fused epilogue are requested before the k loop starts.  The four
-// partial tiles are summed through LDS in a fixed order.
-// STAGED (long contractions with at most 32 rows, e.g. a fully connected layer on 32 flattened images: such
-// a step only streams its weights): the direct fragment loads touch 32 cache lines per instruction and use
-// 32 bytes of each, which is fine for a few chunks but not for a 4096-long row.  Here a wavefront loads its
-// pieces of both operands with whole-line accesses (8 lanes per 128-byte row piece), passes them through an
-// LDS area of its own (no workgroup barrier in the k loop either) and reads the fragments from there; the
-// loads of its next two pieces are in flight meanwhile.  NW = 8 wavefronts split the contraction when the launch has
-// fewer workgroups than the chip has CUs: the time of such a launch is the number of chunks a wavefront walks
-// through times the memory latency.
+// Dense step for SMALL launches (coarse levels, narrow layers) and for skinny ones (at most 32 rows and a
+// long contraction, e.g. a fully connected layer on 32 flattened images, which only streams its weights),
+// built for latency instead of reuse: a workgroup owns a 32-row x 32-column output tile and its NW wavefronts
+// split the contraction in pieces of KC / 2 values of k (128 bytes of a weight row), round robin.  A wavefront
+// loads its piece of both operands with whole-line accesses (8 lanes per 128-byte row piece), passes it through
+// an LDS area of its own and reads the MFMA fragments from there -- no workgroup barrier in the k loop -- with
+// the loads of its next two pieces in flight in two register sets.  (Fragment loads straight from global
+// memory touch 32 cache lines per instruction and use 32 bytes of each: the address path of the CU, not the
+// memory, then sets the time -- 1.79 against 1.63 ms per step of the q = 256 workload, 7.5 against 5.7 ms for
+// the stack with 4096-wide fully connected layers.)  The operands of the fused epilogue are requested before
+// the k loop starts; the NW partial tiles are summed through LDS in a fixed order.  NW = 4, or 8 when the
+// launch has fewer workgroups than the chip has CUs: the time of such a launch is the number of pieces a
+// wavefront walks through times the memory latency.
 // ------------------------------------------------------------------------------------------
 template <typename WT> struct KsOp;
-template <> struct KsOp<float>  { static constexpr int KC = 64;  };   // 8 x (4 k per lane group) x 2 groups
-template <> struct KsOp<__bf16> { static constexpr int KC = 128; };   // 8 x (8 k per lane group) x 2 groups
-
-__device__ __forceinline__ void ks_mma(const float4 (&af)[8], const float4 (&)[8], const uint4 (&wf)[8], floatx16& acc,
-                                       float) {
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const float4 b = *reinterpret_cast<const float4*>(&wf[j]);
-    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(af[j].x, b.x, acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(af[j].y, b.y, acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(af[j].z, b.z, acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(af[j].w, b.w, acc, 0, 0, 0);
-  }
-}
-__device__ __forceinline__ void ks_mma(const float4 (&af)[8], const float4 (&ag)[8], const uint4 (&wf)[8], floatx16& acc,
-                                       __bf16) {
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    bf16x8 av;
-    av[0] = static_cast<__bf16>(af[j].x); av[1] = static_cast<__bf16>(af[j].y);
-    av[2] = static_cast<__bf16>(af[j].z); av[3] = static_cast<__bf16>(af[j].w);
-    av[4] = static_cast<__bf16>(ag[j].x); av[5] = static_cast<__bf16>(ag[j].y);
-    av[6] = static_cast<__bf16>(ag[j].z); av[7] = static_cast<__bf16>(ag[j].w);
-    const bf16x8 b = *reinterpret_cast<const bf16x8*>(&wf[j]);
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, b, acc, 0, 0, 0);
-  }
-}
+template <> struct KsOp<float>  { static constexpr int KC = 64;  };   // a piece is KC / 2 values of k: 4 fragments x (4 k per lane group) x 2 groups
+template <> struct KsOp<__bf16> { static constexpr int KC = 128; };   // 4 fragments x (8 k per lane group) x 2 groups
 
 __device__ __forceinline__ void ks_piece(const float* ap, const float* bp, floatx16& acc) {
   const float4 av = *reinterpret_cast<const float4*>(ap), bv = *reinterpret_cast<const float4*>(bp);
@@ -538,21 +512,20 @@ __device__ __forceinline__ void ks_piece(const __bf16* ap, const __bf16* bp, flo
   acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(ap), *reinterpret_cast<const bf16x8*>(bp),
                                                 acc, 0, 0, 0);
 }
-// LDS of the staged variant: per wavefront one [32][KC / 2 + PAD] area for each operand (144-byte rows)
-template <typename WT> constexpr size_t ksplit_staged_smem(int nw) {
+// its LDS: per wavefront one [32][KC / 2 + PAD] area for each operand (144-byte rows)
+template <typename WT> constexpr size_t ksplit_smem(int nw) {
   return (size_t)nw * 2 * 32 * (KsOp<WT>::KC / 2 + Op<WT>::PAD) * sizeof(WT);
 }
 
-template <typename WT, bool WS, bool STAGED, int NW = 4>
+template <typename WT, bool WS, int NW>
 __global__ __launch_bounds__(NW * 64) void dense_ksplit_kernel(StepArgs a) {
-  static_assert(NW == 4 || (STAGED && NW == 8), "eight wavefronts only in the staged variant");
+  static_assert(NW == 4 || NW == 8, "four or eight wavefronts");
   constexpr int KC = KsOp<WT>::KC;
   constexpr bool BF = sizeof(WT) == 2;
   constexpr int KL = BF ? 8 : 4;                    // consecutive k a lane feeds per piece
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];   // STAGED: the wavefronts' staging areas
-  __shared__ __attribute__((aligned(16))) float part_static[STAGED ? 1 : 4][32][36];
-  static_assert(!STAGED || ksplit_staged_smem<WT>(NW) >= sizeof(float) * NW * 32 * 36, "the partial tiles reuse the staging areas");
-  float (*part)[32][36] = STAGED ? reinterpret_cast<float (*)[32][36]>(smem_raw) : part_static;   // [NW][32][36]
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];   // the wavefronts' staging areas
+  static_assert(ksplit_smem<WT>(NW) >= sizeof(float) * NW * 32 * 36, "the partial tiles reuse the staging areas");
+  float (*part)[32][36] = reinterpret_cast<float (*)[32][36]>(smem_raw);     // [NW][32][36], after the k loop
   __shared__ float red[NW];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, c = lane & 31;
   const int tiles_n = (a.Nf + 31) / 32;
@@ -580,13 +553,10 @@ __global__ __launch_bounds__(NW * 64) void dense_ksplit_kernel(StepArgs a) {
   if (e.E2p) e2 = *reinterpret_cast<const float4*>(e.E2p + eoff);
   if (e.bp && ecol < a.Nf) bv = *reinterpret_cast<const float4*>(e.bp + ecol);
 
-  // ---- k loop: this wavefront takes chunks wave, wave+4, ...; lane (c, g) feeds row m0+c of the
-  // state and row n0+c of the weights, pieces of KL consecutive k at k0 + 2*KL*j + KL*g
+  // ---- k loop.  MFMA lane (c, g) feeds row m0+c of the state and row n0+c of the weights, KL consecutive k
+  // at offset 2*KL*j + KL*g of the piece in fragment j
   floatx16 acc = zero16();
-  const bool arow_ok = m0 + c < a.M, wrow_ok = n0 + c < a.Nf;
-  const unsigned abase = arow_ok ? (unsigned)((m0 + c) * K) : 0u;
-  const unsigned wbase = wrow_ok ? (unsigned)((n0 + c) * K) : 0u;
-  if constexpr (STAGED) {
+  {
     // pieces of KH = KC / 2 values of k (128 bytes of a weight row): two of them are in flight in two register
     // sets, so the loads of the next piece never wait for the current one to be consumed
     constexpr int VEC = Op<WT>::VEC;
@@ -663,40 +633,9 @@ __global__ __launch_bounds__(NW * 64) void dense_ksplit_kernel(StepArgs a) {
       }
     }
     __syncthreads();                                 // every wavefront has left its staging area: the partial tiles go there
-  } else
-  for (int k0 = wave * KC; k0 < K; k0 += 4 * KC) {
-    float4 af[8], ag[8];
-    DR df[8], dg[8];
-    uint4 wf[8];
-    unsigned kmask = 0;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int k = k0 + 2 * KL * j + KL * g;
-      const bool kok = k < K;                        // K % 8 == 0: a piece is in or out as a whole
-      kmask |= kok ? (1u << j) : 0u;
-      const unsigned ao = kok ? abase + k : 0u, wo = kok ? wbase + k : 0u;
-      af[j] = *reinterpret_cast<const float4*>(Xp + ao);
-      if (BF) ag[j] = *reinterpret_cast<const float4*>(Xp + ao + 4);
-      if (Dp) {
-        df[j] = ld_d4(Dp + ao);
-        if (BF) dg[j] = ld_d4(Dp + ao + 4);
-      }
-      wf[j] = ld_weights<WS>(Wp + wo);
-    }
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      if (Dp) {
-        const float4 d0 = d4_to_f4(df[j]);
-        af[j].x *= d0.x; af[j].y *= d0.y; af[j].z *= d0.z; af[j].w *= d0.w;
-        if (BF) { const float4 d1 = d4_to_f4(dg[j]); ag[j].x *= d1.x; ag[j].y *= d1.y; ag[j].z *= d1.z; ag[j].w *= d1.w; }
-      }
-      if (!((kmask >> j) & 1u) || !arow_ok) { af[j] = zero; ag[j] = zero; }
-      if (!((kmask >> j) & 1u) || !wrow_ok) wf[j] = make_uint4(0, 0, 0, 0);
-    }
-    ks_mma(af, ag, wf, acc, WT());
   }
 
-  // ---- sum the four partial tiles (fixed order) and apply the fused epilogue
+  // ---- sum the NW partial tiles (fixed order) and apply the fused epilogue
 #pragma unroll
   for (int r = 0; r < 16; ++r) part[wave][8 * (r >> 2) + 4 * g + (r & 3)][c] = acc[r];
   __syncthreads();
@@ -1055,12 +994,12 @@ static size_t conv_smem_bytes(const StepArgs& a, int dtype) {
 //   0: 64x64   1: 128x128 (two workgroups per CU; a 256x256 bf16 tile with one workgroup per CU halves the
 //   L2 traffic but measured 8-19 % slower at every group count, its single wavefront per SIMD cannot keep
 //   enough loads in flight)
-//  -1: 32x32 with the contraction split over the four wavefronts (latency-bound small launches; also every
-//      long contraction with at most 32 rows, through its staged variant)
-static bool ksplit_staged(const StepArgs& a) { return a.M <= 32 && a.K >= 2048; }
+//  -1: 32x32 with the contraction split over the wavefronts (latency-bound small launches; also every long
+//      contraction with at most 32 rows, which only streams its weights: a 64-row tile would be half empty)
+static bool dense_skinny(const StepArgs& a) { return a.M <= 32 && a.K >= 2048; }
 static int dense_tile_class(const StepArgs& a, int dtype, int groups) {
   auto wgs = [&](int t) { return (long long)((a.M + t - 1) / t) * ((a.Nf + t - 1) / t) * groups; };
-  if (ksplit_staged(a)) return -1;
+  if (dense_skinny(a)) return -1;
   if (wgs(128) >= 256) return 1;
   if (wgs(64) < 256) return -1;      // fewer 64x64 tiles than CUs (measured: at 256 the tiled kernel already wins)
   return 0;
@@ -1095,26 +1034,21 @@ static void launch_dense(dim3 grid, hipStream_t s, const StepArgs& a) {
   else           launch_dense_ws<WT, BM, BN, BK, PF, false>(grid, s, a);
 }
 template <typename WT, bool WS, int NW>
-static void launch_ksplit_staged(dim3 grid, hipStream_t s, const StepArgs& a) {
-  constexpr size_t smem = ksplit_staged_smem<WT>(NW);
+static void launch_ksplit_nw(dim3 grid, hipStream_t s, const StepArgs& a) {
+  constexpr size_t smem = ksplit_smem<WT>(NW);
   static bool raised = false;              // opt in once to more than 64 KB of dynamic LDS
   if (smem > 64 * 1024 && !raised) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(dense_ksplit_kernel<WT, WS, true, NW>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(dense_ksplit_kernel<WT, WS, NW>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     raised = true;
   }
-  hipLaunchKernelGGL((dense_ksplit_kernel<WT, WS, true, NW>), grid, dim3(NW * 64), smem, s, a);
+  hipLaunchKernelGGL((dense_ksplit_kernel<WT, WS, NW>), grid, dim3(NW * 64), smem, s, a);
 }
 template <typename WT>
-static void launch_ksplit(dim3 grid, hipStream_t s, const StepArgs& a, bool staged) {
-  if (staged) {
-    const bool wide = grid.x < 256;          // fewer workgroups than CUs: eight wavefronts split the contraction
-    if (a.wstream) { if (wide) launch_ksplit_staged<WT, true, 8>(grid, s, a);  else launch_ksplit_staged<WT, true, 4>(grid, s, a); }
-    else           { if (wide) launch_ksplit_staged<WT, false, 8>(grid, s, a); else launch_ksplit_staged<WT, false, 4>(grid, s, a); }
-  } else {
-    if (a.wstream) hipLaunchKernelGGL((dense_ksplit_kernel<WT, true, false>), grid, dim3(NT), 0, s, a);
-    else           hipLaunchKernelGGL((dense_ksplit_kernel<WT, false, false>), grid, dim3(NT), 0, s, a);
-  }
+static void launch_ksplit(dim3 grid, hipStream_t s, const StepArgs& a) {
+  const bool wide = grid.x < 256;            // fewer workgroups than CUs: eight wavefronts split the contraction
+  if (a.wstream) { if (wide) launch_ksplit_nw<WT, true, 8>(grid, s, a);  else launch_ksplit_nw<WT, true, 4>(grid, s, a); }
+  else           { if (wide) launch_ksplit_nw<WT, false, 8>(grid, s, a); else launch_ksplit_nw<WT, false, 4>(grid, s, a); }
 }
 
 template <typename WT, int TN, bool N16 = false>
@@ -1152,8 +1086,8 @@ hipError_t launch_step(const StepArgs& a_in, int layer_kind, int dtype, int grou
     const int tc = dense_tile_class(a, dtype, groups);
     if (tc == -1) {
       cls = dtype == 0 ? TRACE_DENSE_F32_KS : TRACE_DENSE_BF16_KS;
-      if (dtype == 0) launch_ksplit<float>(grid, s, a, ksplit_staged(a));
-      else            launch_ksplit<__bf16>(grid, s, a, ksplit_staged(a));
+      if (dtype == 0) launch_ksplit<float>(grid, s, a);
+      else            launch_ksplit<__bf16>(grid, s, a);
     } else if (tc == 1) {
       cls = dtype == 0 ? TRACE_DENSE_F32_128 : TRACE_DENSE_BF16_128;
       if (dtype == 0) launch_dense<float, 128, 128, 32, 2>(grid, s, a);
