@@ -25,9 +25,9 @@ PEAK = {"fp32_mfma": 157.3, "bf16_mfma": 2500.0,       # TFLOP/s, published dens
 # mean over the dispatches of the same bench command; summaries and the calibration of the two factors
 # are in profiles/<workload>_bench_hbm_traffic.md).  None where no counter run was made.
 TRAFFIC_BYTES = {
-    ("cfg2", "dense_ksplit_kernel<float>"): 5.17e6 + 0.97e6,
-    ("cfg2", "dense_sweep_kernel<float>"): 71.87e6 + 25.17e6,
-    ("cfg2", "dense_step_kernel<float,64,64>"): 37.31e6 + 8.39e6,
+    ("cfg2", "dense_ksplit_kernel<float>"): 5.20e6 + 0.97e6,     # mean over its 4- and 8-wavefront launches
+    ("cfg2", "dense_sweep_kernel<float>"): 71.83e6 + 25.17e6,
+    ("cfg2", "dense_step_kernel<float,64,64>"): 36.36e6 + 8.39e6,
     ("cfg4", "conv_step_kernel<bf16>"): 390.67e6 + 250.63e6,
     ("cfg5", "dense_step_kernel<bf16,128,128>"): 307.27e6 + 69.58e6,
 }
