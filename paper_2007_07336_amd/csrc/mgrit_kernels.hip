@@ -1777,9 +1777,9 @@ static hipError_t launch_conv_grad(const GradArgs& a, unsigned blocks, size_t sm
 // Fused F-relaxation sweep for dense layers.  A workgroup owns 32 batch rows of one coarse interval
 // and marches through all steps of the sweep: the fp32 state slice S and its matrix-core operand
 // copy A (Dm .* S in the operand type) stay in LDS, the weights of each layer stream through two LDS
-// slabs of BK values of k (coalesced 16-byte loads into a register ring of PF slabs, running ahead
-// across layer boundaries; while one slab is multiplied the next is written to the other buffer, one
-// barrier per slab).  The raw sums of a step go through the slab buffer that has just become free, so that
+// slabs of BK values of k (whole-line loads into a register ring of PF slabs, running ahead
+// across layer boundaries; while one slab is multiplied the next is written to the other buffer).  Every
+// wavefront loads, stages and multiplies its own weight rows only, so the slab loop has no workgroup barrier.  The raw sums of a step go through the slab buffer that has just become free, so that
 // the update -- new state to LDS and to global memory, next operand -- is one float4 pass over whole rows.  Wavefront w owns the column blocks w*NBW .. w*NBW + NBW - 1 of 32 columns;
 // q = 128 * NBW.
 // ------------------------------------------------------------------------------------------
@@ -1793,10 +1793,11 @@ __global__ __launch_bounds__(NT) void dense_sweep_kernel(SweepArgs a) {
   constexpr int R = SWEEP_R, BK = SweepOp<WT>::BK, VEC = Op<WT>::VEC, KSTEP = Op<WT>::KSTEP, PAD = Op<WT>::PAD;
   constexpr int Q = 128 * NBW, Q4 = Q / 4;
   constexpr int AST = Q + PAD, ST = BK + PAD;
-  constexpr int PPR = BK / VEC;                 // 16-byte pieces per weight row and slab
-  constexpr int BP = Q * PPR / NT;              // pieces per thread and slab
+  constexpr int PPR = BK / VEC;                 // 16-byte pieces per weight row and slab (one 128-byte line)
+  constexpr int WROWS = 32 * NBW;               // weight rows (output columns) of a wavefront
+  constexpr int BP = WROWS * PPR / 64;          // pieces per lane and slab
   constexpr int NSL = Q / BK;                   // slabs per layer
-  static_assert(Q * PPR % NT == 0 && R * Q4 % NT == 0, "slab and slice must divide over 256 threads");
+  static_assert(WROWS * PPR % 64 == 0 && R * Q4 % NT == 0, "slab and slice must divide over the lanes");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   float* S = reinterpret_cast<float*>(smem_raw);           // [R][Q] state slice
   WT* A = reinterpret_cast<WT*>(S + R * Q);                // [R][AST] operand of the current step
@@ -1821,16 +1822,24 @@ __global__ __launch_bounds__(NT) void dense_sweep_kernel(SweepArgs a) {
     const WT* Wp = Wall + layer_of(it / NSL + 1) * a.wsize + (it % NSL) * BK;
 #pragma unroll
     for (int i = 0; i < BP; ++i) {
-      const int p = tid + NT * i, row = p / PPR, kc = (p % PPR) * VEC;
+      const int p = lane + 64 * i, row = wave * WROWS + p / PPR, kc = (p % PPR) * VEC;
       br[i] = ld_weights<false>(Wp + row * Q + kc);
     }
   };
   auto store_slab = [&](const uint4 (&br)[BP], WT* dst) {
 #pragma unroll
     for (int i = 0; i < BP; ++i) {
-      const int p = tid + NT * i, row = p / PPR, kc = (p % PPR) * VEC;
+      const int p = lane + 64 * i, row = wave * WROWS + p / PPR, kc = (p % PPR) * VEC;
       *reinterpret_cast<uint4*>(&dst[row * ST + kc]) = br[i];
     }
+  };
+  // A wavefront loads, stages and multiplies only its own weight rows, so the slab pipeline needs no workgroup
+  // barrier: its LDS operations execute in order, and the fences only keep the compiler from moving the
+  // fragment reads across the stores.
+  auto wave_sync = [&]() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   };
 #pragma unroll
   for (int sidx = 0; sidx < PF; ++sidx)
@@ -1876,6 +1885,7 @@ __global__ __launch_bounds__(NT) void dense_sweep_kernel(SweepArgs a) {
   static_assert(NSL % PF == 0 && PF % 2 == 0, "ring slot and LDS buffer of a slab must be compile-time values");
   store_slab(breg[0], Bs);
   if (PF < total) load_slab(breg[0], PF);
+  __syncthreads();                                         // the first operand is complete
 
   for (int k = 1; k <= a.nsteps; ++k) {
 #ifdef MGRIT_TIMING
@@ -1893,7 +1903,7 @@ __global__ __launch_bounds__(NT) void dense_sweep_kernel(SweepArgs a) {
 #pragma unroll
       for (int sidx = 0; sidx < PF; ++sidx) {
         const int sl = sl0 + sidx, it = (k - 1) * NSL + sl;
-        __syncthreads();                                   // slab it (and A) visible; slab it-1 consumed
+        wave_sync();                                       // slab it of this wavefront is in LDS; slab it-1 consumed
         if (it + 1 < total) {                              // next slab (maybe the next layer's first) -> other buffer
           store_slab(breg[(sidx + 1) % PF], Bs + ((sidx + 1) & 1) * (Q * ST));
           if (it + 1 + PF < total) load_slab(breg[(sidx + 1) % PF], it + 1 + PF);
@@ -1957,6 +1967,7 @@ __global__ __launch_bounds__(NT) void dense_sweep_kernel(SweepArgs a) {
         }
       }
     }
+    __syncthreads();                                       // next operand complete; the sums' buffer is free again
 #ifdef MGRIT_TIMING
     // diagnostic build only: phase times in cycles overwrite the first values of the last state slice
     const long long t_k3 = __builtin_readcyclecounter();
