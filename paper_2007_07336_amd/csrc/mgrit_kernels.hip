@@ -962,6 +962,21 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
   }
 }
 
+// A kernel that uses more than 64 KB of dynamic LDS has to opt in, once per device (the attribute belongs to
+// the device's copy of the kernel).  One of these per kernel instance remembers the largest size each device
+// has been raised to.
+struct LdsOptIn {
+  size_t seen[64] = {};
+  bool need(size_t smem) {
+    if (smem <= 64 * 1024) return false;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return true;
+    if (smem <= seen[dev]) return false;
+    seen[dev] = smem;
+    return true;
+  }
+};
+
 // ------------------------------------------------------------------------------------------
 // launch configuration
 // ------------------------------------------------------------------------------------------
@@ -1020,12 +1035,10 @@ static void launch_dense_ws(dim3 grid, hipStream_t s, const StepArgs& a) {
   constexpr size_t tiles_b = (size_t)(BM + BN) * (BK + Op<WT>::PAD) * sizeof(WT);
   constexpr size_t stage_b = (size_t)4 * 32 * (BN / 2 + 4) * sizeof(float);   // epilogue staging, 2 wavefront columns
   constexpr size_t smem = tiles_b > stage_b ? tiles_b : stage_b;
-  static bool raised = false;              // opt in once to more than 64 KB of dynamic LDS
-  if (smem > 64 * 1024 && !raised) {
+  static LdsOptIn opt;
+  if (opt.need(smem))
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(dense_step_kernel<WT, BM, BN, 2, 2, BK, PF, WS>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    raised = true;
-  }
   hipLaunchKernelGGL((dense_step_kernel<WT, BM, BN, 2, 2, BK, PF, WS>), grid, dim3(NT), smem, s, a);
 }
 template <typename WT, int BM, int BN, int BK, int PF>
@@ -1036,12 +1049,10 @@ static void launch_dense(dim3 grid, hipStream_t s, const StepArgs& a) {
 template <typename WT, bool WS, int NW>
 static void launch_ksplit_nw(dim3 grid, hipStream_t s, const StepArgs& a) {
   constexpr size_t smem = ksplit_smem<WT>(NW);
-  static bool raised = false;              // opt in once to more than 64 KB of dynamic LDS
-  if (smem > 64 * 1024 && !raised) {
+  static LdsOptIn opt;
+  if (opt.need(smem))
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(dense_ksplit_kernel<WT, WS, NW>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    raised = true;
-  }
   hipLaunchKernelGGL((dense_ksplit_kernel<WT, WS, NW>), grid, dim3(NW * 64), smem, s, a);
 }
 template <typename WT>
@@ -1053,12 +1064,10 @@ static void launch_ksplit(dim3 grid, hipStream_t s, const StepArgs& a) {
 
 template <typename WT, int TN, bool N16 = false>
 static void launch_conv(dim3 grid, size_t smem, hipStream_t s, const StepArgs& a) {
-  static size_t raised = 64 * 1024;        // opt in to more than 64 KB of dynamic LDS when a shape needs it
-  if (smem > raised) {
+  static LdsOptIn opt;
+  if (opt.need(smem))
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(conv_step_kernel<WT, TN, N16>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    raised = smem;
-  }
   hipLaunchKernelGGL((conv_step_kernel<WT, TN, N16>), grid, dim3(NT), smem, s, a);
 }
 
@@ -1997,12 +2006,11 @@ static hipError_t launch_sweep_t(const SweepArgs& a, unsigned blocks, size_t sme
   // take 256 registers of a lane)
   constexpr int NSLABS = 128 * NBW / SweepOp<WT>::BK;
   constexpr int PF = NSLABS < 4 ? NSLABS : 4;
-  static bool raised = false;                // opt in once to more than 64 KB of dynamic LDS
-  if (smem > 64 * 1024 && !raised) {
+  static LdsOptIn opt;
+  if (opt.need(smem)) {
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(dense_sweep_kernel<WT, NBW, PF>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
-    raised = true;
   }
   hipLaunchKernelGGL((dense_sweep_kernel<WT, NBW, PF>), dim3(blocks), dim3(NT), smem, s, a);
   return hipGetLastError();
