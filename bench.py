@@ -24,8 +24,11 @@ PEAK = {"fp32_mfma": 157.3, "bf16_mfma": 2500.0,       # TFLOP/s, published dens
 # Measured HBM bytes per launch of the dominant kernel (rocprofv3 --pmc FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0,
 # mean over the dispatches of the same bench command; summaries and the calibration of the two factors
 # are in profiles/<workload>_bench_hbm_traffic.md).  None where no counter run was made.
+EVENT_PAIR_US = 2.6
+
 TRAFFIC_BYTES = {
-    ("cfg2", "dense_ksplit_kernel<float>"): 5.20e6 + 0.97e6,     # mean over its 4- and 8-wavefront launches
+    ("cfg2", "dense_ksplit_kernel<float,4>"): 9.84e6 + 2.10e6,
+    ("cfg2", "dense_ksplit_kernel<float,8>"): 1.72e6 + 0.13e6,
     ("cfg2", "dense_sweep_kernel<float>"): 71.83e6 + 25.17e6,
     ("cfg2", "dense_step_kernel<float,64,64>"): 36.36e6 + 8.39e6,
     ("cfg4", "conv_step_kernel<bf16>"): 390.67e6 + 250.63e6,
@@ -175,7 +178,11 @@ def main():
     tr = M.mgrit_trace_end()
     torch.cuda.synchronize()
     step_classes = {k: v for k, v in tr.items() if k != "dense_grad_kernel"}
-    dom = max(step_classes, key=lambda k: step_classes[k][0])
+    # The dominant kernel is the one with the most kernel time.  The trace brackets every launch with a HIP event
+    # pair, which adds EVENT_PAIR_US to the interval of a short launch (bracketed minus rocprofv3 duration of the
+    # 5 and 7 us launches of workload 2: 2.6 and 2.8 us), so a class of many short launches would look larger
+    # than it is; the ranking takes that off, the figures reported below are the raw bracketed ones.
+    dom = max(step_classes, key=lambda k: step_classes[k][0] - step_classes[k][1] * EVENT_PAIR_US * 1e-3)
     ms_tot, launches, units, alg_bytes = step_classes[dom]
     if wl.layer == I.DENSE:
         flops_per_unit = 2.0 * wl.B * wl.q * wl.q
@@ -209,7 +216,8 @@ def main():
                 "hbm_GBps_bare_step": round(gbps_bare, 1),
                 "mfma_TFLOPs": round(tflops, 3), "mfma_frac": round(tflops / peak_mfma, 5),
                 "hbm_GBps_algorithmic": round(gbps, 1), "hbm_frac": round(gbps / PEAK["hbm_GBps"], 5),
-                "all_kernels_ms": {k: round(v[0] / args.steps, 4) for k, v in tr.items()}}
+                "all_kernels_ms": {k: round(v[0] / args.steps, 4) for k, v in tr.items()},
+                "all_kernels_launches": {k: v[1] // args.steps for k, v in tr.items()}}
 
     out = {"metric": "layer-steps/sec per FAS cycle + time-to-1e-6 residual vs serial, 1\u00d7MI355X",
            "value": round(value, 1), "unit": "layer-steps/s", "n_gpus": 1, "steps": args.steps,

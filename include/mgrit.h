@@ -201,8 +201,8 @@ int32_t mgrit_residual_norm_mixed(const mgrit_problem_t* p, const mgrit_fc_layer
 enum {
   MGRIT_TRACE_DENSE_F32_T64 = 0, MGRIT_TRACE_DENSE_F32_T128, MGRIT_TRACE_DENSE_BF16_T64,
   MGRIT_TRACE_DENSE_BF16_T128, MGRIT_TRACE_CONV_F32, MGRIT_TRACE_CONV_BF16, MGRIT_TRACE_GRAD,
-  MGRIT_TRACE_SWEEP_F32, MGRIT_TRACE_SWEEP_BF16, MGRIT_TRACE_DENSE_BF16_T256,
-  MGRIT_TRACE_DENSE_F32_KSPLIT, MGRIT_TRACE_DENSE_BF16_KSPLIT, MGRIT_TRACE_NCLASS
+  MGRIT_TRACE_SWEEP_F32, MGRIT_TRACE_SWEEP_BF16, MGRIT_TRACE_DENSE_F32_KSPLIT8,
+  MGRIT_TRACE_DENSE_F32_KSPLIT, MGRIT_TRACE_DENSE_BF16_KSPLIT, MGRIT_TRACE_DENSE_BF16_KSPLIT8, MGRIT_TRACE_NCLASS
 };
 void    mgrit_trace_begin(void);
 int32_t mgrit_trace_end(double* ms, int64_t* launches, int64_t* units, double* bytes, int32_t n_classes);

@@ -231,8 +231,8 @@ def mgrit_residual_norm_mixed(p: mgrit_problem_t, fc: mgrit_fc_layers_t, W, b, u
 TRACE_CLASSES = ("dense_step_kernel<float,64,64>", "dense_step_kernel<float,128,128>",
                  "dense_step_kernel<bf16,64,64>", "dense_step_kernel<bf16,128,128>",
                  "conv_step_kernel<float>", "conv_step_kernel<bf16>", "dense_grad_kernel",
-                 "dense_sweep_kernel<float>", "dense_sweep_kernel<bf16>", "dense_step_kernel<bf16,256,256>",
-                 "dense_ksplit_kernel<float>", "dense_ksplit_kernel<bf16>")
+                 "dense_sweep_kernel<float>", "dense_sweep_kernel<bf16>", "dense_ksplit_kernel<float,8>",
+                 "dense_ksplit_kernel<float,4>", "dense_ksplit_kernel<bf16,4>", "dense_ksplit_kernel<bf16,8>")
 
 
 def mgrit_trace_begin() -> None:

@@ -133,8 +133,8 @@ hipError_t launch_sweep(const SweepArgs& a, int dtype, hipStream_t s);
 
 // launch tracing (diagnostic): kernel classes, and begin / collect
 enum { TRACE_DENSE_F32_64 = 0, TRACE_DENSE_F32_128, TRACE_DENSE_BF16_64, TRACE_DENSE_BF16_128,
-       TRACE_CONV_F32, TRACE_CONV_BF16, TRACE_GRAD, TRACE_SWEEP_F32, TRACE_SWEEP_BF16, TRACE_DENSE_BF16_256,
-       TRACE_DENSE_F32_KS, TRACE_DENSE_BF16_KS, TRACE_NCLASS };
+       TRACE_CONV_F32, TRACE_CONV_BF16, TRACE_GRAD, TRACE_SWEEP_F32, TRACE_SWEEP_BF16, TRACE_DENSE_F32_KS8,
+       TRACE_DENSE_F32_KS, TRACE_DENSE_BF16_KS, TRACE_DENSE_BF16_KS8, TRACE_NCLASS };
 void trace_begin();
 int  trace_end(double* ms, long long* launches, long long* units, double* bytes, int ncls);
 void trace_before(hipStream_t s);

@@ -1094,7 +1094,9 @@ hipError_t launch_step(const StepArgs& a_in, int layer_kind, int dtype, int grou
   } else {
     const int tc = dense_tile_class(a, dtype, groups);
     if (tc == -1) {
-      cls = dtype == 0 ? TRACE_DENSE_F32_KS : TRACE_DENSE_BF16_KS;
+      // the 4- and the 8-wavefront form are different kernels to a profiler: separate classes
+      if (grid.x < 256) cls = dtype == 0 ? TRACE_DENSE_F32_KS8 : TRACE_DENSE_BF16_KS8;
+      else              cls = dtype == 0 ? TRACE_DENSE_F32_KS : TRACE_DENSE_BF16_KS;
       if (dtype == 0) launch_ksplit<float>(grid, s, a);
       else            launch_ksplit<__bf16>(grid, s, a);
     } else if (tc == 1) {
