@@ -29,8 +29,8 @@ EVENT_PAIR_US = 2.6
 TRAFFIC_BYTES = {
     ("cfg2", "dense_ksplit_kernel<float,4>"): 9.84e6 + 2.10e6,
     ("cfg2", "dense_ksplit_kernel<float,8>"): 1.72e6 + 0.13e6,
-    ("cfg2", "dense_sweep_kernel<float>"): 71.83e6 + 25.17e6,
-    ("cfg2", "dense_step_kernel<float,64,64>"): 36.36e6 + 8.39e6,
+    ("cfg2", "dense_sweep_kernel<float>"): 71.72e6 + 25.17e6,
+    ("cfg2", "dense_step_kernel<float,64,64>"): 37.44e6 + 8.39e6,
     ("cfg4", "conv_step_kernel<bf16>"): 390.67e6 + 250.63e6,
     ("cfg5", "dense_step_kernel<bf16,128,128>"): 307.27e6 + 69.58e6,
 }
