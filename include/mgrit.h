@@ -17,7 +17,8 @@
  * writes a host output (resnorm_hist, iters_done, norm_out) synchronises that stream before
  * it returns; otherwise it returns with its work in flight on the stream.  Such a call (tol <= 0,
  * no host outputs) consists of kernel launches only, so it may be recorded into a HIP graph by
- * stream capture and replayed.
+ * stream capture and replayed.  Run the same call once outside the capture first: the first launch of
+ * a kernel that uses more than 64 KB of LDS sets an attribute of that kernel on the current device.
  *
  * Environment.  MGRIT_NO_SWEEP=1 makes the library use one launch per layer step also where it would
  * fuse the steps of an F-relaxation sweep into one launch (dense layers of width 128 or 256 with many
