@@ -21,8 +21,9 @@
  * a kernel that uses more than 64 KB of LDS sets an attribute of that kernel on the current device.
  *
  * Environment.  MGRIT_NO_SWEEP=1 makes the library use one launch per layer step also where it would
- * fuse the steps of an F-relaxation sweep into one launch (dense layers of width 128 or 256 with many
- * coarse intervals); results agree with the fused path to rounding.  Read at every call; diagnostic.
+ * fuse the steps of an F-relaxation sweep into one launch (dense layers of width 128 or 256, or float
+ * convolution layers of at most 16 channels on images of at most 832 pixels, with many coarse intervals);
+ * results agree with the fused path to rounding.  Read at every call; diagnostic.
  *
  * Layouts (all row-major, last index fastest):
  *   dense: state [B][q] float;  W [N][q_out][q_in];  b [N][q] float
@@ -203,7 +204,8 @@ enum {
   MGRIT_TRACE_DENSE_F32_T64 = 0, MGRIT_TRACE_DENSE_F32_T128, MGRIT_TRACE_DENSE_BF16_T64,
   MGRIT_TRACE_DENSE_BF16_T128, MGRIT_TRACE_CONV_F32, MGRIT_TRACE_CONV_BF16, MGRIT_TRACE_GRAD,
   MGRIT_TRACE_SWEEP_F32, MGRIT_TRACE_SWEEP_BF16, MGRIT_TRACE_DENSE_F32_KSPLIT8,
-  MGRIT_TRACE_DENSE_F32_KSPLIT, MGRIT_TRACE_DENSE_BF16_KSPLIT, MGRIT_TRACE_DENSE_BF16_KSPLIT8, MGRIT_TRACE_NCLASS
+  MGRIT_TRACE_DENSE_F32_KSPLIT, MGRIT_TRACE_DENSE_BF16_KSPLIT, MGRIT_TRACE_DENSE_BF16_KSPLIT8,
+  MGRIT_TRACE_CONV_SWEEP_F32, MGRIT_TRACE_NCLASS
 };
 void    mgrit_trace_begin(void);
 int32_t mgrit_trace_end(double* ms, int64_t* launches, int64_t* units, double* bytes, int32_t n_classes);

@@ -232,7 +232,8 @@ TRACE_CLASSES = ("dense_step_kernel<float,64,64>", "dense_step_kernel<float,128,
                  "dense_step_kernel<bf16,64,64>", "dense_step_kernel<bf16,128,128>",
                  "conv_step_kernel<float>", "conv_step_kernel<bf16>", "dense_grad_kernel",
                  "dense_sweep_kernel<float>", "dense_sweep_kernel<bf16>", "dense_ksplit_kernel<float,8>",
-                 "dense_ksplit_kernel<float,4>", "dense_ksplit_kernel<bf16,4>", "dense_ksplit_kernel<bf16,8>")
+                 "dense_ksplit_kernel<float,4>", "dense_ksplit_kernel<bf16,4>", "dense_ksplit_kernel<bf16,8>",
+                 "conv_sweep_kernel")
 
 
 def mgrit_trace_begin() -> None:

@@ -250,11 +250,14 @@ struct Solver {
     if (g[l] && !plain_rhs) { a.E1 = g[l]; a.e1m = PtMap{js0, jstride}; a.c1 = 1.0f; }
     launch(a, groups);
   }
-  // One fused launch per F-relaxation sweep where it pays: dense layers of a supported width, at least two
-  // steps per interval, and enough (interval, 32-row slice) workgroups to occupy the chip -- with fewer, the
+  // One fused launch per F-relaxation sweep where it pays: dense layers of a supported width or convolution
+  // layers of at most 16 float channels on images that fit one workgroup, at least two steps per interval, and
+  // enough workgroups -- (interval, 32-row slice) or (interval, image) -- to occupy the chip; with fewer, the
   // lockstep launches (which spread one step over many workgroups) are as fast.
   bool use_sweep(int l) const {
-    if (p->layer != MGRIT_LAYER_DENSE || pl.fcP || p->m < 3 || !sweep_enabled()) return false;
+    if (pl.fcP || p->m < 3 || !sweep_enabled()) return false;
+    if (p->layer == MGRIT_LAYER_CONV3X3)         // workgroup = (interval, image)
+      return conv_sweep_supported(p->Himg, p->Wimg, p->C, p->dtype) && (long long)pl.B * pl.Nl[l + 1] >= 128;
     if (!sweep_supported(p->q, p->dtype)) return false;
     return sweep_blocks(pl.M, pl.Nl[l + 1]) >= 128;
   }
@@ -274,7 +277,12 @@ struct Solver {
       else         { a.lb = 0;                   a.ls = (long long)p->m * mp;  a.lk = mp; }
       a.hs = pl.hl[l]; a.act = act; a.nsteps = p->m - 1; a.nchains = Nc;
       a.M = pl.M; a.q = pl.Nf; a.E = pl.E; a.wsize = pl.wsize;
-      if (err == hipSuccess) chk(launch_sweep(a, p->dtype, s));
+      if (p->layer == MGRIT_LAYER_CONV3X3) {
+        a.M = pl.B; a.Himg = p->Himg; a.Wimg = p->Wimg; a.C = p->C;
+        if (err == hipSuccess) chk(launch_conv_sweep(a, s));
+      } else if (err == hipSuccess) {
+        chk(launch_sweep(a, p->dtype, s));
+      }
       for (int k = 1; k <= tail; ++k) propagate(l, (long long)Nc * p->m + k, p->m, 1);
       return;
     }

@@ -126,15 +126,20 @@ struct SweepArgs {
   float hs;
   int act, nsteps, nchains, M, q;
   long long E, wsize;
+  int Himg, Wimg, C;                     // convolution sweep only (then M = images per state)
 };
 bool       sweep_supported(int q, int dtype);
 int        sweep_blocks(int M, int nchains);
 hipError_t launch_sweep(const SweepArgs& a, int dtype, hipStream_t s);
+// The same for 3x3 convolution layers of at most 16 float channels on images small enough for one workgroup
+// (a convolution needs its neighbours' rows, so the unit is a whole image): workgroup (interval ci, image).
+bool       conv_sweep_supported(int Himg, int Wimg, int C, int dtype);
+hipError_t launch_conv_sweep(const SweepArgs& a, hipStream_t s);
 
 // launch tracing (diagnostic): kernel classes, and begin / collect
 enum { TRACE_DENSE_F32_64 = 0, TRACE_DENSE_F32_128, TRACE_DENSE_BF16_64, TRACE_DENSE_BF16_128,
        TRACE_CONV_F32, TRACE_CONV_BF16, TRACE_GRAD, TRACE_SWEEP_F32, TRACE_SWEEP_BF16, TRACE_DENSE_F32_KS8,
-       TRACE_DENSE_F32_KS, TRACE_DENSE_BF16_KS, TRACE_DENSE_BF16_KS8, TRACE_NCLASS };
+       TRACE_DENSE_F32_KS, TRACE_DENSE_BF16_KS, TRACE_DENSE_BF16_KS8, TRACE_CONV_SWEEP_F32, TRACE_NCLASS };
 void trace_begin();
 int  trace_end(double* ms, long long* launches, long long* units, double* bytes, int ncls);
 void trace_before(hipStream_t s);

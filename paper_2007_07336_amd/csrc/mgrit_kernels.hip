@@ -5,6 +5,7 @@
 
 #include <stdlib.h>
 
+#include <type_traits>
 #include <vector>
 
 namespace mgrit {
@@ -2039,6 +2040,261 @@ hipError_t launch_sweep(const SweepArgs& a, int dtype, hipStream_t s) {
                      (a.G ? 4.0 : 0.0) * (double)a.E + 4.0 * (double)a.E;
   trace_after(s, dtype == 0 ? TRACE_SWEEP_F32 : TRACE_SWEEP_BF16, (long long)a.nchains * a.nsteps,
               (double)a.nchains * (a.nsteps * per + 4.0 * (double)a.E));
+  return e;
+}
+
+// ------------------------------------------------------------------------------------------
+// Fused F-relaxation sweep for 3x3 convolution layers with at most 16 float channels.  A workgroup owns one
+// image of one coarse interval and marches through all steps of the sweep.  In LDS: the fp32 state of the image
+// St [pixel][20], its matrix-core operand P (Dm .* state) as a patch with a one-pixel frame of zeros
+// [(H+2)(W+2)][20], and the nine 16x16 weight slices of the current layer.  A step multiplies 16-pixel blocks
+// (wavefront w of eight takes blocks w, w+8, ..) with v_mfma_f32_16x16x4_f32 over the nine taps and adds h*act(.) into St
+// right away (St is not an operand, so no barrier is needed for that); after a barrier one float4 pass over
+// whole pixels adds the right-hand side, stores the new state to global memory and writes the next operand.
+// ------------------------------------------------------------------------------------------
+constexpr int CSW_CS = 20;                       // floats per pixel in LDS (16 channels + 4 padding)
+constexpr int CSW_MAXBLK = 52;                   // 16-pixel blocks per image at most
+constexpr int CSW_PASS = (CSW_MAXBLK * 16 * 4 + 511) / 512;   // float4 pieces per thread in a pass over the image at most
+constexpr int CSW_NT = 512;                      // eight wavefronts: two per SIMD hide each other's LDS and barrier waits
+static size_t conv_sweep_smem(int Himg, int Wimg) {
+  return ((size_t)Himg * Wimg + (size_t)(Himg + 2) * (Wimg + 2) + 9 * 16) * CSW_CS * sizeof(float);
+}
+bool conv_sweep_supported(int Himg, int Wimg, int C, int dtype) {
+  if (dtype != 0 || (C != 8 && C != 16) || Himg < 1 || Wimg < 1 || Wimg > 256) return false;
+  if ((Himg * Wimg + 15) / 16 > CSW_MAXBLK) return false;
+  return conv_sweep_smem(Himg, Wimg) <= (size_t)150 * 1024;
+}
+
+__global__ __launch_bounds__(CSW_NT) void conv_sweep_kernel(SweepArgs a, unsigned wmagic) {
+  constexpr int NT = CSW_NT;                                 // shadows the file-wide 256
+  constexpr int CS = CSW_CS;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  const int H = a.Himg, Wd = a.Wimg, C = a.C, HW = H * Wd, PW = Wd + 2;
+  float* St = reinterpret_cast<float*>(smem_raw);            // [HW][CS]
+  float* P = St + HW * CS;                                   // [(H+2)*(W+2)][CS]
+  float* Wt = P + (H + 2) * PW * CS;                         // [9][16][CS]
+  const int tid = threadIdx.x, lane = tid & 63, r16 = lane & 15, kq = lane >> 4;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6); // the same in every lane: block conditions stay scalar
+  const int L = logical_block();
+  const long long ci = L / a.M;
+  const int img = L % a.M;
+  const long long img_off = (long long)img * HW * C;
+  const float* Wall = reinterpret_cast<const float*>(a.W);
+  const float* Dall = reinterpret_cast<const float*>(a.Dm);
+  auto layer_of = [&](int k) { return a.lb + ci * a.ls + (long long)(k - 1) * a.lk; };
+  const int cq = C / 4, n4 = HW * cq;                        // float4 pieces of a pixel (2 or 4) / of the image
+  const int cqs = C == 16 ? 2 : 1;                           // log2(cq)
+  const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+
+  // weight slices of a layer: 9 taps x 16 rows x 4 pieces = 576 pieces of 16 bytes, rows / channels past C are zero
+  uint4 wall[2];
+  unsigned wallmask = 0;
+  auto load_w = [&](long long layer) {
+    const float* Wp = Wall + layer * a.wsize;
+    wallmask = 0;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int p = tid + NT * i;
+      const int tap = p >> 6, row = (p >> 2) & 15, kc = (p & 3) * 4;
+      const bool ok = p < 576 && row < C && kc < C;
+      wallmask |= ok ? (1u << i) : 0u;
+      wall[i] = *reinterpret_cast<const uint4*>(Wp + (ok ? (unsigned)((row * 9 + tap) * C + kc) : 0u));
+    }
+  };
+  auto store_w = [&]() {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int p = tid + NT * i;
+      if (p < 576) {
+        const int tap = p >> 6, row = (p >> 2) & 15, kc = (p & 3) * 4;
+        uint4 v = wall[i];
+        if (!((wallmask >> i) & 1u)) v = make_uint4(0, 0, 0, 0);
+        *reinterpret_cast<uint4*>(&Wt[(tap * 16 + row) * CS + kc]) = v;
+      }
+    }
+  };
+  load_w(layer_of(1));
+
+  // ---- the frame of the operand patch, and with fewer than 16 channels the channels past C, are zero for the
+  // whole sweep: cleared once (the frame alone when every channel is written)
+  if (C < 16) {
+    for (int p = tid; p < (H + 2) * PW * (CS / 4); p += NT) *reinterpret_cast<float4*>(P + 4 * p) = zero;
+  } else {
+    const int nfr = 2 * PW + 2 * H;                          // top and bottom rows, left and right columns
+    for (int p = tid; p < nfr * 4; p += NT) {
+      const int f = p >> 2, c4 = (p & 3) * 4;
+      int fy, fx;
+      if (f < PW) { fy = 0; fx = f; }
+      else if (f < 2 * PW) { fy = H + 1; fx = f - PW; }
+      else { const int t = f - 2 * PW; fy = 1 + (t >> 1); fx = (t & 1) ? PW - 1 : 0; }
+      *reinterpret_cast<float4*>(P + (fy * PW + fx) * CS + c4) = zero;
+    }
+  }
+  __syncthreads();
+  {
+    const float* sp = a.S + (a.sm.base + ci * a.sm.stride) * a.E + img_off;
+    const float* dp = Dall ? Dall + layer_of(1) * a.E + img_off : nullptr;
+    for (int p = tid; p < n4; p += NT) {
+      const int px = p >> cqs, c4 = (p - (px << cqs)) * 4;
+      const float4 v = *reinterpret_cast<const float4*>(sp + 4 * p);
+      *reinterpret_cast<float4*>(St + px * CS + c4) = v;
+      float4 o = v;
+      if (dp) { const float4 d = *reinterpret_cast<const float4*>(dp + 4 * p); o.x *= d.x; o.y *= d.y; o.z *= d.z; o.w *= d.w; }
+      const int py = div_small(px, wmagic);
+      *reinterpret_cast<float4*>(P + ((py + 1) * PW + (px - py * Wd) + 1) * CS + c4) = o;
+    }
+  }
+  store_w();
+  __syncthreads();
+
+  const int nblk = (HW + 15) / 16;
+#ifdef MGRIT_TIMING
+  long long tm_mma = 0, tm_b1 = 0, tm_pass = 0, tm_b2 = 0;
+  const long long tm_begin = __builtin_readcyclecounter();
+#endif
+  for (int k = 1; k <= a.nsteps; ++k) {
+#ifdef MGRIT_TIMING
+    const long long tm0 = __builtin_readcyclecounter();
+#endif
+    const long long layer = layer_of(k);
+    if (k < a.nsteps) load_w(layer_of(k + 1));               // next layer's slices: in flight during this step
+    float bo = 0.0f;
+    if (a.bias && r16 < C) bo = a.bias[layer * C + r16];
+    // the pass at the end of the step needs the right-hand side and the next step's act' factors: requested now,
+    // their latency passes behind the matrix instructions
+    const bool build = k < a.nsteps;
+    const float* gp = a.G ? a.G + (a.gb + ci * a.gs + k) * a.E + img_off : nullptr;
+    const float* dp = (Dall && build) ? Dall + layer_of(k + 1) * a.E + img_off : nullptr;
+    float4 gpre[CSW_PASS], dpre[CSW_PASS];
+#pragma unroll
+    for (int i = 0; i < CSW_PASS; ++i) {
+      const int p = tid + NT * i;
+      const unsigned off = p < n4 ? 4u * (unsigned)p : 0u;
+      if (gp) gpre[i] = *reinterpret_cast<const float4*>(gp + off);
+      if (dp) dpre[i] = *reinterpret_cast<const float4*>(dp + off);
+    }
+    // the nine B fragments of this lane (output channel r16, input channels 4 kq .. + 3) serve every block
+    float4 bf[9];
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap) bf[tap] = *reinterpret_cast<const float4*>(Wt + (tap * 16 + r16) * CS + 4 * kq);
+    // four blocks at a time: their accumulators are independent, so consecutive matrix instructions never
+    // wait for each other.  nv = blocks of the group inside the image (the same for all lanes of the wavefront).
+    auto group = [&](int blk0, auto full) {
+      constexpr bool FULL = decltype(full)::value;
+      const int nv = FULL ? 4 : (nblk - blk0 + 7) / 8;
+      const float* ap[4];
+      floatx4 acc[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        int p = (blk0 + 8 * i) * 16 + r16;                   // this lane's A row: pixel p (rows past the image use pixel 0)
+        if (p >= HW) p = 0;
+        const int py = div_small(p, wmagic);
+        ap[i] = P + (py * PW + (p - py * Wd)) * CS + 4 * kq;
+        acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+      }
+#pragma unroll
+      for (int tap = 0; tap < 9; ++tap) {
+        const int toff = ((tap / 3) * PW + (tap % 3)) * CS;
+        float4 af[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) if (FULL || i < nv) af[i] = *reinterpret_cast<const float4*>(ap[i] + toff);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) if (FULL || i < nv) acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[i].x, bf[tap].x, acc[i], 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) if (FULL || i < nv) acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[i].y, bf[tap].y, acc[i], 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) if (FULL || i < nv) acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[i].z, bf[tap].z, acc[i], 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) if (FULL || i < nv) acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[i].w, bf[tap].w, acc[i], 0, 0, 0);
+      }
+      // register v of a lane holds pixel 4 kq + v of the block, output channel r16.  All sixteen state values
+      // are read before the first is written back (written as one read-modify-write each, every read would wait
+      // for the write before it: the compiler cannot tell that the addresses differ).
+      float sv[4][4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int pv = (blk0 + 8 * i) * 16 + 4 * kq + v;   // >= HW past the image
+          sv[i][v] = St[(pv < HW ? pv : 0) * CS + r16];
+        }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int pv = (blk0 + 8 * i) * 16 + 4 * kq + v;
+          if ((FULL || i < nv) && pv < HW && r16 < C) St[pv * CS + r16] = sv[i][v] + a.hs * act_fn(acc[i][v] + bo, a.act);
+        }
+    };
+    for (int blk0 = wave; blk0 < nblk; blk0 += 32) {
+      if (blk0 + 24 < nblk) group(blk0, std::true_type());
+      else group(blk0, std::false_type());
+    }
+#ifdef MGRIT_TIMING
+    const long long tm1 = __builtin_readcyclecounter();
+#endif
+    __syncthreads();                                         // every block is done with P and has updated St
+#ifdef MGRIT_TIMING
+    const long long tm2 = __builtin_readcyclecounter();
+#endif
+    {
+      float* xo = a.X + (a.xb + ci * a.xs + (long long)k * a.xk) * a.E + img_off;
+#pragma unroll
+      for (int i = 0; i < CSW_PASS; ++i) {
+        const int p = tid + NT * i;
+        if (p < n4) {
+          const int px = p >> cqs, c4 = (p - (px << cqs)) * 4;
+          float4 u = *reinterpret_cast<const float4*>(St + px * CS + c4);
+          if (gp) {
+            u.x += gpre[i].x; u.y += gpre[i].y; u.z += gpre[i].z; u.w += gpre[i].w;
+            *reinterpret_cast<float4*>(St + px * CS + c4) = u;
+          }
+          *reinterpret_cast<float4*>(xo + 4 * p) = u;
+          if (build) {
+            if (dp) { u.x *= dpre[i].x; u.y *= dpre[i].y; u.z *= dpre[i].z; u.w *= dpre[i].w; }
+            const int py = div_small(px, wmagic);
+            *reinterpret_cast<float4*>(P + ((py + 1) * PW + (px - py * Wd) + 1) * CS + c4) = u;
+          }
+        }
+      }
+      if (build) store_w();
+    }
+#ifdef MGRIT_TIMING
+    const long long tm3 = __builtin_readcyclecounter();
+#endif
+    __syncthreads();                                         // next operand and weight slices complete
+#ifdef MGRIT_TIMING
+    // diagnostic build only: phase times in cycles overwrite the first values of the last state of the image
+    const long long tm4 = __builtin_readcyclecounter();
+    tm_mma += tm1 - tm0; tm_b1 += tm2 - tm1; tm_pass += tm3 - tm2; tm_b2 += tm4 - tm3;
+    if (k == a.nsteps && (tid & 63) == 0) {
+      float* xt = a.X + (a.xb + ci * a.xs + (long long)k * a.xk) * a.E + img_off + 8 * wave;
+      xt[0] = (float)(tm0 - tm_begin); xt[1] = (float)tm_mma; xt[2] = (float)tm_b1; xt[3] = (float)tm_pass; xt[4] = (float)tm_b2;
+    }
+#endif
+  }
+}
+
+hipError_t launch_conv_sweep(const SweepArgs& a, hipStream_t s) {
+  if (a.nchains <= 0 || a.nsteps <= 0) return hipSuccess;
+  if (!conv_sweep_supported(a.Himg, a.Wimg, a.C, 0) || a.M < 1) return hipErrorInvalidValue;
+  const size_t smem = conv_sweep_smem(a.Himg, a.Wimg);
+  static LdsOptIn opt;
+  if (opt.need(smem)) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_sweep_kernel),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+  }
+  const unsigned blocks = (unsigned)a.M * (unsigned)a.nchains;
+  const unsigned wmagic = ((1u << 20) + (unsigned)a.Wimg - 1u) / (unsigned)a.Wimg;
+  trace_before(s);
+  hipLaunchKernelGGL(conv_sweep_kernel, dim3(blocks), dim3(CSW_NT), smem, s, a, wmagic);
+  const hipError_t e = hipGetLastError();
+  // algorithmic bytes per layer step: weights and bias, the act' factor, the right-hand side, the state out
+  // (the state in is read once per chain)
+  const double per = 4.0 * (double)a.wsize + (a.bias ? 4.0 * a.C : 0.0) + (a.Dm ? 4.0 : 0.0) * (double)a.E +
+                     (a.G ? 4.0 : 0.0) * (double)a.E + 4.0 * (double)a.E;
+  trace_after(s, TRACE_CONV_SWEEP_F32, (long long)a.nchains * a.nsteps, (double)a.nchains * (a.nsteps * per + 4.0 * (double)a.E));
   return e;
 }
 

@@ -500,6 +500,84 @@ def test_dense_adjoint_fused_sweeps(wl, fused, monkeypatch):
     assert eL <= tol and eW <= tol and eb <= tol, (eL, eW, eb)
 
 
+# ------------------------------------------------------------------ fused sweeps of convolution layers
+CONV_SWEEP_CASES = [
+    I.reduced(I.cfg3(2), name="csweep_fp32_c16_7x5_B8_N64_m4_L2_FCF", B=8, Himg=7, Wimg=5, N=64),
+    # 784 pixels: 49 blocks of 16 over eight wavefronts (the last one a block short); 8 channels (half of the MFMA
+    # columns padding, the whole patch cleared); trailing F-points behind the fused launch
+    I.reduced(I.cfg3(1), name="csweep_fp32_c8_28x28_B8_N66_m4_L2_F_tanh", B=8, C=8, N=66, relax=I.RELAX_F, act=I.TANH,
+              lifted_input=False),
+    I.reduced(I.cfg3(1), name="csweep_fp32_c16_28x28_B8_N64_m4_L2", B=8, N=64, bias_var=0.1),
+    # three levels with enough intervals that the middle level's sweeps are fused too (they carry the FAS right-hand side)
+    I.reduced(I.cfg3(1), name="csweep_fp32_c16_9x9_B32_N48_m3_L3_rhs", B=32, Himg=9, Wimg=9, N=48, m=3, max_levels=3,
+              lifted_input=False),
+    # a pixel count that is no multiple of 16 and a one-pixel-wide image
+    I.reduced(I.cfg3(1), name="csweep_fp32_c16_5x1_B16_N32_m4", B=16, Himg=5, Wimg=1, N=32, m=4, max_levels=2,
+              lifted_input=False, act=I.TANH),
+]
+
+
+@pytest.mark.parametrize("fused", [True, False], ids=["fused", "lockstep"])
+@pytest.mark.parametrize("wl", CONV_SWEEP_CASES, ids=lambda w: w.name)
+def test_conv_forward_fused_sweeps(wl, fused, monkeypatch):
+    import paper_2007_07336_amd as M
+    if not fused:
+        monkeypatch.setenv("MGRIT_NO_SWEEP", "1")
+    _announce(f"{wl.name} fused={fused}")
+    data = I.generate(wl)
+    gp = GpuProblem(wl, data)
+    M.mgrit_trace_begin()
+    rc, U, hist, it = gp.forward()
+    tr = M.mgrit_trace_end()
+    assert ("conv_sweep_kernel" in tr) == fused, tr                           # the path under test did run
+    Uo, hist_o, it_o = oracle_forward(wl, data)
+    assert rel_l2_per_state(U, Uo) <= TOL[wl.dtype]
+    assert it == it_o
+    for a, b in zip(hist, hist_o):
+        assert abs(a - b) <= 1e-3 * max(b, 1e-6)
+
+
+def test_conv_fused_sweeps_nested_start():
+    wl = I.reduced(I.cfg3(2), name="csweep_fp32_c16_6x6_B32_N48_m3_L3_nested", B=32, Himg=6, Wimg=6, N=48, m=3, max_levels=3,
+                   lifted_input=False, act=I.TANH)
+    _announce(wl.name)
+    data = I.generate(wl)
+    gp = GpuProblem(wl, data, init=3)
+    rc, U, hist, it = gp.forward()
+    Uo, hist_o, _ = oracle_forward(wl, data, init=3)
+    assert rel_l2_per_state(U, Uo) <= 1e-5
+
+
+CONV_SWEEP_ADJ_CASES = [
+    I.reduced(I.cfg3(2), name="adj_csweep_fp32_c16_7x5_B8_N64_m4_tanh", B=8, Himg=7, Wimg=5, N=64, act=I.TANH),
+    I.reduced(I.cfg3(1), name="adj_csweep_fp32_c8_12x12_B8_N66_m4_relu_trailing", B=8, C=8, Himg=12, Wimg=12, N=66,
+              lifted_input=False),
+    I.reduced(I.cfg3(1), name="adj_csweep_fp32_c16_9x9_B32_N48_m3_L3_rhs", B=32, Himg=9, Wimg=9, N=48, m=3, max_levels=3,
+              lifted_input=False, act=I.TANH),
+]
+
+
+@pytest.mark.parametrize("fused", [True, False], ids=["fused", "lockstep"])
+@pytest.mark.parametrize("wl", CONV_SWEEP_ADJ_CASES, ids=lambda w: w.name)
+def test_conv_adjoint_fused_sweeps(wl, fused, monkeypatch):
+    import paper_2007_07336_amd as M
+    if not fused:
+        monkeypatch.setenv("MGRIT_NO_SWEEP", "1")
+    _announce(f"{wl.name} fused={fused}")
+    data = I.generate(wl)
+    Uo, _, _ = oracle_forward(wl, data, max_iter=2)
+    U = Uo.astype(np.float32)
+    lamN = np.random.default_rng(9).standard_normal(wl.state_shape).astype(np.float32)
+    gp = GpuProblem(wl, data)
+    M.mgrit_trace_begin()
+    Lam, dW, db, hist, it = gp.adjoint(U, lamN)
+    tr = M.mgrit_trace_end()
+    assert ("conv_sweep_kernel" in tr) == fused, tr
+    Lo, dWo, dbo, hist_o, it_o = oracle_adjoint(wl, data, U, lamN)
+    eL, eW, eb = rel_l2_per_state(Lam, Lo), rel_l2_per_state(dW, dWo), rel_l2_per_state(db, dbo)
+    assert eL <= 1e-5 and eW <= 1e-5 and eb <= 1e-5, (eL, eW, eb)
+
+
 def test_fused_sweeps_repeat_bitwise_and_replay_from_a_hip_graph():
     """The fused sweep launches are deterministic, and a forward + adjoint pair that uses them can be captured
     into a HIP graph and replayed to the same bits."""
