@@ -1745,16 +1745,30 @@ ConvGradGeom conv_grad_geom(int B, int Himg, int Wimg, int C, int dtype, int lay
   const int es = dtype == 0 ? 4 : 2, pad = dtype == 0 ? Op<float>::PAD : Op<__bf16>::PAD;
   const int kstep = dtype == 0 ? Op<float>::KSTEP : Op<__bf16>::KSTEP;
   gm.Wp = (Wimg + 7) & ~7;
-  gm.R = 64 / gm.Wp;
-  if (gm.R < 1) gm.R = 1;
-  if (gm.R > Himg) gm.R = Himg;
+  // Image rows per slab.  A thread transposes at most one 4x4 block of G and three of the U patch per slab, so
+  // R * blocks_per_row <= 256 and (R + 2) * blocks_per_row <= 768; 64 / Wp rows always satisfy that (64 channels,
+  // 32 columns: 2 rows).  With fewer channels more rows fit, and a slab is worth a fixed two barriers and one
+  // memory latency whatever its size: take as many as keep the workgroup under 72 KB of LDS (two per CU).
+  const int bpr = ((Wimg + 3) / 4) * ((C + 3) / 4);    // 4x4 blocks per image row
+  auto smem_of = [&](int R) {
+    const int KL = (R * gm.Wp + kstep - 1) / kstep * kstep, PU = (R + 2) * gm.Wp + pad, PG = KL + pad;
+    return ((size_t)3 * C * PU + (size_t)C * PG + PU) * es;             // U copies, G, the row of ones
+  };
+  int Rmin = 64 / gm.Wp;
+  if (Rmin < 1) Rmin = 1;
+  int R = 256 / (bpr > 0 ? bpr : 1);
+  if (R < Rmin) R = Rmin;
+  while (R > Rmin && ((R + 2) * bpr > 768 || smem_of(R) > (size_t)72 * 1024)) --R;
+  if (R > Himg) R = Himg;
+  R = (Himg + (Himg + R - 1) / R - 1) / ((Himg + R - 1) / R);         // the same number of slabs, of balanced height
+  gm.R = R;
   const int KP = gm.R * gm.Wp;
   gm.KL = (KP + kstep - 1) / kstep * kstep;
   gm.PU = (gm.R + 2) * gm.Wp + pad;                     // reads reach slot 2*Wp + KL - 1 <= (R+2)*Wp + pad - 1
   gm.PG = gm.KL + pad;
   gm.spi = (Himg + gm.R - 1) / gm.R;
   gm.slabs = B * gm.spi;
-  gm.smem = ((size_t)3 * C * gm.PU + (size_t)C * gm.PG + gm.PU) * es;      // U copies, G, the row of ones
+  gm.smem = smem_of(gm.R);
   gm.ok = Wimg <= 64 && gm.smem <= (size_t)150 * 1024;
   int ch = (512 + layers - 1) / (layers > 0 ? layers : 1);  // aim at two workgroups per compute unit
   if (ch > 64) ch = 64;
