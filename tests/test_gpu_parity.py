@@ -578,12 +578,16 @@ def test_conv_adjoint_fused_sweeps(wl, fused, monkeypatch):
     assert eL <= 1e-5 and eW <= 1e-5 and eb <= 1e-5, (eL, eW, eb)
 
 
-def test_fused_sweeps_repeat_bitwise_and_replay_from_a_hip_graph():
+@pytest.mark.parametrize("kind", ["dense", "conv"])
+def test_fused_sweeps_repeat_bitwise_and_replay_from_a_hip_graph(kind):
     """The fused sweep launches are deterministic, and a forward + adjoint pair that uses them can be captured
     into a HIP graph and replayed to the same bits."""
     import torch
     import paper_2007_07336_amd as M
-    wl = I.reduced(I.cfg2(2), name="sweep_fp32_q256_B64_N256_graph", q=256, B=64, N=256)
+    if kind == "dense":
+        wl = I.reduced(I.cfg2(2), name="sweep_fp32_q256_B64_N256_graph", q=256, B=64, N=256)
+    else:
+        wl = I.reduced(I.cfg3(2), name="csweep_fp32_c16_12x12_B16_N64_graph", B=16, Himg=12, Wimg=12, N=64, act=I.TANH)
     _announce(wl.name)
     data = I.generate(wl)
     gp = GpuProblem(wl, data)
@@ -600,7 +604,7 @@ def test_fused_sweeps_repeat_bitwise_and_replay_from_a_hip_graph():
     M.mgrit_trace_begin()
     pair()
     tr = M.mgrit_trace_end()
-    assert any(k.startswith("dense_sweep_kernel") for k in tr), tr
+    assert any(k.startswith("dense_sweep_kernel" if kind == "dense" else "conv_sweep_kernel") for k in tr), tr
     torch.cuda.synchronize()
     ref = [t.clone() for t in (gp.U, Lam, dW, db)]
     for t in (gp.U, Lam, dW, db):
