@@ -196,6 +196,9 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
   return s;
 }
 
+// (In the kernels below the wavefront index is read with readfirstlane: the compiler cannot see that tid >> 6 is
+// the same in all lanes, and with a scalar index the address arithmetic and conditions that depend on it stay on
+// the scalar unit.)
 // XCD-aware workgroup order: hardware deals consecutive workgroup ids round-robin to the 8
 // XCDs; remap so that consecutive logical tiles (which share a group's state and weights)
 // land on the same XCD and meet in its L2.
@@ -366,7 +369,7 @@ __global__ __launch_bounds__(NT) void dense_step_kernel(StepArgs a) {
   WT* Bs = As + BM * ST;                             // [BN][ST]
   __shared__ float red[4];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, c = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), g = lane >> 5, c = lane & 31;
   const int tiles_n = (a.Nf + BN - 1) / BN;
   const int L = logical_block();
   const int gi = L / a.tiles, tile = L % a.tiles;
@@ -528,7 +531,7 @@ __global__ __launch_bounds__(NW * 64) void dense_ksplit_kernel(StepArgs a) {
   static_assert(ksplit_smem<WT>(NW) >= sizeof(float) * NW * 32 * 36, "the partial tiles reuse the staging areas");
   float (*part)[32][36] = reinterpret_cast<float (*)[32][36]>(smem_raw);     // [NW][32][36], after the k loop
   __shared__ float red[NW];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, c = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), g = lane >> 5, c = lane & 31;
   const int tiles_n = (a.Nf + 31) / 32;
   const int L = logical_block();
   const int gi = L / a.tiles, tile = L % a.tiles;
@@ -692,7 +695,7 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   __shared__ float red[4];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, c = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), g = lane >> 5, c = lane & 31;
   const int C = a.Nf, H = a.Himg, Wd = a.Wimg, TH = a.TH;
   const int Cp = N16 ? 16 : (C + KSTEP - 1) / KSTEP * KSTEP;   // a compile-time value in the 16-wide variant (C <= 16)
   const int CS = Cp + PAD;
@@ -1331,7 +1334,7 @@ __global__ __launch_bounds__(NT) void dense_grad_kernel(GradArgs a) {
   __shared__ __attribute__((aligned(16))) unsigned char lds_raw[TILE_B > STAGE_B ? TILE_B : STAGE_B];
   OT* As = reinterpret_cast<OT*>(lds_raw);
   OT* Bs = As + BM * ST;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, c = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), g = lane >> 5, c = lane & 31;
   const int q = a.Nf;
   const int tiles_n = (q + BN - 1) / BN;
   const int L = logical_block();
@@ -1434,7 +1437,7 @@ __global__ __launch_bounds__(NT) void conv_grad_tap_kernel(GradArgs a) {
   constexpr int BKR = 32, ST = BKR + Op<OT>::PAD, KSTEP = Op<OT>::KSTEP;
   __shared__ __attribute__((aligned(16))) OT As[64 * ST];
   __shared__ __attribute__((aligned(16))) OT Bs[64 * ST];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, c = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), g = lane >> 5, c = lane & 31;
   const int C = a.Nf, H = a.Himg, Wd = a.Wimg;
   const int L = logical_block();
   const int gi = L / 9, tap = L % 9;
@@ -1524,7 +1527,7 @@ template <typename OT, int TM, int TN>
 __global__ __launch_bounds__(NT) void conv_grad_kernel(GradArgs a) {
   constexpr int KSTEP = Op<OT>::KSTEP;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, c = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), g = lane >> 5, c = lane & 31;
   const int C = a.Nf, H = a.Himg, Wd = a.Wimg;
   const int Wp = a.gWp, R = a.gR, PU = a.gPU, PG = a.gPG, KL = a.gKL;
   OT* Ut = reinterpret_cast<OT*>(smem_raw);             // [3][C][PU]
@@ -1829,7 +1832,7 @@ __global__ __launch_bounds__(NT) void dense_sweep_kernel(SweepArgs a) {
   WT* A = reinterpret_cast<WT*>(S + R * Q);                // [R][AST] operand of the current step
   WT* Bs = A + R * AST;                                    // [2][Q][ST] weight slabs: row = output column, k fastest
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, c = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), g = lane >> 5, c = lane & 31;
   const int L = logical_block();
   const int nsl = (a.M + R - 1) / R;
   const long long ci = L / nsl;
