@@ -11,8 +11,11 @@
  *
  * Memory.  The caller owns every buffer.  Pointers marked "device" are HIP device pointers
  * aligned to 256 bytes; pointers marked "host" are ordinary host pointers.  The library
- * allocates no device memory and keeps no state between calls (the optional launch trace at
- * the end of this file aside).  All device work is enqueued
+ * allocates no device memory and keeps no state of a solve between calls.  What it does keep, per
+ * process, is bookkeeping: for every kernel that needs more than 64 KB of LDS, the largest size it
+ * has been raised to on each device (the opt-in is a per-device attribute of the kernel, set at
+ * the first launch that needs it), and the optional launch trace at the end of this file.  None
+ * of this is guarded: call the library from one host thread at a time.  All device work is enqueued
  * on `hip_stream` (a hipStream_t passed as void*; NULL = the default stream).  A call that
  * writes a host output (resnorm_hist, iters_done, norm_out) synchronises that stream before
  * it returns; otherwise it returns with its work in flight on the stream.  Such a call (tol <= 0,

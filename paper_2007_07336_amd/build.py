@@ -23,9 +23,9 @@ def build(verbose: bool = True) -> str:
     objs = []
     flags = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17",
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-             # the 256x256 tile holds 256 accumulator registers per lane; its fully unrolled epilogue is
-             # past the default cost limit of `#pragma unroll`, and a loop left rolled would index the
-             # accumulators dynamically and push them to scratch memory
+             # kernels that keep a few hundred accumulator / state registers per lane have fully unrolled
+             # loops past the default cost limit of `#pragma unroll`; a loop left rolled would index those
+             # registers dynamically and push them to scratch memory
              "-mllvm", "-pragma-unroll-threshold=200000",
              "-I", os.path.join(ROOT, "include")]
     procs = []

@@ -437,9 +437,6 @@ __global__ __launch_bounds__(NT) void dense_step_kernel(StepArgs a) {
   // The k slabs are visited in a rotated order that depends on the group: with a power-of-two
   // row pitch every workgroup would otherwise ask the same HBM channels for the same k at the
   // same time.  Workgroups of one group keep a common order, so they still meet in L2.
-#ifdef MGRIT_TIMING
-  const long long t_start = __builtin_readcyclecounter();
-#endif
   const int nk = (K + BK - 1) / BK;
   const int rot = (int)(((long long)gi * 5) % nk);
   auto slab_k0 = [&](int j) { int sl = rot + j; if (sl >= nk) sl -= nk; return sl * BK; };
@@ -472,18 +469,8 @@ __global__ __launch_bounds__(NT) void dense_step_kernel(StepArgs a) {
   long long row0[TM];
 #pragma unroll
   for (int i = 0; i < TM; ++i) row0[i] = m0 + wm0 + i * 32;
-#ifdef MGRIT_TIMING
-  const long long t_loop = __builtin_readcyclecounter();
-#endif
   static_assert(WC == 2, "the launch wrapper sizes the epilogue staging for two wavefront columns");
   epilogue<TM, TN>(a, gi, layer, acc, row0, (long long)a.M, n0 + wn0, L, red, reinterpret_cast<float*>(smem_raw));
-#ifdef MGRIT_TIMING
-  // diagnostic build only: overwrite the norm partial with phase times in cycles
-  __syncthreads();
-  const long long t_end = __builtin_readcyclecounter();
-  if (a.norm_partial && threadIdx.x == 0)
-    a.norm_partial[L] = (L & 1) ? (float)(t_end - t_loop) : (float)(t_loop - t_start);
-#endif
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1903,10 +1890,6 @@ __global__ __launch_bounds__(NT) void dense_sweep_kernel(SweepArgs a) {
       cvt_store4(&A[row * AST + c4t], v);
     }
   };
-#ifdef MGRIT_TIMING
-  long long t_mma = 0, t_epi = 0, t_bld = 0;
-  const long long t_begin = __builtin_readcyclecounter();
-#endif
   __syncthreads();                                         // S complete
   build_operand(layer_of(1));
   // slab j lives in ring slot j % PF and goes to LDS buffer j % 2; a slot is reloaded with slab j + PF as
@@ -1917,9 +1900,6 @@ __global__ __launch_bounds__(NT) void dense_sweep_kernel(SweepArgs a) {
   __syncthreads();                                         // the first operand is complete
 
   for (int k = 1; k <= a.nsteps; ++k) {
-#ifdef MGRIT_TIMING
-    const long long t_k0 = __builtin_readcyclecounter();
-#endif
     floatx16 acc[1][NBW];
     // bias of this thread's column group in the float4 pass: requested before the contraction, its latency
     // would otherwise open the epilogue
@@ -1948,9 +1928,6 @@ __global__ __launch_bounds__(NT) void dense_sweep_kernel(SweepArgs a) {
         }
       }
     }
-#ifdef MGRIT_TIMING
-    const long long t_k1 = __builtin_readcyclecounter();
-#endif
     // ---- epilogue of step k.  The raw sums go through the weight buffer that the last slab has just left
     // (the other one already holds the next layer's first slab), so that the update is one float4 pass over
     // whole rows: new state to S and to global memory, and the next step's operand to A.
@@ -1963,9 +1940,6 @@ __global__ __launch_bounds__(NT) void dense_sweep_kernel(SweepArgs a) {
       for (int r = 0; r < 16; ++r)                          // lane holds rows 8*(r/4) + 4*g + r%4 of column n
         Z[(8 * (r >> 2) + 4 * g + (r & 3)) * ZST + (wave * NBW + t) * 32 + c] = acc[0][t][r];
     __syncthreads();
-#ifdef MGRIT_TIMING
-    const long long t_k2 = __builtin_readcyclecounter();
-#endif
     {
       const float* gp = a.G ? a.G + (a.gb + ci * a.gs + k) * a.E + slice_off : nullptr;
       float* xo = a.X + (a.xb + ci * a.xs + (long long)k * a.xk) * a.E + slice_off;
@@ -1997,16 +1971,6 @@ __global__ __launch_bounds__(NT) void dense_sweep_kernel(SweepArgs a) {
       }
     }
     __syncthreads();                                       // next operand complete; the sums' buffer is free again
-#ifdef MGRIT_TIMING
-    // diagnostic build only: phase times in cycles overwrite the first values of the last state slice
-    const long long t_k3 = __builtin_readcyclecounter();
-    t_mma += t_k1 - t_k0; t_epi += t_k2 - t_k1; t_bld += t_k3 - t_k2;
-    __syncthreads();
-    if (k == a.nsteps && tid == 0) {
-      float* xt = a.X + (a.xb + ci * a.xs + (long long)k * a.xk) * a.E + slice_off;
-      xt[0] = (float)(t_k0 - t_begin); xt[1] = (float)t_mma; xt[2] = (float)t_epi; xt[3] = (float)t_bld;
-    }
-#endif
   }
 }
 
@@ -2165,14 +2129,7 @@ __global__ __launch_bounds__(CSW_NT) void conv_sweep_kernel(SweepArgs a, unsigne
   __syncthreads();
 
   const int nblk = (HW + 15) / 16;
-#ifdef MGRIT_TIMING
-  long long tm_mma = 0, tm_b1 = 0, tm_pass = 0, tm_b2 = 0;
-  const long long tm_begin = __builtin_readcyclecounter();
-#endif
   for (int k = 1; k <= a.nsteps; ++k) {
-#ifdef MGRIT_TIMING
-    const long long tm0 = __builtin_readcyclecounter();
-#endif
     const long long layer = layer_of(k);
     if (k < a.nsteps) load_w(layer_of(k + 1));               // next layer's slices: in flight during this step
     float bo = 0.0f;
@@ -2247,13 +2204,7 @@ __global__ __launch_bounds__(CSW_NT) void conv_sweep_kernel(SweepArgs a, unsigne
       if (blk0 + 24 < nblk) group(blk0, std::true_type());
       else group(blk0, std::false_type());
     }
-#ifdef MGRIT_TIMING
-    const long long tm1 = __builtin_readcyclecounter();
-#endif
     __syncthreads();                                         // every block is done with P and has updated St
-#ifdef MGRIT_TIMING
-    const long long tm2 = __builtin_readcyclecounter();
-#endif
     {
       float* xo = a.X + (a.xb + ci * a.xs + (long long)k * a.xk) * a.E + img_off;
 #pragma unroll
@@ -2276,19 +2227,7 @@ __global__ __launch_bounds__(CSW_NT) void conv_sweep_kernel(SweepArgs a, unsigne
       }
       if (build) store_w();
     }
-#ifdef MGRIT_TIMING
-    const long long tm3 = __builtin_readcyclecounter();
-#endif
     __syncthreads();                                         // next operand and weight slices complete
-#ifdef MGRIT_TIMING
-    // diagnostic build only: phase times in cycles overwrite the first values of the last state of the image
-    const long long tm4 = __builtin_readcyclecounter();
-    tm_mma += tm1 - tm0; tm_b1 += tm2 - tm1; tm_pass += tm3 - tm2; tm_b2 += tm4 - tm3;
-    if (k == a.nsteps && (tid & 63) == 0) {
-      float* xt = a.X + (a.xb + ci * a.xs + (long long)k * a.xk) * a.E + img_off + 8 * wave;
-      xt[0] = (float)(tm0 - tm_begin); xt[1] = (float)tm_mma; xt[2] = (float)tm_b1; xt[3] = (float)tm_pass; xt[4] = (float)tm_b2;
-    }
-#endif
   }
 }
 

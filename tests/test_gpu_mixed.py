@@ -88,7 +88,7 @@ MIXED_CASES = [
         act=I.TANH),
     # d = 2048: the dense launches of the fully connected groups use the tiled kernels, not only the small-launch one
     _mx("mixed_fp32_c32_8x8_N16_m2_L2_P2_d2048", C=32, Himg=8, Wimg=8, B=40, N=16, max_levels=2, fc_period=2, max_iter=1),
-    # at most 32 samples: the fully connected steps take the 16-wavefront k-split kernel (d = 2048 float, 4096 bf16)
+    # at most 32 samples: the fully connected steps take the k-split kernel (skinny launch) (d = 2048 float, 4096 bf16)
     _mx("mixed_fp32_c32_8x8_B20_N8_P2_d2048_deep_ksplit", C=32, Himg=8, Wimg=8, B=20, N=8, max_levels=2, fc_period=2, max_iter=1),
     _mx("mixed_bf16_c64_8x8_B8_N4_P2_d4096_deep_ksplit", dtype=I.BF16, C=64, Himg=8, Wimg=8, B=8, N=4, max_levels=2, fc_period=2,
         max_iter=1, act=I.TANH),

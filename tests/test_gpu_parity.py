@@ -79,11 +79,11 @@ DENSE_CASES = [
     I.reduced(I.cfg5(2), name="dense_bf16_q136_B50_N64_m4", q=136, B=50, N=64, m=4, head_classes=0),
     I.reduced(I.cfg5(2), name="dense_bf16_q256_B130_N256_m16", q=256, B=130, N=256, head_classes=0),
     I.reduced(I.cfg2(1), name="dense_fp32_serial_L1", q=40, B=9, N=13, max_levels=1),
-    # enough groups for the largest tiles (256x256 bf16, 128x128 fp32), ragged against them
+    # enough groups for the largest tiles (128x128, both operand types), ragged against them
     I.reduced(I.cfg5(1), name="dense_bf16_q264_B260_N128_m2_bigtile", q=264, B=260, N=128, m=2, max_levels=2,
               head_classes=0),
     I.reduced(I.cfg2(1), name="dense_fp32_q136_B130_N128_m2_bigtile", q=136, B=130, N=128, m=2, max_levels=2),
-    # at most 32 rows and a long contraction: the 16-wavefront k-split kernel (ragged rows, bias, both operand types)
+    # at most 32 rows and a long contraction: the k-split kernel in its skinny-launch role (ragged rows, bias, both operand types)
     I.reduced(I.cfg2(1), name="dense_fp32_q2048_B20_N8_m2_deep_ksplit", q=2048, B=20, N=8, m=2, max_levels=2, bias_var=0.1),
     I.reduced(I.cfg5(1), name="dense_bf16_q4096_B9_N4_m2_deep_ksplit", q=4096, B=9, N=4, m=2, max_levels=2, head_classes=0,
               bias_var=0.1),
@@ -260,7 +260,7 @@ ADJ_CASES = [
     I.reduced(I.cfg5(2), name="adj_chain_fp32_q256_relu_F_L2", q=256, B=12, N=32, m=4, dtype=I.FP32, act=I.RELU,
               max_levels=2, relax=I.RELAX_F),
     I.reduced(I.cfg5(1), name="adj_fp32_q512_B8_N16_m4", q=512, B=8, N=16, m=4, dtype=I.FP32),
-    # the 16-wavefront k-split kernel with the act' operand and in the act' launch itself
+    # the k-split kernel (skinny launch) with the act' operand and in the act' launch itself
     I.reduced(I.cfg5(1), name="adj_dense_fp32_q2048_B20_N8_m2_deep_ksplit", q=2048, B=20, N=8, m=2, max_levels=2, dtype=I.FP32),
     I.reduced(I.cfg5(1), name="adj_dense_bf16_q4096_B32_N4_m2_deep_ksplit", q=4096, B=32, N=4, m=2, max_levels=2),
     # level sizes that are no multiples of m: the adjoint hierarchy counts from layer N, its trailing F-points end at layer 0
@@ -406,10 +406,12 @@ def test_maximum_layer_count_forward_and_adjoint():
     Lam, dW, db, _, _ = gp.adjoint(Ul, lamN)
     Lo, dWo, dbo, _, _ = oracle_adjoint(wl, data, Ul, lamN)
     eL, eW, eb = rel_l2_per_state(Lam, Lo), rel_l2_per_state(dW, dWo), rel_l2_per_state(db, dbo)
-    # 65535 float32 steps in sequence accumulate rounding of about sqrt(N) * 2^-24 = 1.5e-5 in a state, which
-    # the float64 oracle does not have (the 1e-5 bar is set at the benchmark depths, N <= 1024); a layer's
-    # gradient is a sum of B = 2 terms of either sign, which amplifies that relative error a few times
-    assert eL <= 3e-5 and eW <= 1e-4 and eb <= 1e-4, (eL, eW, eb)
+    # Tolerance at this depth (the 1e-5 bar is stated for the benchmark depths, N <= 1024): N float32 layer steps
+    # in sequence, each rounding the state once (relative 2^-24), leave a random-walk error of sqrt(N) * 2^-24 =
+    # 1.5e-5 in a state that the float64 oracle does not have, so a state may differ by 2e-5; a layer's gradient
+    # is a sum over B = 2 samples of products of two such quantities with either sign, which at most triples
+    # the relative error: 5e-5.
+    assert eL <= 2e-5 and eW <= 5e-5 and eb <= 5e-5, (eL, eW, eb)
 
 
 # ------------------------------------------------------------------ fused F-relaxation sweeps (dense layers)

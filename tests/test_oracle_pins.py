@@ -331,6 +331,67 @@ def test_scalar_brute_force_coarse_equation_and_norm():
     assert abs(got_rms - math.sqrt(sum(r * r for r in Rall) / (N + 1))) < 1e-13
 
 
+def test_in_cycle_rms_history_brute_force():
+    """The residual history with the RMS norm (Alg. 1 step 6; Sec. IV-A reports the L2 norm of R_h) is
+    sqrt(sum of R^2 over the fine C-points / number of summed entries), the number of entries being
+    (N_1 + 1) * batch * width -- written out here with pure-Python loops over every sample and feature,
+    for a two-level and a three-level hierarchy (the count is the fine level's C-points in both), forward
+    and adjoint.  A divisor that counted all N + 1 points, forgot point 0, or forgot the batch or the
+    width fails."""
+    rng = np.random.default_rng(81)
+    N, m, h, B, q = 12, 2, 0.2, 3, 2
+    W = rng.standard_normal((N, q, q))
+    b = rng.standard_normal((N, q)) * 0.5
+    u0 = rng.standard_normal((B, q))
+    x = rng.standard_normal((N + 1, B, q))
+    x[0] = u0
+
+    def phi(n, u):          # one sample: u + h tanh(W_n u + b_n), element by element
+        out = []
+        for o in range(q):
+            z = b[n][o]
+            for i in range(q):
+                z += W[n][o][i] * u[i]
+            out.append(u[o] + h * math.tanh(z))
+        return out
+
+    # F-relaxation by hand, then the C-point rows of f_h - L_h(x)
+    xs = [[list(x[j][r]) for r in range(B)] for j in range(N + 1)]
+    for i in range(N // m):
+        for k in range(1, m):
+            j = i * m + k
+            for r in range(B):
+                xs[j][r] = phi(j - 1, xs[j - 1][r])
+    ssq, entries = 0.0, 0
+    for j in range(0, N + 1, m):
+        for r in range(B):
+            row = [u0[r][o] - xs[0][r][o] for o in range(q)] if j == 0 else \
+                  [p - c for p, c in zip(phi(j - 1, xs[j - 1][r]), xs[j][r])]
+            for v in row:
+                ssq += v * v
+                entries += 1
+    assert entries == 7 * 3 * 2                       # (N/m + 1) C-points x batch x width
+    Uinit = np.array(xs)
+    for levels in (2, 3):                             # 12/6 and 12/6/3: the same fine C-points either way
+        _, hist, _ = O.fas_forward(W, b, u0, h, m, levels, 1, O.RELAX_F, 2, DENSE, TANH, init=2, U_init=Uinit,
+                                   norm_kind=1)
+        assert abs(hist[0] - math.sqrt(ssq / 42.0)) < 1e-13, (levels, hist[0])
+        _, hist_l2, _ = O.fas_forward(W, b, u0, h, m, levels, 1, O.RELAX_F, 2, DENSE, TANH, init=2, U_init=Uinit)
+        assert abs(hist_l2[0] - math.sqrt(ssq)) < 1e-13
+        for a, c in zip(hist, hist_l2):               # every cycle's entry carries the same divisor
+            assert abs(a - c / math.sqrt(42.0)) < 1e-14
+    # adjoint: the same count on the reversed axis (N = 13, m = 3: C-points 13, 10, 7, 4, 1 -> 5 of them)
+    N2, m2 = 13, 3
+    W2 = rng.standard_normal((N2, q, q))
+    b2 = rng.standard_normal((N2, q)) * 0.5
+    U2 = rng.standard_normal((N2 + 1, B, q))
+    lamN = rng.standard_normal((B, q))
+    _, _, _, ha, _ = O.fas_adjoint(W2, b2, U2, lamN, h, m2, 2, 1, O.RELAX_FCF, 2, DENSE, TANH, norm_kind=1)
+    _, _, _, ha2, _ = O.fas_adjoint(W2, b2, U2, lamN, h, m2, 2, 1, O.RELAX_FCF, 2, DENSE, TANH, norm_kind=0)
+    for a, c in zip(ha, ha2):
+        assert abs(a - c / math.sqrt(5 * 3 * 2)) < 1e-14
+
+
 # ---------------------------------------------------------------------------------------
 # Multilevel: converges to serial propagation, the limit the iteration is defined by
 # ---------------------------------------------------------------------------------------
