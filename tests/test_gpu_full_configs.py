@@ -223,3 +223,61 @@ def test_cfg5_full_adjoint_elementwise(cfg5_data):
     eL, eW, eb = rel_l2_per_state(Lam, Lo), rel_l2_per_state(dW, dWo), rel_l2_per_state(db, dbo)
     print(f"cfg5 adjoint: Lam {eL:.3e}  dW {eW:.3e}  db {eb:.3e}  hist {hist} vs {hist_o}", flush=True)
     assert eL <= 2e-2 and eW <= 2e-2 and eb <= 2e-2, (eL, eW, eb)
+
+
+# ------------------------------------------------------------------------------------------------
+# The two large workloads through their WHOLE hierarchy against the full oracle (Alg. 1 steps 1-6 on
+# every level: relaxation, residual, injection, coarse right-hand side, recursive / serial coarse
+# solve, correction), at the workload's own N, m, level count, relaxation and operand type, two
+# cycles, forward and adjoint with the parameter gradient.  Only the batch is cut so that the
+# float64 oracle finishes in about a minute; a layer step treats every sample alike, so the level
+# schedule, index maps and kernels at the fine level are those of the full batch.
+# ------------------------------------------------------------------------------------------------
+def _full_hierarchy_case(wl, lam_from_head, data=None):
+    data = I.generate(wl) if data is None else data
+    gp = GpuProblem(wl, data)
+    sizes, _ = gp.M.mgrit_level_map(gp.p)
+    _say(f"{wl.name}: levels {sizes}, batch {wl.B}, {wl.max_iter} cycles, forward")
+    _, U, hist, it = gp.forward()
+    Uo, hist_o, it_o = oracle_forward(wl, data)
+    assert it == it_o == wl.max_iter
+    err = rel_l2_per_state(U, Uo)
+    err_inc = rel_l2_per_state(U[1:] - U[0], Uo[1:] - Uo[0])
+    print(f"{wl.name} forward: per-state rel L2 {err:.3e}, increment rel L2 {err_inc:.3e}, "
+          f"hist {hist} vs oracle {hist_o}", flush=True)
+    assert err <= TOL[wl.dtype], err
+    assert err_inc <= 1e-1, err_inc
+    for a, b in zip(hist, hist_o):
+        assert abs(a - b) <= 5e-2 * b, (hist, hist_o)
+    # adjoint about bf16-representable states (both sides then take every act' decision from the same
+    # operand values, the kernel's), two cycles, and the parameter gradient of every layer
+    _say(f"{wl.name}: adjoint + gradient")
+    Ulin = I.round_to_bf16(Uo.astype(np.float32))
+    del Uo, U
+    if lam_from_head:
+        lamN = I.terminal_adjoint(wl, data, Ulin[-1])
+    else:
+        lamN = (np.random.default_rng(23).standard_normal(wl.state_shape) / wl.B).astype(np.float32)
+    Lam, dW, db, hist_a, it_a = gp.adjoint(Ulin, lamN)
+    Lo, dWo, dbo, hist_ao, _ = O.fas_adjoint(data["W"], data["b"], Ulin, lamN, wl.h, wl.m, wl.max_levels,
+                                              wl.min_coarse, wl.relax, wl.max_iter, wl.layer, wl.act)
+    eL, eW, eb = rel_l2_per_state(Lam, Lo), rel_l2_per_state(dW, dWo), rel_l2_per_state(db, dbo)
+    print(f"{wl.name} adjoint: Lam {eL:.3e}  dW {eW:.3e}  db {eb:.3e}  hist {hist_a} vs {hist_ao}", flush=True)
+    assert it_a == wl.max_iter
+    assert eL <= TOL[wl.dtype] and eW <= TOL[wl.dtype] and eb <= TOL[wl.dtype], (eL, eW, eb)
+    for a, b in zip(hist_a, hist_ao):
+        assert abs(a - b) <= 5e-2 * b, (hist_a, hist_ao)
+
+
+def test_cfg4_whole_hierarchy_two_cycles_against_the_oracle():
+    """512 / 64 / 8 layers, m = 8, FCF, bf16 operands, 64 channels on 32x32 images; batch 2 of 32."""
+    _full_hierarchy_case(I.reduced(I.cfg4(2), name="cfg4_hierarchy_B2", B=2), lam_from_head=False)
+
+
+def test_cfg5_whole_hierarchy_two_cycles_against_the_oracle(cfg5_data):
+    """1024 / 64 / 4 layers, m = 16, FCF, bf16 operands, width 1024, softmax head; the first 32 of the 256 samples
+    (parameters and head are those of the full workload, drawn once for this module)."""
+    _, full = cfg5_data
+    data = {"W": full["W"], "b": full["b"], "u0": np.ascontiguousarray(full["u0"][:32]), "W_o": full["W_o"],
+            "labels": full["labels"][:32]}
+    _full_hierarchy_case(I.reduced(I.cfg5(2), name="cfg5_hierarchy_B32", B=32), lam_from_head=True, data=data)
