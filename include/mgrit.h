@@ -134,6 +134,25 @@ int32_t mgrit_fas_forward(const mgrit_problem_t* p, const void* W, const float* 
                           float* U, double* resnorm_hist, int32_t* iters_done,
                           void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* The forward solve for callers that cannot allocate device memory -- code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc: mgrit_fas_forward without the workspace argument.  Its
+ * workspace is a fixed array of MGRIT_STATIC_SCRATCH_BYTES in device memory that belongs to the library; every
+ * GPU the library runs on holds one copy until the process ends.  The call itself allocates and frees nothing,
+ * on the device or through any allocating runtime call; inputs and outputs are the caller's as above, results are
+ * those of mgrit_fas_forward (same kernels, same schedule).
+ *   - MGRIT_ERR_WORKSPACE if mgrit_workspace_bytes(p) exceeds MGRIT_STATIC_SCRATCH_BYTES (the plain dense
+ *     q = 256, N = 256, B = 128 workload needs 32 MB; the two large benchmark workloads do not fit).
+ *   - The first call on a device looks up the address of that device's copy of the array; make it outside
+ *     a stream capture (the same rule as for the LDS attribute above).  With tol <= 0 and both host outputs
+ *     NULL the call is kernel launches only.
+ *   - All calls on one GPU share that GPU's array, whatever their streams: calls that overlap in time on one
+ *     GPU race on it.  Nothing in it has to be cleared between calls -- every part is written before it is
+ *     read -- so a call may follow one with a different problem.
+ * Errors otherwise as mgrit_fas_forward; MGRIT_ERR_UNSUPPORTED for a device index above 63. */
+enum { MGRIT_STATIC_SCRATCH_BYTES = 64 * 1024 * 1024 };
+int32_t mgrit_fas_forward_static(const mgrit_problem_t* p, const void* W, const float* b, const float* u0,
+                                 float* U, double* resnorm_hist, int32_t* iters_done, void* hip_stream);
+
 /* Adjoint (backward) solve by the same cycle on the reversed layer axis.  The paper states
  * that the multigrid removes the serial backward propagation as well (Sec. III-C) and prints
  * no equations; the system solved is the exact reverse-mode derivative of Eq. (1):

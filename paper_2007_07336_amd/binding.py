@@ -63,6 +63,8 @@ def lib() -> ctypes.CDLL:
         L.mgrit_adjoint_workspace_bytes.restype = ctypes.c_size_t
         L.mgrit_fas_forward.argtypes = [P, vp, vp, vp, vp, dp, i32p, vp, ctypes.c_size_t, vp]
         L.mgrit_fas_forward.restype = ctypes.c_int32
+        L.mgrit_fas_forward_static.argtypes = [P, vp, vp, vp, vp, dp, i32p, vp]
+        L.mgrit_fas_forward_static.restype = ctypes.c_int32
         L.mgrit_fas_adjoint.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, dp, i32p, vp, ctypes.c_size_t, vp]
         L.mgrit_fas_adjoint.restype = ctypes.c_int32
         L.mgrit_residual_norm.argtypes = [P, vp, vp, vp, vp, dp, vp, ctypes.c_size_t, vp]
@@ -154,6 +156,20 @@ def mgrit_fas_forward(p: mgrit_problem_t, W, b, u0, U, workspace, *, want_hist=T
                                  workspace.numel() * workspace.element_size(), _stream(stream))
     if check and rc != MGRIT_OK:
         raise MgritError(rc, "mgrit_fas_forward")
+    return rc, ([hist[i] for i in range(iters.value)] if want_hist else None), iters.value
+
+
+MGRIT_STATIC_SCRATCH_BYTES = 64 * 1024 * 1024
+
+
+def mgrit_fas_forward_static(p: mgrit_problem_t, W, b, u0, U, *, want_hist=True, stream=None, check=True):
+    """mgrit_fas_forward on the library's own fixed workspace (no workspace argument, nothing allocated)."""
+    hist = (ctypes.c_double * max(p.max_iter, 1))() if want_hist else None
+    iters = ctypes.c_int32(0)
+    rc = lib().mgrit_fas_forward_static(ctypes.byref(p), _ptr(W), _ptr(b), _ptr(u0), _ptr(U), hist,
+                                        ctypes.byref(iters) if want_hist else None, _stream(stream))
+    if check and rc != MGRIT_OK:
+        raise MgritError(rc, "mgrit_fas_forward_static")
     return rc, ([hist[i] for i in range(iters.value)] if want_hist else None), iters.value
 
 

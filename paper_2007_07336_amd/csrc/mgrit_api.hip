@@ -565,6 +565,12 @@ int residual_norm_impl(const mgrit_problem_t* p, const mgrit_fc_layers_t* fc, co
   return isfinite(v) ? MGRIT_OK : MGRIT_ERR_NONFINITE;
 }
 
+// Workspace of the entry point that allocates nothing: a fixed array in device memory that every GPU the
+// library runs on holds until the process ends.  In host code its name is only a handle; the address of a
+// device's copy comes from hipGetSymbolAddress, once per device, and only that address is handed to kernels.
+__device__ __align__(256) unsigned char scratch[MGRIT_STATIC_SCRATCH_BYTES];
+void* g_scratch_ptr[64] = {};
+
 }  // namespace
 
 extern "C" {
@@ -614,6 +620,26 @@ int32_t mgrit_fas_adjoint(const mgrit_problem_t* p, const void* W, const float* 
 int32_t mgrit_residual_norm(const mgrit_problem_t* p, const void* W, const float* b, const float* u0, const float* U,
                             double* norm_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
   return residual_norm_impl(p, nullptr, W, b, u0, U, norm_out, workspace, workspace_bytes, hip_stream);
+}
+
+int32_t mgrit_fas_forward_static(const mgrit_problem_t* p, const void* W, const float* b, const float* u0, float* U,
+                                 double* resnorm_hist, int32_t* iters_done, void* hip_stream) {
+  Plan pl;
+  if (!p) return MGRIT_ERR_POINTER;
+  const int rc = make_plan(p, &pl);
+  if (rc != MGRIT_OK) return rc;
+  if (pl.bytes_fwd > (size_t)MGRIT_STATIC_SCRATCH_BYTES) return MGRIT_ERR_WORKSPACE;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return MGRIT_ERR_HIP;
+  if (dev < 0 || dev >= 64) return MGRIT_ERR_UNSUPPORTED;
+  if (!g_scratch_ptr[dev]) {                     // first call on this device: look up its copy of the array
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return MGRIT_ERR_HIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  // nothing in the workspace has to start at zero: every array in it is written before it is read
+  return forward_impl(p, nullptr, W, b, u0, U, resnorm_hist, iters_done, g_scratch_ptr[dev],
+                      (size_t)MGRIT_STATIC_SCRATCH_BYTES, hip_stream);
 }
 
 size_t mgrit_workspace_bytes_mixed(const mgrit_problem_t* p, int32_t fc_period) {
