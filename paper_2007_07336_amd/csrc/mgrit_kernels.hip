@@ -1414,6 +1414,148 @@ __global__ __launch_bounds__(NT) void dense_grad_kernel(GradArgs a) {
     }
   }
 }
+// The same contraction on a 256x256 output tile for wide layers (q >= 512): eight wavefronts, 2 (rows of dW) x 4
+// (columns), each owning 128 x 64.  A 128x128 tile re-reads every operand panel q / 128 times from L2 -- 20 MB per
+// layer at q = 1024, five times the 4 MB of dW that go out -- and that traffic, not HBM, set its time; the wide tile
+// halves it.  The bias gradient db[o] = hs * sum over the batch of G[.][o] rides along: the column tiles with
+// n0 == 0 sum the float G values they stage anyway (per thread over its rows, then over the eight row lanes in a
+// fixed order), which spares the separate pass over Dm and Lam.
+template <typename OT>
+__global__ __launch_bounds__(512) void dense_grad_wide_kernel(GradArgs a) {
+  constexpr int BKR = 32, ST = BKR + Op<OT>::PAD, KSTEP = Op<OT>::KSTEP;
+  constexpr int BM = 256, BN = 256, TM = 4, TN = 2, NTH = 512;
+  constexpr int SW = 64 + 4;                          // staging row stride (floats) of a wavefront's 32 x 64 block row
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];   // operand tiles, later the output staging
+  OT* As = reinterpret_cast<OT*>(lds_raw);            // [BM][ST]  G^T: row = output feature o, k = batch row
+  OT* Bs = As + BM * ST;                              // [BN][ST]  U^T: row = input feature i
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), g = lane >> 5, c = lane & 31;
+  const int q = a.Nf;
+  const int tiles_n = (q + BN - 1) / BN;
+  const int L = logical_block();
+  const int gi = L / a.tiles, tile = L % a.tiles;
+  const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
+  const float* Up = a.U + (a.um.base + gi * a.um.stride) * a.E;
+  const float* Lp = a.Lam + (a.lm.base + gi * a.lm.stride) * a.E;
+  const OT* Dp = reinterpret_cast<const OT*>(a.Dm) + (a.dm.base + gi * a.dm.stride) * a.E;
+  float* dWp = a.dW ? a.dW + (long long)gi * a.wsize : nullptr;
+  typedef typename DRaw<OT>::type DR;
+  const bool want_db = a.db != nullptr && n0 == 0;
+
+  const int rb = tid & 7, cb = tid >> 3;             // 4 batch rows x 4 columns per thread, of G and of U
+  const bool aok = m0 + 4 * cb < q, bok = n0 + 4 * cb < q;      // q % 4 == 0: a float4 is in or out as a whole
+  float4 lv[4], uv[4];
+  DR dv[4];
+  unsigned rmask = 0;
+  float bsum[4] = {0.f, 0.f, 0.f, 0.f};
+  auto load_slab = [&](int r0) {
+    rmask = 0;
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+      const int row = r0 + 4 * rb + rr;
+      const bool rok = row < a.M;
+      rmask |= rok ? (1u << rr) : 0u;
+      const unsigned offa = (rok && aok) ? (unsigned)(row * q + m0 + 4 * cb) : 0u;
+      const unsigned offb = (rok && bok) ? (unsigned)(row * q + n0 + 4 * cb) : 0u;
+      dv[rr] = ld_d4(Dp + offa);
+      lv[rr] = *reinterpret_cast<const float4*>(Lp + offa);
+      uv[rr] = *reinterpret_cast<const float4*>(Up + offb);
+    }
+  };
+  auto store_slab = [&]() {
+    float gk[4][4], uk[4][4];                         // [column][k]
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+      const bool rok = (rmask >> rr) & 1u;
+      const float ga = (rok && aok) ? 1.0f : 0.0f, ub = (rok && bok) ? 1.0f : 0.0f;
+      const float4 dd = d4_to_f4(dv[rr]);
+      gk[0][rr] = ga * dd.x * lv[rr].x; gk[1][rr] = ga * dd.y * lv[rr].y;
+      gk[2][rr] = ga * dd.z * lv[rr].z; gk[3][rr] = ga * dd.w * lv[rr].w;
+      uk[0][rr] = ub * uv[rr].x; uk[1][rr] = ub * uv[rr].y; uk[2][rr] = ub * uv[rr].z; uk[3][rr] = ub * uv[rr].w;
+    }
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc) {
+      bsum[cc] += (gk[cc][0] + gk[cc][1]) + (gk[cc][2] + gk[cc][3]);
+      cvt_store4(&As[(4 * cb + cc) * ST + 4 * rb], make_float4(gk[cc][0], gk[cc][1], gk[cc][2], gk[cc][3]));
+      cvt_store4(&Bs[(4 * cb + cc) * ST + 4 * rb], make_float4(uk[cc][0], uk[cc][1], uk[cc][2], uk[cc][3]));
+    }
+  };
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) acc[i][j] = zero16();
+  const int wm0 = (wave >> 2) * 128, wn0 = (wave & 3) * 64;
+  load_slab(0);
+  for (int r0 = 0; r0 < a.M; r0 += BKR) {
+    __syncthreads();
+    store_slab();
+    __syncthreads();
+    if (r0 + BKR < a.M) load_slab(r0 + BKR);
+#pragma unroll
+    for (int ks = 0; ks < BKR; ks += KSTEP) {
+      const OT* ap[TM];
+      const OT* bp[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) ap[i] = &As[(wm0 + i * 32 + c) * ST + ks];
+#pragma unroll
+      for (int j = 0; j < TN; ++j) bp[j] = &Bs[(wn0 + j * 32 + c) * ST + ks];
+      mma_step<TM, TN>(ap, bp, acc, g);
+    }
+  }
+  __syncthreads();                                    // every wavefront is done with the operand tiles
+  if (want_db) {
+    // the eight row lanes rb of a column block hold partial sums over disjoint batch rows: add them in lane order
+    float4* part = reinterpret_cast<float4*>(lds_raw);          // [64 column blocks][8 row lanes]
+    part[cb * 8 + rb] = make_float4(bsum[0], bsum[1], bsum[2], bsum[3]);
+    __syncthreads();
+    if (rb == 0 && aok) {
+      float4 t = part[cb * 8];
+#pragma unroll
+      for (int j = 1; j < 8; ++j) { const float4 v = part[cb * 8 + j]; t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w; }
+      t.x *= a.hs; t.y *= a.hs; t.z *= a.hs; t.w *= a.hs;
+      *reinterpret_cast<float4*>(a.db + (long long)gi * q + m0 + 4 * cb) = t;
+    }
+    __syncthreads();
+  }
+  if (!dWp) return;
+  // output through LDS so that a lane stores a float4 and 16 lanes a whole 256-byte row segment
+  float* stage = reinterpret_cast<float*>(lds_raw) + wave * 32 * SW;
+  const int lrow = lane >> 4, colq = (lane & 15) * 4;
+  const int col = n0 + wn0 + colq;
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) stage[(8 * (r >> 2) + 4 * g + (r & 3)) * SW + j * 32 + c] = acc[i][j][r];
+#pragma unroll
+    for (int h = 0; h < 8; ++h) {
+      const int rl = 4 * h + lrow;
+      const int row = m0 + wm0 + i * 32 + rl;
+      float4 z = *reinterpret_cast<const float4*>(&stage[rl * SW + colq]);
+      z.x *= a.hs; z.y *= a.hs; z.z *= a.hs; z.w *= a.hs;
+      if (row < q && col < q) *reinterpret_cast<float4*>(dWp + (long long)row * q + col) = z;
+    }
+  }
+}
+template <typename OT> constexpr size_t dense_grad_wide_smem() {
+  constexpr size_t tiles = (size_t)512 * (32 + Op<OT>::PAD) * sizeof(OT), stage = (size_t)8 * 32 * 68 * sizeof(float);
+  return tiles > stage ? tiles : stage;
+}
+template <typename OT>
+static hipError_t launch_dense_grad_wide(const GradArgs& a, unsigned blocks, hipStream_t s) {
+  constexpr size_t smem = dense_grad_wide_smem<OT>();
+  static LdsOptIn opt;
+  if (opt.need(smem)) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(dense_grad_wide_kernel<OT>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL((dense_grad_wide_kernel<OT>), dim3(blocks), dim3(512), smem, s, a);
+  return hipGetLastError();
+}
+
 // Parameter gradient (3x3 conv): dK[n][o][dy][dx][i] = hs * sum over pixels of G[b,y,x,o] *
 // U[b,y+dy-1,x+dx-1,i] (zero outside the image), G = Dm .* Lam.  One workgroup per (layer, tap):
 // a C x C output tile (C <= 64), contraction over all B*H*W pixels in slabs of 32, operands
@@ -2254,11 +2396,27 @@ hipError_t launch_conv_sweep(const SweepArgs& a, hipStream_t s) {
   return e;
 }
 
+// MGRIT_GRAD_NARROW=1 in the environment keeps wide dense layers on the 128x128 gradient kernel with its separate
+// bias pass (diagnostic; the tests compare both)
+static bool dense_grad_narrow_forced() {
+  const char* e = getenv("MGRIT_GRAD_NARROW");
+  return e && e[0] == '1';
+}
 hipError_t launch_grad(const GradArgs& a_in, int layer_kind, int dtype, int groups, hipStream_t s) {
   if (groups <= 0) return hipSuccess;
   GradArgs a = a_in;
   trace_before(s);
-  if (layer_kind == 0) {
+  bool db_done = false;
+  if (layer_kind == 0 && a.Nf >= 512 && !dense_grad_narrow_forced()) {
+    // wide layers: 256x256 tiles, the bias gradient in the same launch
+    a.tiles = ((a.Nf + 255) / 256) * ((a.Nf + 255) / 256);
+    if (a.dW || a.db) {
+      const unsigned blocks = (unsigned)a.tiles * (unsigned)groups;
+      const hipError_t e = dtype == 0 ? launch_dense_grad_wide<float>(a, blocks, s) : launch_dense_grad_wide<__bf16>(a, blocks, s);
+      if (e != hipSuccess) { trace_after(s, TRACE_GRAD, groups, 0.0); return e; }
+    }
+    db_done = true;
+  } else if (layer_kind == 0) {
     a.tiles = ((a.Nf + 127) / 128) * ((a.Nf + 127) / 128);
     if (a.dW) {
       dim3 grid((unsigned)a.tiles * (unsigned)groups);
@@ -2300,7 +2458,7 @@ hipError_t launch_grad(const GradArgs& a_in, int layer_kind, int dtype, int grou
       }
     }
   }
-  if (a.db && layer_kind == 0) launch_bias_grad(a, dtype, groups, s);
+  if (a.db && layer_kind == 0 && !db_done) launch_bias_grad(a, dtype, groups, s);
   const hipError_t e = hipGetLastError();
   // algorithmic bytes of a layer's gradient: U, Lam and the act' factors in, dW and db out
   const double ges = dtype == 0 ? 4.0 : 2.0;

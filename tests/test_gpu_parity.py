@@ -414,6 +414,47 @@ def test_maximum_layer_count_forward_and_adjoint():
     assert eL <= 2e-5 and eW <= 5e-5 and eb <= 5e-5, (eL, eW, eb)
 
 
+# ------------------------------------------------------------------ parameter gradient of wide dense layers
+# Layers of width 512 and more take the 256x256 gradient kernel, which also forms the bias gradient;
+# MGRIT_GRAD_NARROW=1 keeps them on the 128x128 kernel with its separate bias pass.  Widths ragged against the
+# 256-wide tile (520 = 2 x 256 + 8, 776), batches ragged against the 32-row slabs (50, 70), both operand types.
+GRAD_WIDE_CASES = [
+    I.reduced(I.cfg5(1), name="gradw_fp32_q520_B50_N8_m2", q=520, B=50, N=8, m=2, max_levels=2, dtype=I.FP32),
+    I.reduced(I.cfg5(1), name="gradw_bf16_q776_B70_N8_m4", q=776, B=70, N=8, m=4, max_levels=2),
+    I.reduced(I.cfg5(1), name="gradw_bf16_q1024_B256_N16_m4", q=1024, B=256, N=16, m=4, max_levels=2),
+]
+
+
+@pytest.mark.parametrize("wide", [True, False], ids=["tile256", "tile128"])
+@pytest.mark.parametrize("wl", GRAD_WIDE_CASES, ids=lambda w: w.name)
+def test_dense_parameter_gradient_wide_layers(wl, wide, monkeypatch):
+    if not wide:
+        monkeypatch.setenv("MGRIT_GRAD_NARROW", "1")
+    _announce(f"{wl.name} wide={wide}")
+    data = I.generate(wl)
+    Uo, _, _ = oracle_forward(wl, data)
+    U = Uo.astype(np.float32)
+    lamN = I.terminal_adjoint(wl, data, U[-1])
+    gp = GpuProblem(wl, data)
+    Lam, dW, db, hist, it = gp.adjoint(U, lamN)
+    Lo, dWo, dbo, hist_o, it_o = oracle_adjoint(wl, data, U, lamN)
+    tol = TOL[wl.dtype]
+    eL, eW, eb = rel_l2_per_state(Lam, Lo), rel_l2_per_state(dW, dWo), rel_l2_per_state(db, dbo)
+    print(f"{wl.name}: Lam {eL:.3e} dW {eW:.3e} db {eb:.3e}", flush=True)
+    assert eL <= tol and eW <= tol and eb <= tol, (eL, eW, eb)
+    # the bias gradient alone (dW not requested) and the weight gradient alone
+    import torch
+    import paper_2007_07336_amd as M
+    Ud, lam = torch.from_numpy(U).cuda(), torch.from_numpy(lamN).cuda()
+    ws = torch.empty(M.mgrit_adjoint_workspace_bytes(gp.p), dtype=torch.uint8, device="cuda")
+    Lam2, db2 = torch.zeros_like(Ud), torch.full_like(gp.b, float("nan"))
+    M.mgrit_fas_adjoint(gp.p, gp.W, gp.b, Ud, lam, Lam2, None, db2, ws)
+    assert np.array_equal(db2.cpu().numpy(), db)
+    dW2 = torch.full(gp.W.shape, float("nan"), dtype=torch.float32, device="cuda")
+    M.mgrit_fas_adjoint(gp.p, gp.W, gp.b, Ud, lam, Lam2, dW2, None, ws)
+    assert np.array_equal(dW2.cpu().numpy(), dW)
+
+
 # ------------------------------------------------------------------ fused F-relaxation sweeps (dense layers)
 # Shapes on which the library fuses the steps of an F-relaxation sweep into one launch (width 128 or 256;
 # at least 128 (interval, 32-row slice) workgroups; m >= 3); each also runs with the fused
