@@ -1938,18 +1938,21 @@ static hipError_t launch_conv_grad(const GradArgs& a, unsigned blocks, size_t sm
 // slabs of BK values of k (whole-line loads into a register ring of PF slabs, running ahead
 // across layer boundaries; while one slab is multiplied the next is written to the other buffer).  Every
 // wavefront loads, stages and multiplies its own weight rows only, so the slab loop has no workgroup barrier.  The raw sums of a step go through the slab buffer that has just become free, so that
-// the update -- new state to LDS and to global memory, next operand -- is one float4 pass over whole rows.  Wavefront w owns the column blocks w*NBW .. w*NBW + NBW - 1 of 32 columns;
-// q = 128 * NBW.
+// the update -- new state to LDS and to global memory, next operand -- is one float4 pass over whole rows.  Wavefront w of NWV owns the column blocks w*NBW .. w*NBW + NBW - 1 of 32 columns;
+// q = 32 * NBW * NWV.  Width 256 runs with eight wavefronts of one column block each: two per SIMD, so that one
+// wavefront's fragment reads and float4 passes hide behind the other's matrix instructions (four wavefronts of two
+// blocks left the matrix cores idle half of the time).
 // ------------------------------------------------------------------------------------------
 constexpr int SWEEP_R = 32;
 template <typename WT> struct SweepOp;
 template <> struct SweepOp<float>  { static constexpr int BK = 32; };
 template <> struct SweepOp<__bf16> { static constexpr int BK = 64; };
 
-template <typename WT, int NBW, int PF>
-__global__ __launch_bounds__(NT) void dense_sweep_kernel(SweepArgs a) {
+template <typename WT, int NBW, int PF, int NWV>
+__global__ __launch_bounds__(64 * NWV) void dense_sweep_kernel(SweepArgs a) {
+  constexpr int NT = 64 * NWV;                  // shadows the file-wide 256: NWV wavefronts
   constexpr int R = SWEEP_R, BK = SweepOp<WT>::BK, VEC = Op<WT>::VEC, KSTEP = Op<WT>::KSTEP, PAD = Op<WT>::PAD;
-  constexpr int Q = 128 * NBW, Q4 = Q / 4;
+  constexpr int Q = 32 * NBW * NWV, Q4 = Q / 4;
   constexpr int AST = Q + PAD, ST = BK + PAD;
   constexpr int PPR = BK / VEC;                 // 16-byte pieces per weight row and slab (one 128-byte line)
   constexpr int WROWS = 32 * NBW;               // weight rows (output columns) of a wavefront
@@ -2126,35 +2129,42 @@ bool sweep_supported(int q, int dtype) {
 }
 int sweep_blocks(int M, int nchains) { return ((M + SWEEP_R - 1) / SWEEP_R) * nchains; }
 
-template <typename WT, int NBW>
+template <typename WT, int NBW, int NWV>
 static hipError_t launch_sweep_t(const SweepArgs& a, unsigned blocks, size_t smem, hipStream_t s) {
   // weight slabs in flight in registers: as many as a layer has, at most 4 (eight measured no faster and
   // take 256 registers of a lane)
-  constexpr int NSLABS = 128 * NBW / SweepOp<WT>::BK;
+  constexpr int NSLABS = 32 * NBW * NWV / SweepOp<WT>::BK;
   constexpr int PF = NSLABS < 4 ? NSLABS : 4;
   static LdsOptIn opt;
   if (opt.need(smem)) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(dense_sweep_kernel<WT, NBW, PF>),
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(dense_sweep_kernel<WT, NBW, PF, NWV>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL((dense_sweep_kernel<WT, NBW, PF>), dim3(blocks), dim3(NT), smem, s, a);
+  hipLaunchKernelGGL((dense_sweep_kernel<WT, NBW, PF, NWV>), dim3(blocks), dim3(64 * NWV), smem, s, a);
   return hipGetLastError();
+}
+// MGRIT_SWEEP_WAVES=4 in the environment runs width 256 with four wavefronts of two column blocks (diagnostic)
+static bool sweep_four_waves() {
+  const char* e = getenv("MGRIT_SWEEP_WAVES");
+  return e && e[0] == '4';
 }
 hipError_t launch_sweep(const SweepArgs& a, int dtype, hipStream_t s) {
   if (a.nchains <= 0 || a.nsteps <= 0) return hipSuccess;
   if (!sweep_supported(a.q, dtype) || a.M < 1) return hipErrorInvalidValue;
   const size_t smem = sweep_smem_bytes(a.q, dtype);
   const unsigned blocks = (unsigned)sweep_blocks(a.M, a.nchains);
-  const int nbw = a.q / 128;
+  const bool wide = a.q == 256, w4 = sweep_four_waves();
   trace_before(s);
   hipError_t e = hipErrorInvalidValue;
   if (dtype == 0) {
-    if (nbw == 1) e = launch_sweep_t<float, 1>(a, blocks, smem, s);
-    else if (nbw == 2) e = launch_sweep_t<float, 2>(a, blocks, smem, s);
+    if (!wide) e = launch_sweep_t<float, 1, 4>(a, blocks, smem, s);
+    else if (w4) e = launch_sweep_t<float, 2, 4>(a, blocks, smem, s);
+    else e = launch_sweep_t<float, 1, 8>(a, blocks, smem, s);
   } else {
-    if (nbw == 1) e = launch_sweep_t<__bf16, 1>(a, blocks, smem, s);
-    else if (nbw == 2) e = launch_sweep_t<__bf16, 2>(a, blocks, smem, s);
+    if (!wide) e = launch_sweep_t<__bf16, 1, 4>(a, blocks, smem, s);
+    else if (w4) e = launch_sweep_t<__bf16, 2, 4>(a, blocks, smem, s);
+    else e = launch_sweep_t<__bf16, 1, 8>(a, blocks, smem, s);
   }
   // algorithmic bytes per layer step: weights and bias, the act' factor, the right-hand side, the state out
   // (the state in is read once per chain)
