@@ -184,7 +184,9 @@ struct Solver {
     a.M = pl.M; a.Nf = pl.Nf; a.K = pl.K; a.Himg = p->Himg; a.Wimg = p->Wimg; a.TH = pl.TH;
     a.E = pl.E; a.wsize = pl.wsize;
     a.dbf16 = p->dtype == MGRIT_BF16 ? 1 : 0;
-    a.wstream = (double)p->N * (double)pl.wsize * (double)pl.esize > 128.0 * 1024.0 * 1024.0 ? 1 : 0;
+    // weights that a level touches: above 128 MB they are streamed past the caches, else later sweeps of the
+    // same cycle find them in the last-level cache (a coarse level re-reads its few layers several times per cycle)
+    a.wstream = (double)pl.Nl[l] * (double)pl.wsize * (double)pl.esize > 128.0 * 1024.0 * 1024.0 ? 1 : 0;
     return a;
   }
   // Groups of a launch whose layer a.wm(gi) is fully connected: gi = g0 + per * j, j < cnt.  The layer index is

@@ -185,3 +185,31 @@ def test_inputs_are_reproducible_and_bf16_exact():
     import torch
     ref = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
     assert np.array_equal(I.round_to_bf16(x), ref)
+
+
+def test_static_workspace_entry_point_checks_size_and_problem_before_touching_the_gpu():
+    """mgrit_fas_forward_static refuses a problem whose workspace exceeds the library's fixed array, and an invalid
+    problem, from host logic alone (no GPU call is made before these checks)."""
+    big = M.make_problem(N=512, h=1 / 512, m=8, max_levels=3, relax=1, max_iter=1, layer=1, act=1, dtype=1, B=32,
+                         C=64, Himg=32, Wimg=32)
+    assert M.mgrit_workspace_bytes(big) > M.MGRIT_STATIC_SCRATCH_BYTES
+    fake = ctypes.c_void_p(256)
+    L = M.lib()
+    assert L.mgrit_fas_forward_static(ctypes.byref(big), fake, fake, fake, fake, None, None, None) == Bd.MGRIT_ERR_WORKSPACE
+    bad = _problem(m=1)
+    assert L.mgrit_fas_forward_static(ctypes.byref(bad), fake, fake, fake, fake, None, None, None) == Bd.MGRIT_ERR_PROBLEM
+    assert L.mgrit_fas_forward_static(None, fake, fake, fake, fake, None, None, None) == Bd.MGRIT_ERR_POINTER
+    hdr = open(os.path.join(ROOT, "include", "mgrit.h")).read()
+    assert "MGRIT_STATIC_SCRATCH_BYTES = 64 * 1024 * 1024" in hdr and M.MGRIT_STATIC_SCRATCH_BYTES == 64 * 1024 * 1024
+
+
+def test_bench_reads_measured_traffic_from_the_profile_tables():
+    import bench
+    v = bench.measured_traffic_bytes("cfg2", "dense_sweep_kernel<float>")
+    assert v is not None and 5e7 < v < 2e8                      # fetch + write of one 64-interval sweep, bytes
+    assert bench.measured_traffic_bytes("no_such_workload", "dense_sweep_kernel<float>") is None
+    with pytest.raises(RuntimeError):                           # a table that does not list the kernel is stale
+        bench.measured_traffic_bytes("cfg2", "conv_sweep_kernel")
+    for cls in Bd.TRACE_CLASSES:                                # every traced step-kernel class has a row pattern
+        if cls != "dense_grad_kernel":
+            assert cls in bench.PROFILE_ROW, cls
