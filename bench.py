@@ -57,15 +57,17 @@ def measured_traffic_bytes(workload, kernel_class):
     if not os.path.exists(path):
         return None
     pat = re.compile(r"^\|\s*" + PROFILE_ROW[kernel_class])
-    got = {}
+    tot, cnt = {}, {}
     for line in open(path):
-        if pat.match(line):
+        if pat.match(line):          # several instances of one class (e.g. streaming and plain weight loads): weighted mean
             cells = [c.strip() for c in line.strip().strip("|").split("|")]
-            got[cells[1]] = float(cells[-1]) * 1e6
-    if set(got) != {"FETCH_SIZE", "WRITE_SIZE"}:
+            n = float(cells[2])
+            tot[cells[1]] = tot.get(cells[1], 0.0) + n * float(cells[-1]) * 1e6
+            cnt[cells[1]] = cnt.get(cells[1], 0.0) + n
+    if set(tot) != {"FETCH_SIZE", "WRITE_SIZE"}:
         raise RuntimeError("%s has no FETCH_SIZE / WRITE_SIZE rows for %s: re-run the counter passes after a kernel "
                            "change (profiles/README.md)" % (path, kernel_class))
-    return got["FETCH_SIZE"] + got["WRITE_SIZE"]
+    return tot["FETCH_SIZE"] / cnt["FETCH_SIZE"] + tot["WRITE_SIZE"] / cnt["WRITE_SIZE"]
 
 
 def layer_steps_per_solve(sizes, m, relax, iters):
