@@ -1652,9 +1652,13 @@ __global__ __launch_bounds__(NT) void conv_grad_tap_kernel(GradArgs a) {
 // LDS is cleared once; slots that are never written (row padding, the column left of x = 0 in the
 // dx = -1 copy, ...) stay zero, rows outside the image are written as zeros every slab.
 // With few layers the slabs of a layer are split over `gchunks` workgroups that write partial sums.
-template <typename OT, int TM, int TN>
+// N16 (float, at most 16 channels): 16x16x4 blocks, so the output-channel side carries no padding rows (a 32-row
+// block would be half empty at 16 channels, and this kernel is bound by the matrix cores); wavefront w then owns the
+// 16-column blocks w, w+4, ..
+template <typename OT, int TM, int TN, bool N16 = false>
 __global__ __launch_bounds__(NT) void conv_grad_kernel(GradArgs a) {
-  constexpr int KSTEP = Op<OT>::KSTEP;
+  static_assert(!N16 || (sizeof(OT) == 4 && TM == 1), "the 16-wide variant is float only");
+  constexpr int KSTEP = N16 ? 16 : Op<OT>::KSTEP;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), g = lane >> 5, c = lane & 31;
   const int C = a.Nf, H = a.Himg, Wd = a.Wimg;
@@ -1770,21 +1774,27 @@ __global__ __launch_bounds__(NT) void conv_grad_kernel(GradArgs a) {
   // this lane's operand rows: output channel o for A, column n = tap * C + i for B; column 9C multiplies G by
   // ones, which sums it over the pixels (the bias gradient).  Clamped: blocks past the end compute values
   // that are never stored.
+  constexpr int BW = N16 ? 16 : 32;                     // block width: rows of A and columns of B per block
+  const int bl = N16 ? (lane & 15) : c;                 // this lane's row / column inside a block
+  const int kq = lane >> 4;                             // 16-wide blocks: the lane's quarter of a k step
   const OT* arow[TM];
   const OT* brow[TN];
 #pragma unroll
-  for (int i = 0; i < TM; ++i) arow[i] = Gt + min(32 * i + c, C - 1) * PG;
+  for (int i = 0; i < TM; ++i) arow[i] = Gt + min(BW * i + bl, C - 1) * PG;
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
-    const int n = min(32 * (wave + 4 * j) + c, 9 * C);
+    const int n = min(BW * (wave + 4 * j) + bl, 9 * C);
     const int tap = n / C, ii = n % C;
     brow[j] = n == 9 * C ? ones : Ut + ((tap % 3) * C + ii) * PU + (tap / 3) * Wp;
   }
   floatx16 acc[TM][TN];
+  floatx4 acc16[TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int j = 0; j < TN; ++j) acc[i][j] = zero16();
+#pragma unroll
+  for (int j = 0; j < TN; ++j) acc16[j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
   const int s_begin = ch * a.gspc, s_end = min(s_begin + a.gspc, a.gslabs);
   if (s_begin < s_end) load_slab(s_begin);
@@ -1794,13 +1804,26 @@ __global__ __launch_bounds__(NT) void conv_grad_kernel(GradArgs a) {
     __syncthreads();
     if (sl + 1 < s_end) load_slab(sl + 1);
     for (int ks = 0; ks < KL; ks += KSTEP) {
-      const OT* ap[TM];
-      const OT* bp[TN];
+      if constexpr (N16) {
+        // lane (bl, kq) feeds k = ks + 4 kq .. + 3, one value per instruction
+        const float4 af = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(arow[0]) + ks + 4 * kq);
 #pragma unroll
-      for (int i = 0; i < TM; ++i) ap[i] = arow[i] + ks;
+        for (int j = 0; j < TN; ++j) {
+          const float4 bf = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(brow[j]) + ks + 4 * kq);
+          acc16[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.x, bf.x, acc16[j], 0, 0, 0);
+          acc16[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.y, bf.y, acc16[j], 0, 0, 0);
+          acc16[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.z, bf.z, acc16[j], 0, 0, 0);
+          acc16[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.w, bf.w, acc16[j], 0, 0, 0);
+        }
+      } else {
+        const OT* ap[TM];
+        const OT* bp[TN];
 #pragma unroll
-      for (int j = 0; j < TN; ++j) bp[j] = brow[j] + ks;
-      mma_step<TM, TN>(ap, bp, acc, g);
+        for (int i = 0; i < TM; ++i) ap[i] = arow[i] + ks;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bp[j] = brow[j] + ks;
+        mma_step<TM, TN>(ap, bp, acc, g);
+      }
     }
   }
   const bool direct = a.gchunks == 1;
@@ -1811,20 +1834,36 @@ __global__ __launch_bounds__(NT) void conv_grad_kernel(GradArgs a) {
   float* dbd = direct ? (a.db ? a.db + (long long)gi * C : nullptr)
                       : a.partial + ((long long)ch * a.layers + gi) * pstride + a.wsize;
   const float scale = direct ? a.hs : 1.0f;
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
+  if constexpr (N16) {
+    // register v of lane (bl, kq) holds row o = 4 kq + v, column n = 16 (wave + 4 j) + bl of the block
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-      const int n = 32 * (wave + 4 * j) + c;
+      const int n = 16 * (wave + 4 * j) + bl;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int o = 32 * i + 8 * (r >> 2) + 4 * g + (r & 3);
+      for (int v = 0; v < 4; ++v) {
+        const int o = 4 * kq + v;
         if (o < C) {
-          if (n < NC) { if (dKd) dKd[(long long)o * NC + n] = scale * acc[i][j][r]; }
-          else if (n == NC) { if (dbd) dbd[o] = scale * acc[i][j][r]; }
+          if (n < NC) { if (dKd) dKd[(long long)o * NC + n] = scale * acc16[j][v]; }
+          else if (n == NC) { if (dbd) dbd[o] = scale * acc16[j][v]; }
         }
       }
     }
+  } else {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int n = 32 * (wave + 4 * j) + c;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int o = 32 * i + 8 * (r >> 2) + 4 * g + (r & 3);
+          if (o < C) {
+            if (n < NC) { if (dKd) dKd[(long long)o * NC + n] = scale * acc[i][j][r]; }
+            else if (n == NC) { if (dbd) dbd[o] = scale * acc[i][j][r]; }
+          }
+        }
+      }
+  }
 }
 // dK and db = hs * (sum of the chunk partial sums, in chunk order).  A record holds wsize values of dK and C of db.
 __global__ __launch_bounds__(NT) void conv_grad_reduce_kernel(const float* partial, float* dW, float* db, int layers,
@@ -1875,7 +1914,7 @@ __global__ __launch_bounds__(NT) void bias_grad_kernel(GradArgs a) {
 ConvGradGeom conv_grad_geom(int B, int Himg, int Wimg, int C, int dtype, int layers) {
   ConvGradGeom gm = {};
   const int es = dtype == 0 ? 4 : 2, pad = dtype == 0 ? Op<float>::PAD : Op<__bf16>::PAD;
-  const int kstep = dtype == 0 ? Op<float>::KSTEP : Op<__bf16>::KSTEP;
+  const int kstep = (dtype == 0 && C <= 16) ? 16 : dtype == 0 ? Op<float>::KSTEP : Op<__bf16>::KSTEP;   // as conv_grad_n16
   gm.Wp = (Wimg + 7) & ~7;
   // Image rows per slab.  A thread transposes at most one 4x4 block of G and three of the U patch per slab, so
   // R * blocks_per_row <= 256 and (R + 2) * blocks_per_row <= 768; 64 / Wp rows always satisfy that (64 channels,
@@ -1920,14 +1959,14 @@ static void launch_bias_grad(const GradArgs& a, int dtype, int groups, hipStream
   if (dtype == 0) hipLaunchKernelGGL((bias_grad_kernel<float>), grid, dim3(NT), 0, s, a);
   else            hipLaunchKernelGGL((bias_grad_kernel<__bf16>), grid, dim3(NT), 0, s, a);
 }
-template <typename OT, int TM, int TN>
+template <typename OT, int TM, int TN, bool N16 = false>
 static hipError_t launch_conv_grad(const GradArgs& a, unsigned blocks, size_t smem, hipStream_t s) {
   if (smem > 64 * 1024) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_grad_kernel<OT, TM, TN>),
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_grad_kernel<OT, TM, TN, N16>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL((conv_grad_kernel<OT, TM, TN>), dim3(blocks), dim3(NT), smem, s, a);
+  hipLaunchKernelGGL((conv_grad_kernel<OT, TM, TN, N16>), dim3(blocks), dim3(NT), smem, s, a);
   return hipGetLastError();
 }
 
@@ -2448,16 +2487,21 @@ hipError_t launch_grad(const GradArgs& a_in, int layer_kind, int dtype, int grou
       a.gWp = gm.Wp; a.gR = gm.R; a.gKL = gm.KL; a.gPU = gm.PU; a.gPG = gm.PG;
       a.gspi = gm.spi; a.gslabs = gm.slabs; a.gchunks = gm.chunks; a.gspc = gm.spc;
       a.tiles = gm.chunks;
-      const int tm = a.Nf > 32 ? 2 : 1, tn = ((9 * a.Nf + 1 + 31) / 32 + 3) / 4;
+      const bool n16 = dtype == 0 && a.Nf <= 16;            // 16x16x4 blocks (8 or 16 float channels)
+      const int tm = a.Nf > 32 ? 2 : 1, tn = n16 ? ((9 * a.Nf + 1 + 15) / 16 + 3) / 4 : ((9 * a.Nf + 1 + 31) / 32 + 3) / 4;
       hipError_t e = hipErrorInvalidValue;                 // also the result if the partial-sum buffer is missing
       const unsigned blocks = (unsigned)gm.chunks * (unsigned)groups;
       const bool have_buf = gm.chunks == 1 || a.partial != nullptr;
+      if (have_buf && n16 && tn == 2) e = launch_conv_grad<float, 1, 2, true>(a, blocks, gm.smem, s);      // 8 channels: 73 columns
+      else if (have_buf && n16 && tn == 3) e = launch_conv_grad<float, 1, 3, true>(a, blocks, gm.smem, s); // 16 channels: 145 columns
+      else {
 #define MGRIT_CG(TM_, TN_)                                                                                     \
       if (have_buf && tm == TM_ && tn == TN_)                                                                   \
         e = dtype == 0 ? launch_conv_grad<float, TM_, TN_>(a, blocks, gm.smem, s)                               \
                        : launch_conv_grad<__bf16, TM_, TN_>(a, blocks, gm.smem, s);
       MGRIT_CG(1, 1) MGRIT_CG(1, 2) MGRIT_CG(1, 3) MGRIT_CG(2, 3) MGRIT_CG(2, 4) MGRIT_CG(2, 5)
 #undef MGRIT_CG
+      }
       if (e != hipSuccess) { trace_after(s, TRACE_GRAD, groups, 0.0); return e; }
       if (gm.chunks > 1) {
         const long long total4 = (long long)groups * (a.wsize + a.Nf) / 4;
