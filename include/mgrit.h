@@ -23,10 +23,12 @@
  * stream capture and replayed.  Run the same call once outside the capture first: the first launch of
  * a kernel that uses more than 64 KB of LDS sets an attribute of that kernel on the current device.
  *
- * Environment.  MGRIT_NO_SWEEP=1 makes the library use one launch per layer step also where it would
- * fuse the steps of an F-relaxation sweep into one launch (dense layers of width 128 or 256, or float
- * convolution layers of at most 16 channels on images of at most 832 pixels, with many coarse intervals);
- * results agree with the fused path to rounding.  Read at every call; diagnostic.
+ * Environment (diagnostic switches, read at every call; results agree with the default path to rounding).
+ * MGRIT_NO_SWEEP=1 makes the library use one launch per layer step also where it would fuse the steps of an
+ * F-relaxation sweep into one launch (dense layers of width 128 or 256, or float convolution layers of at
+ * most 16 channels on images of at most 832 pixels, with many coarse intervals).  MGRIT_SWEEP_WAVES=4 runs
+ * the fused sweep of width 256 with four instead of eight wavefronts.  MGRIT_GRAD_NARROW=1 keeps the
+ * parameter gradient of dense layers of width 512 and more on 128x128 tiles with a separate bias pass.
  *
  * Layouts (all row-major, last index fastest):
  *   dense: state [B][q] float;  W [N][q_out][q_in];  b [N][q] float

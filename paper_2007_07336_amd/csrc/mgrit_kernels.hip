@@ -1021,15 +1021,21 @@ int step_grid_blocks(const StepArgs& a, int layer_kind, int dtype, int groups) {
   return ((a.M + t - 1) / t) * ((a.Nf + t - 1) / t);
 }
 
+// A failed LDS opt-in of a step kernel: the launch is skipped and launch_step returns this status.
+static hipError_t g_step_attr_err = hipSuccess;
+static bool step_opt_in(LdsOptIn& opt, const void* kernel, size_t smem) {
+  if (!opt.need(smem)) return true;
+  const hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  if (e != hipSuccess) { g_step_attr_err = e; opt = LdsOptIn(); return false; }
+  return true;
+}
 template <typename WT, int BM, int BN, int BK, int PF, bool WS>
 static void launch_dense_ws(dim3 grid, hipStream_t s, const StepArgs& a) {
   constexpr size_t tiles_b = (size_t)(BM + BN) * (BK + Op<WT>::PAD) * sizeof(WT);
   constexpr size_t stage_b = (size_t)4 * 32 * (BN / 2 + 4) * sizeof(float);   // epilogue staging, 2 wavefront columns
   constexpr size_t smem = tiles_b > stage_b ? tiles_b : stage_b;
   static LdsOptIn opt;
-  if (opt.need(smem))
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(dense_step_kernel<WT, BM, BN, 2, 2, BK, PF, WS>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  if (!step_opt_in(opt, reinterpret_cast<const void*>(dense_step_kernel<WT, BM, BN, 2, 2, BK, PF, WS>), smem)) return;
   hipLaunchKernelGGL((dense_step_kernel<WT, BM, BN, 2, 2, BK, PF, WS>), grid, dim3(NT), smem, s, a);
 }
 template <typename WT, int BM, int BN, int BK, int PF>
@@ -1041,9 +1047,7 @@ template <typename WT, bool WS, int NW>
 static void launch_ksplit_nw(dim3 grid, hipStream_t s, const StepArgs& a) {
   constexpr size_t smem = ksplit_smem<WT>(NW);
   static LdsOptIn opt;
-  if (opt.need(smem))
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(dense_ksplit_kernel<WT, WS, NW>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  if (!step_opt_in(opt, reinterpret_cast<const void*>(dense_ksplit_kernel<WT, WS, NW>), smem)) return;
   hipLaunchKernelGGL((dense_ksplit_kernel<WT, WS, NW>), grid, dim3(NW * 64), smem, s, a);
 }
 template <typename WT>
@@ -1056,9 +1060,7 @@ static void launch_ksplit(dim3 grid, hipStream_t s, const StepArgs& a) {
 template <typename WT, int TN, bool N16 = false>
 static void launch_conv(dim3 grid, size_t smem, hipStream_t s, const StepArgs& a) {
   static LdsOptIn opt;
-  if (opt.need(smem))
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(conv_step_kernel<WT, TN, N16>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  if (!step_opt_in(opt, reinterpret_cast<const void*>(conv_step_kernel<WT, TN, N16>), smem)) return;
   hipLaunchKernelGGL((conv_step_kernel<WT, TN, N16>), grid, dim3(NT), smem, s, a);
 }
 
@@ -1067,6 +1069,7 @@ hipError_t launch_step(const StepArgs& a_in, int layer_kind, int dtype, int grou
   StepArgs a = a_in;
   a.tiles = step_grid_blocks(a, layer_kind, dtype, groups);
   const dim3 grid((unsigned)a.tiles * (unsigned)groups);
+  g_step_attr_err = hipSuccess;
   trace_before(s);
   int cls;
   if (layer_kind == 1) {
@@ -1100,7 +1103,8 @@ hipError_t launch_step(const StepArgs& a_in, int layer_kind, int dtype, int grou
       else            launch_dense<__bf16, 64, 64, 128, 2>(grid, s, a);
     }
   }
-  const hipError_t e = hipGetLastError();
+  hipError_t e = hipGetLastError();
+  if (g_step_attr_err != hipSuccess) e = g_step_attr_err;
   int worked = groups;                 // groups that did a layer step (a mixed stack's convolution launch skips some)
   if (layer_kind == 1 && a.skipper > 0 && a.skip0 < groups) worked -= (groups - 1 - a.skip0) / a.skipper + 1;
   // algorithmic bytes: per layer step the layer's weights and bias once, the input state, every fused epilogue
