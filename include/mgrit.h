@@ -29,6 +29,8 @@
  * most 16 channels on images of at most 832 pixels, with many coarse intervals).  MGRIT_SWEEP_WAVES=4 runs
  * the fused sweep of width 256 with four instead of eight wavefronts.  MGRIT_GRAD_NARROW=1 keeps the
  * parameter gradient of dense layers of width 512 and more on 128x128 tiles with a separate bias pass.
+ * MGRIT_MASKED_STEP=1 sends dense layer steps whose batch, width and contraction length are whole multiples of
+ * the tile through the bounds-masked loop that ragged shapes use.
  *
  * Layouts (all row-major, last index fastest):
  *   dense: state [B][q] float;  W [N][q_out][q_in];  b [N][q] float

@@ -357,17 +357,18 @@ __device__ __forceinline__ void epilogue(const StepArgs& a, int gi, long long la
 // 4 wavefronts arranged WR x WC, each owning TM x TN blocks of 32x32.  Both operands are
 // staged through LDS in BK-wide slabs with a register prefetch of the next slab.
 // ------------------------------------------------------------------------------------------
-template <typename WT, int BM, int BN, int WR, int WC, int BK, int PF, bool WS>
-__global__ __launch_bounds__(NT) void dense_step_kernel(StepArgs a) {
+template <typename WT, int BM, int BN, int WR, int WC, int BK, int PF, bool WS, bool HD = true, bool FULL = false>
+__global__ __launch_bounds__(64 * WR * WC, WR * WC == 8 ? 4 : 1) void dense_step_kernel(StepArgs a) {
+  constexpr int NTH = 64 * WR * WC;
   constexpr int ST = BK + Op<WT>::PAD, VEC = Op<WT>::VEC, KSTEP = Op<WT>::KSTEP;
   constexpr int TM = BM / WR / 32, TN = BN / WC / 32;
-  constexpr int AP = BM * BK / 4 / NT;      // float4 pieces of the state slab per thread
-  constexpr int BP = BN * BK / VEC / NT;    // 16-byte pieces of the weight slab per thread
-  static_assert(AP >= 1 && BP >= 1 && WR * WC == 4 && BK % KSTEP == 0, "tile does not fit 256 threads");
+  constexpr int AP = BM * BK / 4 / NTH;      // float4 pieces of the state slab per thread
+  constexpr int BP = BN * BK / VEC / NTH;    // 16-byte pieces of the weight slab per thread
+  static_assert(AP >= 1 && BP >= 1 && (WR * WC == 4 || WR * WC == 8) && BK % KSTEP == 0, "tile does not fit the workgroup");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   WT* As = reinterpret_cast<WT*>(smem_raw);          // [BM][ST]
   WT* Bs = As + BM * ST;                             // [BN][ST]
-  __shared__ float red[4];
+  __shared__ float red[WR * WC];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), g = lane >> 5, c = lane & 31;
   const int tiles_n = (a.Nf + BN - 1) / BN;
@@ -376,7 +377,7 @@ __global__ __launch_bounds__(NT) void dense_step_kernel(StepArgs a) {
   const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
   const long long layer = a.wm.base + gi * a.wm.stride;
   const float* Xp = a.X + (a.xm.base + gi * a.xm.stride) * a.E;
-  const WT* Dp = a.Dm ? reinterpret_cast<const WT*>(a.Dm) + (a.dm.base + gi * a.dm.stride) * a.E : nullptr;
+  const WT* Dp = HD && a.Dm ? reinterpret_cast<const WT*>(a.Dm) + (a.dm.base + gi * a.dm.stride) * a.E : nullptr;
   const WT* Wp = reinterpret_cast<const WT*>(a.W) + layer * a.wsize;
   const int K = a.K;
   typedef typename DRaw<WT>::type DR;
@@ -385,44 +386,70 @@ __global__ __launch_bounds__(NT) void dense_step_kernel(StepArgs a) {
   // predicated load makes the compiler wait for it right away, which serialises the whole slab):
   // out-of-range pieces read element 0 instead and are zeroed when the slab goes to LDS.
   float4 areg[PF][AP];
-  DR dreg[PF][AP];
+  constexpr int DP = HD ? AP : 1;          // without the act' factor (HD false) its registers are not reserved
+  DR dreg[PF][DP];
   uint4 breg[PF][BP];
   unsigned amask[PF], bmask[PF];
-  auto load_slab = [&](float4 (&ar)[AP], DR (&dr)[AP], uint4 (&br)[BP], unsigned& am, unsigned& bm, int k0) {
+  // FULL (the launch wrapper has checked it): M, Nf and K are whole multiples of the tile, an operand of one group
+  // spans less than 4 GB, and HD says whether the act' factor is there.  Then nothing is masked, and a piece's
+  // address is a workgroup-uniform base plus a 32-bit byte offset that costs one vector addition per load -- with
+  // bf16 matrix instructions the masks, selects and 64-bit address arithmetic of the general path take several
+  // times as many issue cycles as the multiplications of a slab.
+  const unsigned aoff0 = FULL ? (unsigned)((m0 + tid / (BK / 4)) * K + (tid % (BK / 4)) * 4) : 0u;
+  const unsigned boff0 = FULL ? (unsigned)((n0 + tid / (BK / VEC)) * K + (tid % (BK / VEC)) * VEC) : 0u;
+  const unsigned astep = (unsigned)(NTH / (BK / 4)) * (unsigned)K, bstep = (unsigned)(NTH / (BK / VEC)) * (unsigned)K;
+  const char* Xc = reinterpret_cast<const char*>(Xp);
+  const char* Dc = reinterpret_cast<const char*>(Dp);
+  const char* Wc = reinterpret_cast<const char*>(Wp);
+  auto load_slab = [&](float4 (&ar)[AP], DR (&dr)[DP], uint4 (&br)[BP], unsigned& am, unsigned& bm, int k0) {
+    if constexpr (FULL) {
+#pragma unroll
+      for (int i = 0; i < AP; ++i) {
+        const unsigned off = aoff0 + (unsigned)i * astep + (unsigned)k0;
+        ar[i] = *reinterpret_cast<const float4*>(Xc + 4u * off);
+        if (HD) dr[HD ? i : 0] = ld_d4(reinterpret_cast<const WT*>(Dc + (unsigned)sizeof(WT) * off));
+      }
+#pragma unroll
+      for (int i = 0; i < BP; ++i) {
+        const unsigned off = boff0 + (unsigned)i * bstep + (unsigned)k0;
+        br[i] = ld_weights<WS>(reinterpret_cast<const WT*>(Wc + (unsigned)sizeof(WT) * off));
+      }
+      return;
+    }
     am = 0; bm = 0;
 #pragma unroll
     for (int i = 0; i < AP; ++i) {
-      const int p = tid + NT * i, row = p / (BK / 4), kc = (p % (BK / 4)) * 4;
+      const int p = tid + NTH * i, row = p / (BK / 4), kc = (p % (BK / 4)) * 4;
       const bool ok = m0 + row < a.M && k0 + kc < K;
       const unsigned off = ok ? (unsigned)((m0 + row) * K + k0 + kc) : 0u;
       am |= ok ? (1u << i) : 0u;
       ar[i] = *reinterpret_cast<const float4*>(Xp + off);
-      if (Dp) dr[i] = ld_d4(Dp + off);
+      if (HD && Dp) dr[HD ? i : 0] = ld_d4(Dp + off);
     }
 #pragma unroll
     for (int i = 0; i < BP; ++i) {
-      const int p = tid + NT * i, row = p / (BK / VEC), kc = (p % (BK / VEC)) * VEC;
+      const int p = tid + NTH * i, row = p / (BK / VEC), kc = (p % (BK / VEC)) * VEC;
       const bool ok = n0 + row < a.Nf && k0 + kc < K;
       const unsigned off = ok ? (unsigned)((n0 + row) * K + k0 + kc) : 0u;
       bm |= ok ? (1u << i) : 0u;
       br[i] = ld_weights<WS>(Wp + off);
     }
   };
-  auto store_slab = [&](const float4 (&ar)[AP], const DR (&dr)[AP], const uint4 (&br)[BP], unsigned am,
+  auto store_slab = [&](const float4 (&ar)[AP], const DR (&dr)[DP], const uint4 (&br)[BP], unsigned am,
                         unsigned bm) {
 #pragma unroll
     for (int i = 0; i < AP; ++i) {
-      const int p = tid + NT * i, row = p / (BK / 4), kc = (p % (BK / 4)) * 4;
+      const int p = tid + NTH * i, row = p / (BK / 4), kc = (p % (BK / 4)) * 4;
       float4 v = ar[i];
-      if (Dp) { const float4 d = d4_to_f4(dr[i]); v.x *= d.x; v.y *= d.y; v.z *= d.z; v.w *= d.w; }
-      if (!((am >> i) & 1u)) v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (HD && (FULL || Dp)) { const float4 d = d4_to_f4(dr[HD ? i : 0]); v.x *= d.x; v.y *= d.y; v.z *= d.z; v.w *= d.w; }
+      if (!FULL && !((am >> i) & 1u)) v = make_float4(0.f, 0.f, 0.f, 0.f);
       cvt_store4(&As[row * ST + kc], v);
     }
 #pragma unroll
     for (int i = 0; i < BP; ++i) {
-      const int p = tid + NT * i, row = p / (BK / VEC), kc = (p % (BK / VEC)) * VEC;
+      const int p = tid + NTH * i, row = p / (BK / VEC), kc = (p % (BK / VEC)) * VEC;
       uint4 v = br[i];
-      if (!((bm >> i) & 1u)) v = make_uint4(0, 0, 0, 0);
+      if (!FULL && !((bm >> i) & 1u)) v = make_uint4(0, 0, 0, 0);
       *reinterpret_cast<uint4*>(&Bs[row * ST + kc]) = v;
     }
   };
@@ -469,7 +496,6 @@ __global__ __launch_bounds__(NT) void dense_step_kernel(StepArgs a) {
   long long row0[TM];
 #pragma unroll
   for (int i = 0; i < TM; ++i) row0[i] = m0 + wm0 + i * 32;
-  static_assert(WC == 2, "the launch wrapper sizes the epilogue staging for two wavefront columns");
   epilogue<TM, TN>(a, gi, layer, acc, row0, (long long)a.M, n0 + wn0, L, red, reinterpret_cast<float*>(smem_raw));
 }
 
@@ -1029,19 +1055,36 @@ static bool step_opt_in(LdsOptIn& opt, const void* kernel, size_t smem) {
   if (e != hipSuccess) { g_step_attr_err = e; opt = LdsOptIn(); return false; }
   return true;
 }
-template <typename WT, int BM, int BN, int BK, int PF, bool WS>
-static void launch_dense_ws(dim3 grid, hipStream_t s, const StepArgs& a) {
+template <typename WT, int BM, int BN, int BK, int PF, bool WS, int WR, int WC, bool HD, bool FULL>
+static void launch_dense_k(dim3 grid, hipStream_t s, const StepArgs& a) {
   constexpr size_t tiles_b = (size_t)(BM + BN) * (BK + Op<WT>::PAD) * sizeof(WT);
-  constexpr size_t stage_b = (size_t)4 * 32 * (BN / 2 + 4) * sizeof(float);   // epilogue staging, 2 wavefront columns
+  constexpr size_t stage_b = (size_t)(WR * WC) * 32 * (BN / WC + 4) * sizeof(float);   // epilogue staging
   constexpr size_t smem = tiles_b > stage_b ? tiles_b : stage_b;
   static LdsOptIn opt;
-  if (!step_opt_in(opt, reinterpret_cast<const void*>(dense_step_kernel<WT, BM, BN, 2, 2, BK, PF, WS>), smem)) return;
-  hipLaunchKernelGGL((dense_step_kernel<WT, BM, BN, 2, 2, BK, PF, WS>), grid, dim3(NT), smem, s, a);
+  if (!step_opt_in(opt, reinterpret_cast<const void*>(dense_step_kernel<WT, BM, BN, WR, WC, BK, PF, WS, HD, FULL>), smem)) return;
+  hipLaunchKernelGGL((dense_step_kernel<WT, BM, BN, WR, WC, BK, PF, WS, HD, FULL>), grid, dim3(64 * WR * WC), smem, s, a);
 }
-template <typename WT, int BM, int BN, int BK, int PF>
+// Whole tiles and 32-bit byte offsets within one group's operands: the kernel's unmasked path.
+template <typename WT, int BM, int BN, int BK>
+static bool dense_full(const StepArgs& a) {
+  const char* e = getenv("MGRIT_MASKED_STEP");
+  if (e && e[0] == '1') return false;
+  return a.M % BM == 0 && a.Nf % BN == 0 && a.K % BK == 0 && (long long)a.M * a.K < (1ll << 30) &&
+         (long long)a.Nf * a.K * (long long)sizeof(WT) < (1ll << 32);
+}
+template <typename WT, int BM, int BN, int BK, int PF, bool WS, int WR = 2, int WC = 2>
+static void launch_dense_ws(dim3 grid, hipStream_t s, const StepArgs& a) {
+  if (dense_full<WT, BM, BN, BK>(a)) {
+    if (a.Dm) launch_dense_k<WT, BM, BN, BK, PF, WS, WR, WC, true, true>(grid, s, a);
+    else      launch_dense_k<WT, BM, BN, BK, PF, WS, WR, WC, false, true>(grid, s, a);
+  } else {
+    launch_dense_k<WT, BM, BN, BK, PF, WS, WR, WC, true, false>(grid, s, a);
+  }
+}
+template <typename WT, int BM, int BN, int BK, int PF, int WR = 2, int WC = 2>
 static void launch_dense(dim3 grid, hipStream_t s, const StepArgs& a) {
-  if (a.wstream) launch_dense_ws<WT, BM, BN, BK, PF, true>(grid, s, a);
-  else           launch_dense_ws<WT, BM, BN, BK, PF, false>(grid, s, a);
+  if (a.wstream) launch_dense_ws<WT, BM, BN, BK, PF, true, WR, WC>(grid, s, a);
+  else           launch_dense_ws<WT, BM, BN, BK, PF, false, WR, WC>(grid, s, a);
 }
 template <typename WT, bool WS, int NW>
 static void launch_ksplit_nw(dim3 grid, hipStream_t s, const StepArgs& a) {

@@ -455,6 +455,45 @@ def test_dense_parameter_gradient_wide_layers(wl, wide, monkeypatch):
     assert np.array_equal(dW2.cpu().numpy(), dW)
 
 
+# ------------------------------------------------------------------ dense steps on whole tiles
+# When batch, width and contraction length are whole multiples of the tile, the dense step kernel runs a loop
+# without bounds masks (MGRIT_MASKED_STEP=1 sends such shapes through the masked loop that ragged shapes use).
+# Both must agree with the oracle, and with each other bit for bit: the arithmetic is the same.  Shapes: the
+# 128x128 tile in both operand types (batch 256 / 128, width 512 so that the fused sweeps stay out of the way)
+# and the 64x64 tile (batch 64, width 192).
+WHOLE_TILE_CASES = [
+    I.reduced(I.cfg5(1), name="whole_bf16_q512_B256_N16_m4", q=512, B=256, N=16, m=4, max_levels=2),
+    I.reduced(I.cfg5(1), name="whole_fp32_q512_B128_N16_m4", q=512, B=128, N=16, m=4, max_levels=2, dtype=I.FP32),
+    I.reduced(I.cfg5(1), name="whole_bf16_q192_B64_N64_m4", q=192, B=64, N=64, m=4, max_levels=2),
+]
+
+
+@pytest.mark.parametrize("wl", WHOLE_TILE_CASES, ids=lambda w: w.name)
+def test_dense_step_whole_tiles_unmasked_and_masked(wl, monkeypatch):
+    _announce(wl.name)
+    data = I.generate(wl)
+    Uo, hist_o, _ = oracle_forward(wl, data)
+    res = {}
+    for masked in (False, True):
+        if masked:
+            monkeypatch.setenv("MGRIT_MASKED_STEP", "1")
+        gp = GpuProblem(wl, data)
+        rc, U, hist, it = gp.forward()
+        assert rc == 0
+        lamN = I.terminal_adjoint(wl, data, U[-1])
+        Lam, dW, db, _, _ = gp.adjoint(U, lamN)
+        res[masked] = (U, Lam, dW, db, lamN)
+    U, Lam, dW, db, lamN = res[False]
+    for x, y in zip(res[False][:4], res[True][:4]):
+        assert np.array_equal(x, y)
+    tol = TOL[wl.dtype]
+    eU = rel_l2_per_state(U, Uo)
+    Lo, dWo, dbo, _, _ = oracle_adjoint(wl, data, U, lamN)
+    eL, eW = rel_l2_per_state(Lam, Lo), rel_l2_per_state(dW, dWo)
+    print(f"{wl.name}: U {eU:.3e} Lam {eL:.3e} dW {eW:.3e}", flush=True)
+    assert eU <= tol and eL <= tol and eW <= tol, (eU, eL, eW)
+
+
 # ------------------------------------------------------------------ fused F-relaxation sweeps (dense layers)
 # Shapes on which the library fuses the steps of an F-relaxation sweep into one launch (width 128 or 256;
 # at least 128 (interval, 32-row slice) workgroups; m >= 3); each also runs with the fused
