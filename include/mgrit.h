@@ -31,6 +31,8 @@
  * parameter gradient of dense layers of width 512 and more on 128x128 tiles with a separate bias pass.
  * MGRIT_MASKED_STEP=1 sends dense layer steps whose batch, width and contraction length are whole multiples of
  * the tile through the bounds-masked loop that ragged shapes use.
+ * MGRIT_CONV_GENERIC=1 keeps bf16 convolution layers of 64 channels on the kernel that takes the channel count at
+ * run time instead of the one compiled for 64.
  *
  * Layouts (all row-major, last index fastest):
  *   dense: state [B][q] float;  W [N][q_out][q_in];  b [N][q] float

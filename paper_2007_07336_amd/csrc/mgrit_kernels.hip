@@ -697,9 +697,14 @@ __global__ __launch_bounds__(NW * 64) void dense_ksplit_kernel(StepArgs a) {
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 // p / w for 0 <= p < 4096 and 1 <= w <= 256 with magic = ceil(2^20 / w): exact because p * (magic * w - 2^20) < 2^20
 __device__ __forceinline__ int div_small(int p, unsigned magic) { return (int)(((unsigned)p * magic) >> 20); }
-template <typename WT, int TN, bool N16 = false>
+// CFIX > 0: the channel count is this compile-time value (a multiple of the MFMA's k step that fills the
+// workgroup's output columns), so the tap loop unrolls with its LDS reads ahead of the matrix instructions and
+// the weight pieces need neither masks nor divisions -- with bf16 matrix instructions a tap is 16 of them per
+// wavefront, and a rolled k loop that waits for every fragment read takes several times as long.
+template <typename WT, int TN, bool N16 = false, int CFIX = 0>
 __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
   static_assert(!N16 || (sizeof(WT) == 4 && TN == 1), "the 16-wide variant is float only");
+  static_assert(CFIX == 0 || (!N16 && CFIX == 32 * TN && CFIX % Op<WT>::KSTEP == 0), "fixed channel count = output columns");
   constexpr int VEC = Op<WT>::VEC, KSTEP = N16 ? 16 : Op<WT>::KSTEP, PAD = Op<WT>::PAD;
   constexpr int TM = 2;
   constexpr int CW = N16 ? 16 : 32 * TN;    // output channels a workgroup covers
@@ -709,8 +714,8 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
   __shared__ float red[4];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), g = lane >> 5, c = lane & 31;
-  const int C = a.Nf, H = a.Himg, Wd = a.Wimg, TH = a.TH;
-  const int Cp = N16 ? 16 : (C + KSTEP - 1) / KSTEP * KSTEP;   // a compile-time value in the 16-wide variant (C <= 16)
+  const int C = CFIX ? CFIX : a.Nf, H = a.Himg, Wd = a.Wimg, TH = a.TH;
+  const int Cp = N16 ? 16 : CFIX ? CFIX : (C + KSTEP - 1) / KSTEP * KSTEP;   // a compile-time value in the 16-wide and the fixed variant
   const int CS = Cp + PAD;
   const int PW = Wd + 2;
   WT* patch = reinterpret_cast<WT*>(smem_raw);
@@ -943,7 +948,7 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
           if (wave_active) {
             const int toff = ((tap / 3) * PW + (tap % 3)) * CS;
             const WT* wt = wbuf[sidx];
-            for (int ks = 0; ks < Cp; ks += KSTEP) {
+            auto kstep = [&](int ks) {
               const WT* ap[TM];
               const WT* bp[TN];
 #pragma unroll
@@ -951,6 +956,12 @@ __global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
 #pragma unroll
               for (int j = 0; j < TN; ++j) bp[j] = wt + (j * 32 + c) * CS + ks;
               mma_step<TM, TN>(ap, bp, acc, g);
+            };
+            if constexpr (CFIX > 0) {
+#pragma unroll
+              for (int ks = 0; ks < CFIX; ks += KSTEP) kstep(ks);
+            } else {
+              for (int ks = 0; ks < Cp; ks += KSTEP) kstep(ks);
             }
           }
           __syncthreads();                      // tap+1 visible; everyone is done with this buffer
@@ -1100,11 +1111,16 @@ static void launch_ksplit(dim3 grid, hipStream_t s, const StepArgs& a) {
   else           { if (wide) launch_ksplit_nw<WT, false, 8>(grid, s, a); else launch_ksplit_nw<WT, false, 4>(grid, s, a); }
 }
 
-template <typename WT, int TN, bool N16 = false>
+template <typename WT, int TN, bool N16 = false, int CFIX = 0>
 static void launch_conv(dim3 grid, size_t smem, hipStream_t s, const StepArgs& a) {
   static LdsOptIn opt;
-  if (!step_opt_in(opt, reinterpret_cast<const void*>(conv_step_kernel<WT, TN, N16>), smem)) return;
-  hipLaunchKernelGGL((conv_step_kernel<WT, TN, N16>), grid, dim3(NT), smem, s, a);
+  if (!step_opt_in(opt, reinterpret_cast<const void*>(conv_step_kernel<WT, TN, N16, CFIX>), smem)) return;
+  hipLaunchKernelGGL((conv_step_kernel<WT, TN, N16, CFIX>), grid, dim3(NT), smem, s, a);
+}
+// MGRIT_CONV_GENERIC=1 in the environment keeps 64-channel bf16 layers on the kernel with a run-time channel count
+static bool conv_fixed_channels(const StepArgs& a, int dtype) {
+  const char* e = getenv("MGRIT_CONV_GENERIC");
+  return dtype == 1 && a.Nf == 64 && !(e && e[0] == '1');
 }
 
 hipError_t launch_step(const StepArgs& a_in, int layer_kind, int dtype, int groups, hipStream_t s) {
@@ -1126,6 +1142,7 @@ hipError_t launch_step(const StepArgs& a_in, int layer_kind, int dtype, int grou
       else            launch_conv<__bf16, 1>(grid, smem, s, a);
     } else {
       if (dtype == 0) launch_conv<float, 2>(grid, smem, s, a);
+      else if (conv_fixed_channels(a, dtype)) launch_conv<__bf16, 2, false, 64>(grid, smem, s, a);
       else            launch_conv<__bf16, 2>(grid, smem, s, a);
     }
   } else {

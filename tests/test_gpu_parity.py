@@ -135,6 +135,35 @@ def test_conv_forward(wl):
     _check_forward(wl)
 
 
+# bf16 layers of 64 channels run a kernel compiled for that channel count (unrolled tap loop, no masks on the
+# weight pieces); MGRIT_CONV_GENERIC=1 keeps them on the kernel with a run-time channel count.  Same arithmetic:
+# forward and adjoint results must agree bit for bit, and with the oracle.
+def test_conv_bf16_64_channels_fixed_and_generic_kernel(monkeypatch):
+    wl = I.reduced(I.cfg4(2), name="conv_bf16_c64_20x12_B3_N32_m4_L2", B=3, Himg=20, Wimg=12, N=32, m=4, max_levels=2)
+    _announce(wl.name)
+    data = I.generate(wl)
+    Uo, _, _ = oracle_forward(wl, data)
+    res = {}
+    for generic in (False, True):
+        if generic:
+            monkeypatch.setenv("MGRIT_CONV_GENERIC", "1")
+        gp = GpuProblem(wl, data)
+        rc, U, hist, it = gp.forward()
+        assert rc == 0
+        lamN = np.random.default_rng(5).standard_normal(wl.state_shape).astype(np.float32)
+        Ul = I.round_to_bf16(U)      # ReLU' is a 0/1 decision: both sides take it on bf16-representable states
+        Lam, dW, db, _, _ = gp.adjoint(Ul, lamN)
+        res[generic] = (U, Lam, dW, db, lamN, Ul)
+    for x, y in zip(res[False][:4], res[True][:4]):
+        assert np.array_equal(x, y)
+    U, Lam, dW, db, lamN, Ul = res[False]
+    tol = TOL[wl.dtype]
+    Lo, dWo, dbo, _, _ = oracle_adjoint(wl, data, Ul, lamN)
+    eU, eL, eW = rel_l2_per_state(U, Uo), rel_l2_per_state(Lam, Lo), rel_l2_per_state(dW, dWo)
+    print(f"{wl.name}: U {eU:.3e} Lam {eL:.3e} dW {eW:.3e}", flush=True)
+    assert eU <= tol and eL <= tol and eW <= tol, (eU, eL, eW)
+
+
 # ------------------------------------------------------------------ options of the boundary
 def test_init_modes_and_user_guess():
     for q in (24, 128):
