@@ -31,6 +31,8 @@
  * parameter gradient of dense layers of width 512 and more on 128x128 tiles with a separate bias pass.
  * MGRIT_MASKED_STEP=1 sends dense layer steps whose batch, width and contraction length are whole multiples of
  * the tile through the bounds-masked loop that ragged shapes use.
+ * MGRIT_STEP_REREAD=1 makes the epilogue of the bf16 128x128 dense tile read the state for the skip connection
+ * from memory again instead of keeping it in registers from the contraction loop.
  * MGRIT_CONV_GENERIC=1 keeps bf16 convolution layers of 64 channels on the kernel that takes the channel count at
  * run time instead of the one compiled for 64.
  *

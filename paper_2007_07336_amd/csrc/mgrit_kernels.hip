@@ -357,7 +357,11 @@ __device__ __forceinline__ void epilogue(const StepArgs& a, int gi, long long la
 // 4 wavefronts arranged WR x WC, each owning TM x TN blocks of 32x32.  Both operands are
 // staged through LDS in BK-wide slabs with a register prefetch of the next slab.
 // ------------------------------------------------------------------------------------------
-template <typename WT, int BM, int BN, int WR, int WC, int BK, int PF, bool WS, bool HD = true, bool FULL = false>
+// XR (with FULL, square layers, BN = 2 BK, PF = 1): the two k slabs of the state operand that cover the tile's own
+// output columns are kept in registers when they pass through, as the skip-connection operand of the epilogue, and
+// the epilogue works on the whole 128 x 128 tile in the arrangement of those loads (thread -> 8 rows x 4 columns of
+// each 64-column half), so the state is read from memory once per step instead of twice.
+template <typename WT, int BM, int BN, int WR, int WC, int BK, int PF, bool WS, bool HD = true, bool FULL = false, bool XR = false>
 __global__ __launch_bounds__(64 * WR * WC, WR * WC == 8 ? 4 : 1) void dense_step_kernel(StepArgs a) {
   constexpr int NTH = 64 * WR * WC;
   constexpr int ST = BK + Op<WT>::PAD, VEC = Op<WT>::VEC, KSTEP = Op<WT>::KSTEP;
@@ -459,6 +463,9 @@ __global__ __launch_bounds__(64 * WR * WC, WR * WC == 8 ? 4 : 1) void dense_step
   for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int j = 0; j < TN; ++j) acc[i][j] = zero16();
+  static_assert(!XR || (FULL && PF == 1 && BN == 2 * BK && BM == 128 && NTH == 256), "XR: whole 128 x 128 tiles, two slabs per tile width");
+  constexpr int NXO = XR ? AP : 1;
+  float4 xown[2][NXO];
 
   const int wm0 = (wave / WC) * (BM / WR), wn0 = (wave % WC) * (BN / WC);
   // The k slabs are visited in a rotated order that depends on the group: with a power-of-two
@@ -477,6 +484,24 @@ __global__ __launch_bounds__(64 * WR * WC, WR * WC == 8 ? 4 : 1) void dense_step
       if (it < nk) {
         __syncthreads();
         store_slab(areg[sidx], dreg[sidx], breg[sidx], amask[sidx], bmask[sidx]);
+        if constexpr (XR) {
+          const int kcur = slab_k0(it);
+          // (component by component: a struct copy under a condition becomes a memcpy into private memory,
+          // which would put the kept slabs into scratch)
+          if (kcur == n0) {
+#pragma unroll
+            for (int q = 0; q < AP; ++q) {
+              xown[0][q].x = areg[sidx][q].x; xown[0][q].y = areg[sidx][q].y;
+              xown[0][q].z = areg[sidx][q].z; xown[0][q].w = areg[sidx][q].w;
+            }
+          } else if (kcur == n0 + BK) {
+#pragma unroll
+            for (int q = 0; q < AP; ++q) {
+              xown[1][q].x = areg[sidx][q].x; xown[1][q].y = areg[sidx][q].y;
+              xown[1][q].z = areg[sidx][q].z; xown[1][q].w = areg[sidx][q].w;
+            }
+          }
+        }
         __syncthreads();
         if (it + PF < nk) load_slab(areg[sidx], dreg[sidx], breg[sidx], amask[sidx], bmask[sidx], slab_k0(it + PF));
 #pragma unroll
@@ -493,6 +518,85 @@ __global__ __launch_bounds__(64 * WR * WC, WR * WC == 8 ? 4 : 1) void dense_step
     }
   }
 
+  if constexpr (XR) {
+    // whole-tile epilogue: accumulators -> LDS [BM][BN + 4], then thread (rq, cq) handles rows rq + 16 i, columns
+    // 64 half + 4 cq .. + 3 -- the float4 it loaded for the state slabs k0 = n0 and n0 + BK
+    constexpr int SWF = BN + 4;
+    float* stage = reinterpret_cast<float*>(smem_raw);
+    __syncthreads();                           // every wavefront is done reading the operand tiles
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          stage[(wm0 + i * 32 + 8 * (r >> 2) + 4 * g + (r & 3)) * SWF + wn0 + jn * 32 + c] = acc[i][jn][r];
+    __syncthreads();
+    const EpiPtrs e = epi_ptrs(a, gi, layer);
+    const int rq = tid / (BK / 4), cq = (tid % (BK / 4)) * 4;
+    const bool dact = a.mode == MODE_DACT;
+    float sq = 0.0f;
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      const int col = n0 + half * BK + cq;
+      float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (e.bp) bv = *reinterpret_cast<const float4*>(e.bp + col);
+#pragma unroll
+      for (int h0 = 0; h0 < AP; h0 += 4) {
+        float4 z[4], e1[4], e2[4];
+        unsigned off[4];
+        const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int row = rq + (NTH / (BK / 4)) * (h0 + u);
+          off[u] = (unsigned)((m0 + row) * a.Nf + col);
+          z[u] = *reinterpret_cast<const float4*>(&stage[row * SWF + half * BK + cq]);
+        }
+        // (branches, not selects: a select between a load and a constant becomes a select of two addresses,
+        // one of them in private memory, and a generic load)
+        if (e.E1p) {
+#pragma unroll
+          for (int u = 0; u < 4; ++u) e1[u] = *reinterpret_cast<const float4*>(e.E1p + off[u]);
+        } else {
+#pragma unroll
+          for (int u = 0; u < 4; ++u) e1[u] = zero;
+        }
+        if (e.E2p) {
+#pragma unroll
+          for (int u = 0; u < 4; ++u) e2[u] = *reinterpret_cast<const float4*>(e.E2p + off[u]);
+        } else {
+#pragma unroll
+          for (int u = 0; u < 4; ++u) e2[u] = zero;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const float4 xv = xown[half][XR ? h0 + u : 0];
+          float4 o;
+          if (dact) {
+            o.x = act_prime(z[u].x + bv.x, a.act); o.y = act_prime(z[u].y + bv.y, a.act);
+            o.z = act_prime(z[u].z + bv.z, a.act); o.w = act_prime(z[u].w + bv.w, a.act);
+          } else {
+            o.x = a.sp * (xv.x + a.hs * act_fn(z[u].x + bv.x, a.act)) + a.c1 * e1[u].x + a.c2 * e2[u].x;
+            o.y = a.sp * (xv.y + a.hs * act_fn(z[u].y + bv.y, a.act)) + a.c1 * e1[u].y + a.c2 * e2[u].y;
+            o.z = a.sp * (xv.z + a.hs * act_fn(z[u].z + bv.z, a.act)) + a.c1 * e1[u].z + a.c2 * e2[u].z;
+            o.w = a.sp * (xv.w + a.hs * act_fn(z[u].w + bv.w, a.act)) + a.c1 * e1[u].w + a.c2 * e2[u].w;
+          }
+          if (dact && a.dbf16) {
+            __bf16* ob = reinterpret_cast<__bf16*>(a.Out) + (a.om.base + gi * a.om.stride) * a.E;
+            cvt_store4(ob + off[u], o);
+          } else if (e.Op_) {
+            *reinterpret_cast<float4*>(e.Op_ + off[u]) = o;
+          }
+          sq += (o.x * o.x + o.y * o.y) + (o.z * o.z + o.w * o.w);
+        }
+      }
+    }
+    if (a.norm_partial) {
+      const float sum = block_sum(sq, red);
+      if (threadIdx.x == 0) a.norm_partial[L] = sum;
+    }
+    return;
+  }
   long long row0[TM];
 #pragma unroll
   for (int i = 0; i < TM; ++i) row0[i] = m0 + wm0 + i * 32;
@@ -1066,14 +1170,15 @@ static bool step_opt_in(LdsOptIn& opt, const void* kernel, size_t smem) {
   if (e != hipSuccess) { g_step_attr_err = e; opt = LdsOptIn(); return false; }
   return true;
 }
-template <typename WT, int BM, int BN, int BK, int PF, bool WS, int WR, int WC, bool HD, bool FULL>
+template <typename WT, int BM, int BN, int BK, int PF, bool WS, int WR, int WC, bool HD, bool FULL, bool XR = false>
 static void launch_dense_k(dim3 grid, hipStream_t s, const StepArgs& a) {
   constexpr size_t tiles_b = (size_t)(BM + BN) * (BK + Op<WT>::PAD) * sizeof(WT);
-  constexpr size_t stage_b = (size_t)(WR * WC) * 32 * (BN / WC + 4) * sizeof(float);   // epilogue staging
+  constexpr size_t stage_b = XR ? (size_t)BM * (BN + 4) * sizeof(float)                   // whole-tile epilogue staging
+                                : (size_t)(WR * WC) * 32 * (BN / WC + 4) * sizeof(float);  // per-wavefront staging
   constexpr size_t smem = tiles_b > stage_b ? tiles_b : stage_b;
   static LdsOptIn opt;
-  if (!step_opt_in(opt, reinterpret_cast<const void*>(dense_step_kernel<WT, BM, BN, WR, WC, BK, PF, WS, HD, FULL>), smem)) return;
-  hipLaunchKernelGGL((dense_step_kernel<WT, BM, BN, WR, WC, BK, PF, WS, HD, FULL>), grid, dim3(64 * WR * WC), smem, s, a);
+  if (!step_opt_in(opt, reinterpret_cast<const void*>(dense_step_kernel<WT, BM, BN, WR, WC, BK, PF, WS, HD, FULL, XR>), smem)) return;
+  hipLaunchKernelGGL((dense_step_kernel<WT, BM, BN, WR, WC, BK, PF, WS, HD, FULL, XR>), grid, dim3(64 * WR * WC), smem, s, a);
 }
 // Whole tiles and 32-bit byte offsets within one group's operands: the kernel's unmasked path.
 template <typename WT, int BM, int BN, int BK>
@@ -1083,9 +1188,25 @@ static bool dense_full(const StepArgs& a) {
   return a.M % BM == 0 && a.Nf % BN == 0 && a.K % BK == 0 && (long long)a.M * a.K < (1ll << 30) &&
          (long long)a.Nf * a.K * (long long)sizeof(WT) < (1ll << 32);
 }
+// The skip-connection operand from the registers of the k loop: square layers on the bf16 128 x 128 tile
+// (MGRIT_STEP_REREAD=1 keeps the epilogue's own read of the state)
+template <typename WT, int BM, int BN, int BK, int PF>
+static bool dense_xr(const StepArgs& a) {
+  if (!(sizeof(WT) == 2 && BM == 128 && BN == 128 && BK == 64 && PF == 1)) return false;
+  const char* e = getenv("MGRIT_STEP_REREAD");
+  if (e && e[0] == '1') return false;
+  return a.K == a.Nf && a.mode != MODE_DACT;
+}
 template <typename WT, int BM, int BN, int BK, int PF, bool WS, int WR = 2, int WC = 2>
 static void launch_dense_ws(dim3 grid, hipStream_t s, const StepArgs& a) {
   if (dense_full<WT, BM, BN, BK>(a)) {
+    if constexpr (sizeof(WT) == 2 && BM == 128 && BN == 128 && BK == 64 && PF == 1 && WR == 2 && WC == 2) {
+      if (dense_xr<WT, BM, BN, BK, PF>(a)) {
+        if (a.Dm) launch_dense_k<WT, BM, BN, BK, PF, WS, WR, WC, true, true, true>(grid, s, a);
+        else      launch_dense_k<WT, BM, BN, BK, PF, WS, WR, WC, false, true, true>(grid, s, a);
+        return;
+      }
+    }
     if (a.Dm) launch_dense_k<WT, BM, BN, BK, PF, WS, WR, WC, true, true>(grid, s, a);
     else      launch_dense_k<WT, BM, BN, BK, PF, WS, WR, WC, false, true>(grid, s, a);
   } else {

@@ -486,7 +486,9 @@ def test_dense_parameter_gradient_wide_layers(wl, wide, monkeypatch):
 
 # ------------------------------------------------------------------ dense steps on whole tiles
 # When batch, width and contraction length are whole multiples of the tile, the dense step kernel runs a loop
-# without bounds masks (MGRIT_MASKED_STEP=1 sends such shapes through the masked loop that ragged shapes use).
+# without bounds masks (MGRIT_MASKED_STEP=1 sends such shapes through the masked loop that ragged shapes use), and
+# on bf16 128x128 tiles it keeps the tile's own state columns from that loop for the skip connection
+# (MGRIT_STEP_REREAD=1: the epilogue reads them again).
 # Both must agree with the oracle, and with each other bit for bit: the arithmetic is the same.  Shapes: the
 # 128x128 tile in both operand types (batch 256 / 128, width 512 so that the fused sweeps stay out of the way)
 # and the 64x64 tile (batch 64, width 192).
@@ -503,18 +505,23 @@ def test_dense_step_whole_tiles_unmasked_and_masked(wl, monkeypatch):
     data = I.generate(wl)
     Uo, hist_o, _ = oracle_forward(wl, data)
     res = {}
-    for masked in (False, True):
-        if masked:
-            monkeypatch.setenv("MGRIT_MASKED_STEP", "1")
+    # default; the epilogue reading the state again instead of keeping the tile's own columns from the k loop
+    # (bf16 128x128 tiles); the masked loop
+    for mode, var in (("default", None), ("reread", "MGRIT_STEP_REREAD"), ("masked", "MGRIT_MASKED_STEP")):
+        if var:
+            monkeypatch.setenv(var, "1")
         gp = GpuProblem(wl, data)
         rc, U, hist, it = gp.forward()
         assert rc == 0
         lamN = I.terminal_adjoint(wl, data, U[-1])
         Lam, dW, db, _, _ = gp.adjoint(U, lamN)
-        res[masked] = (U, Lam, dW, db, lamN)
-    U, Lam, dW, db, lamN = res[False]
-    for x, y in zip(res[False][:4], res[True][:4]):
-        assert np.array_equal(x, y)
+        res[mode] = (U, Lam, dW, db, lamN)
+        if var:
+            monkeypatch.delenv(var)
+    U, Lam, dW, db, lamN = res["default"]
+    for mode in ("reread", "masked"):
+        for x, y in zip(res["default"][:4], res[mode][:4]):
+            assert np.array_equal(x, y), mode
     tol = TOL[wl.dtype]
     eU = rel_l2_per_state(U, Uo)
     Lo, dWo, dbo, _, _ = oracle_adjoint(wl, data, U, lamN)
