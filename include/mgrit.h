@@ -33,6 +33,8 @@
  * the tile through the bounds-masked loop that ragged shapes use.
  * MGRIT_STEP_REREAD=1 makes the epilogue of the bf16 128x128 dense tile read the state for the skip connection
  * from memory again instead of keeping it in registers from the contraction loop.
+ * MGRIT_CGRAD_WAVES=4 runs the parameter gradient of convolution layers with more than 32 channels with four
+ * wavefronts per workgroup, as for narrower layers, instead of eight.
  * MGRIT_CONV_GENERIC=1 keeps bf16 convolution layers of 64 channels on the kernel that takes the channel count at
  * run time instead of the one compiled for 64.
  *

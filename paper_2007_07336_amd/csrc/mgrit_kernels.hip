@@ -1840,8 +1840,13 @@ __global__ __launch_bounds__(NT) void conv_grad_tap_kernel(GradArgs a) {
 // N16 (float, at most 16 channels): 16x16x4 blocks, so the output-channel side carries no padding rows (a 32-row
 // block would be half empty at 16 channels, and this kernel is bound by the matrix cores); wavefront w then owns the
 // 16-column blocks w, w+4, ..
-template <typename OT, int TM, int TN, bool N16 = false>
-__global__ __launch_bounds__(NT) void conv_grad_kernel(GradArgs a) {
+// NWV wavefronts: 4, or 8 for more than 32 channels -- there the accumulators of four wavefronts (2 x 5 blocks
+// each) leave room for one workgroup per CU anyway, and with eight the transposing stores of a slab, which
+// take longer than its matrix instructions, are spread over twice the threads.
+template <typename OT, int TM, int TN, bool N16 = false, int NWV = 4>
+__global__ __launch_bounds__(64 * NWV) void conv_grad_kernel(GradArgs a) {
+  constexpr int NTH = 64 * NWV;
+  constexpr int UB = NWV == 8 ? 2 : 3;                  // 4x4 blocks of the U patch per thread, at most
   static_assert(!N16 || (sizeof(OT) == 4 && TM == 1), "the 16-wide variant is float only");
   constexpr int KSTEP = N16 ? 16 : Op<OT>::KSTEP;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -1860,28 +1865,31 @@ __global__ __launch_bounds__(NT) void conv_grad_kernel(GradArgs a) {
 
   {
     const int n16 = (int)(((size_t)3 * C * PU + (size_t)C * PG) * sizeof(OT) / 16);
-    for (int p = tid; p < n16; p += NT) reinterpret_cast<uint4*>(smem_raw)[p] = make_uint4(0u, 0u, 0u, 0u);
-    for (int p = tid; p < PU; p += NT) ones[p] = static_cast<OT>(1.0f);
+    for (int p = tid; p < n16; p += NTH) reinterpret_cast<uint4*>(smem_raw)[p] = make_uint4(0u, 0u, 0u, 0u);
+    for (int p = tid; p < PU; p += NTH) ones[p] = static_cast<OT>(1.0f);
   }
 
-  // this thread's 4x4 blocks: one of G, up to three of the U patch (channel group fastest, then x, then row)
+  // this thread's 4x4 blocks: one of G, up to UB of the U patch (x group fastest, then channel group, then row)
   const int CG = C >> 2, XG = (Wd + 3) >> 2;
   const int nGb = R * XG * CG, nUb = (R + 2) * XG * CG;
   const bool gact = tid < nGb;
   const int gb = gact ? tid : 0;
-  const int g_cg = gb % CG, g_xg = (gb / CG) % XG, g_r = gb / (CG * XG);
-  bool uact[3];
-  int u_cg[3], u_xg[3], u_r[3];
+  // (x group fastest: the lanes of a store instruction then spread over the pixel slots of a channel row, 8 bytes
+  // apart, instead of over channel rows, whose pitch maps every second one to the same LDS banks)
+  const int g_xg = gb % XG, g_cg = (gb / XG) % CG, g_r = gb / (CG * XG);
+  bool uact[UB];
+  int u_cg[UB], u_xg[UB], u_r[UB];
 #pragma unroll
-  for (int t = 0; t < 3; ++t) {
-    const int blk = tid + NT * t;
+  for (int t = 0; t < UB; ++t) {
+    const int blk = tid + NTH * t;
     uact[t] = blk < nUb;
     const int ub = uact[t] ? blk : 0;
-    u_cg[t] = ub % CG; u_xg[t] = (ub / CG) % XG; u_r[t] = ub / (CG * XG);
+    u_xg[t] = ub % XG; u_cg[t] = (ub / XG) % CG; u_r[t] = ub / (CG * XG);
   }
-  float4 lv[4], uv[3][4];
+  const bool lane_shift = (64 % XG) == 0;              // uniform; else the shifted copies are stored element by element
+  float4 lv[4], uv[UB][4];
   DR dv[4];
-  unsigned gmask = 0, umask[3] = {0, 0, 0};
+  unsigned gmask = 0, umask[UB] = {};
   auto load_slab = [&](int sl) {
     const int b = sl / a.gspi, y0 = (sl % a.gspi) * R;
     {
@@ -1899,8 +1907,8 @@ __global__ __launch_bounds__(NT) void conv_grad_kernel(GradArgs a) {
       }
     }
 #pragma unroll
-    for (int t = 0; t < 3; ++t) {
-      if (NT * t >= nUb) break;                        // uniform
+    for (int t = 0; t < UB; ++t) {
+      if (NTH * t >= nUb) break;                        // uniform
       const int y = y0 - 1 + u_r[t];
       const bool rok = uact[t] && y >= 0 && y < H;
       umask[t] = 0;
@@ -1929,17 +1937,36 @@ __global__ __launch_bounds__(NT) void conv_grad_kernel(GradArgs a) {
         cvt_store4(&Gt[(4 * g_cg + cc) * PG + g_r * Wp + 4 * g_xg], make_float4(gk[cc][0], gk[cc][1], gk[cc][2], gk[cc][3]));
     }
 #pragma unroll
-    for (int t = 0; t < 3; ++t) {
-      if (NT * t >= nUb) break;                        // uniform
-      if (!uact[t]) continue;
+    for (int t = 0; t < UB; ++t) {
+      if (NTH * t >= nUb) break;                        // uniform
       float uk[4][4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const bool ok = (umask[t] >> j) & 1u;
+        const bool ok = uact[t] && ((umask[t] >> j) & 1u);
         uk[0][j] = ok ? uv[t][j].x : 0.0f; uk[1][j] = ok ? uv[t][j].y : 0.0f;
         uk[2][j] = ok ? uv[t][j].z : 0.0f; uk[3][j] = ok ? uv[t][j].w : 0.0f;
       }
       const int col = 4 * u_xg[t];
+      if (lane_shift) {
+        // The x groups of an image row sit in consecutive lanes of one wavefront (XG divides 64): the pixel left of
+        // this thread's four comes from lane - 1 and the one right of them from lane + 1 (zero at the row's ends),
+        // so each of the three copies is one aligned 8- or 16-byte store per channel instead of four 2- or 4-byte ones.
+        // Every lane takes part in the exchange; only threads that own a block store.
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) {
+          float left = __shfl_up(uk[cc][3], 1), right = __shfl_down(uk[cc][0], 1);
+          if (u_xg[t] == 0) left = 0.0f;
+          if (u_xg[t] == XG - 1) right = 0.0f;
+          if (uact[t]) {
+            const int i = 4 * u_cg[t] + cc;
+            cvt_store4(Ut + (0 * C + i) * PU + u_r[t] * Wp + col, make_float4(left, uk[cc][0], uk[cc][1], uk[cc][2]));
+            cvt_store4(Ut + (1 * C + i) * PU + u_r[t] * Wp + col, make_float4(uk[cc][0], uk[cc][1], uk[cc][2], uk[cc][3]));
+            cvt_store4(Ut + (2 * C + i) * PU + u_r[t] * Wp + col, make_float4(uk[cc][1], uk[cc][2], uk[cc][3], right));
+          }
+        }
+        continue;
+      }
+      if (!uact[t]) continue;
 #pragma unroll
       for (int cc = 0; cc < 4; ++cc) {
         const int i = 4 * u_cg[t] + cc;
@@ -1968,7 +1995,7 @@ __global__ __launch_bounds__(NT) void conv_grad_kernel(GradArgs a) {
   for (int i = 0; i < TM; ++i) arow[i] = Gt + min(BW * i + bl, C - 1) * PG;
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
-    const int n = min(BW * (wave + 4 * j) + bl, 9 * C);
+    const int n = min(BW * (wave + NWV * j) + bl, 9 * C);
     const int tap = n / C, ii = n % C;
     brow[j] = n == 9 * C ? ones : Ut + ((tap % 3) * C + ii) * PU + (tap / 3) * Wp;
   }
@@ -2023,7 +2050,7 @@ __global__ __launch_bounds__(NT) void conv_grad_kernel(GradArgs a) {
     // register v of lane (bl, kq) holds row o = 4 kq + v, column n = 16 (wave + 4 j) + bl of the block
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-      const int n = 16 * (wave + 4 * j) + bl;
+      const int n = 16 * (wave + NWV * j) + bl;
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
         const int o = 4 * kq + v;
@@ -2038,7 +2065,7 @@ __global__ __launch_bounds__(NT) void conv_grad_kernel(GradArgs a) {
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
-        const int n = 32 * (wave + 4 * j) + c;
+        const int n = 32 * (wave + NWV * j) + c;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int o = 32 * i + 8 * (r >> 2) + 4 * g + (r & 3);
@@ -2096,8 +2123,15 @@ __global__ __launch_bounds__(NT) void bias_grad_kernel(GradArgs a) {
   }
 }
 
+// wavefronts of the all-taps gradient kernel: eight for more than 32 channels (MGRIT_CGRAD_WAVES=4: always four)
+int conv_grad_waves(int C) {
+  const char* e = getenv("MGRIT_CGRAD_WAVES");
+  if (e && e[0] == '4') return 4;
+  return C > 32 ? 8 : 4;
+}
 ConvGradGeom conv_grad_geom(int B, int Himg, int Wimg, int C, int dtype, int layers) {
   ConvGradGeom gm = {};
+  const int nth = 64 * conv_grad_waves(C);
   const int es = dtype == 0 ? 4 : 2, pad = dtype == 0 ? Op<float>::PAD : Op<__bf16>::PAD;
   const int kstep = (dtype == 0 && C <= 16) ? 16 : dtype == 0 ? Op<float>::KSTEP : Op<__bf16>::KSTEP;   // as conv_grad_n16
   gm.Wp = (Wimg + 7) & ~7;
@@ -2112,9 +2146,10 @@ ConvGradGeom conv_grad_geom(int B, int Himg, int Wimg, int C, int dtype, int lay
   };
   int Rmin = 64 / gm.Wp;
   if (Rmin < 1) Rmin = 1;
-  int R = 256 / (bpr > 0 ? bpr : 1);
+  int R = nth / (bpr > 0 ? bpr : 1);
   if (R < Rmin) R = Rmin;
-  while (R > Rmin && ((R + 2) * bpr > 768 || smem_of(R) > (size_t)72 * 1024)) --R;
+  const size_t lds_cap = (size_t)(nth == 256 ? 72 : 150) * 1024;   // two workgroups per CU, or one of eight wavefronts
+  while (R > Rmin && ((R + 2) * bpr > (nth == 256 ? 3 : 2) * nth || smem_of(R) > lds_cap)) --R;
   if (R > Himg) R = Himg;
   R = (Himg + (Himg + R - 1) / R - 1) / ((Himg + R - 1) / R);         // the same number of slabs, of balanced height
   gm.R = R;
@@ -2144,14 +2179,14 @@ static void launch_bias_grad(const GradArgs& a, int dtype, int groups, hipStream
   if (dtype == 0) hipLaunchKernelGGL((bias_grad_kernel<float>), grid, dim3(NT), 0, s, a);
   else            hipLaunchKernelGGL((bias_grad_kernel<__bf16>), grid, dim3(NT), 0, s, a);
 }
-template <typename OT, int TM, int TN, bool N16 = false>
+template <typename OT, int TM, int TN, bool N16 = false, int NWV = 4>
 static hipError_t launch_conv_grad(const GradArgs& a, unsigned blocks, size_t smem, hipStream_t s) {
   if (smem > 64 * 1024) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_grad_kernel<OT, TM, TN, N16>),
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_grad_kernel<OT, TM, TN, N16, NWV>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL((conv_grad_kernel<OT, TM, TN, N16>), dim3(blocks), dim3(NT), smem, s, a);
+  hipLaunchKernelGGL((conv_grad_kernel<OT, TM, TN, N16, NWV>), dim3(blocks), dim3(64 * NWV), smem, s, a);
   return hipGetLastError();
 }
 
@@ -2673,7 +2708,8 @@ hipError_t launch_grad(const GradArgs& a_in, int layer_kind, int dtype, int grou
       a.gspi = gm.spi; a.gslabs = gm.slabs; a.gchunks = gm.chunks; a.gspc = gm.spc;
       a.tiles = gm.chunks;
       const bool n16 = dtype == 0 && a.Nf <= 16;            // 16x16x4 blocks (8 or 16 float channels)
-      const int tm = a.Nf > 32 ? 2 : 1, tn = n16 ? ((9 * a.Nf + 1 + 15) / 16 + 3) / 4 : ((9 * a.Nf + 1 + 31) / 32 + 3) / 4;
+      const int nwv = conv_grad_waves(a.Nf);
+      const int tm = a.Nf > 32 ? 2 : 1, tn = n16 ? ((9 * a.Nf + 1 + 15) / 16 + 3) / 4 : ((9 * a.Nf + 1 + 31) / 32 + nwv - 1) / nwv;
       hipError_t e = hipErrorInvalidValue;                 // also the result if the partial-sum buffer is missing
       const unsigned blocks = (unsigned)gm.chunks * (unsigned)groups;
       const bool have_buf = gm.chunks == 1 || a.partial != nullptr;
@@ -2684,8 +2720,13 @@ hipError_t launch_grad(const GradArgs& a_in, int layer_kind, int dtype, int grou
       if (have_buf && tm == TM_ && tn == TN_)                                                                   \
         e = dtype == 0 ? launch_conv_grad<float, TM_, TN_>(a, blocks, gm.smem, s)                               \
                        : launch_conv_grad<__bf16, TM_, TN_>(a, blocks, gm.smem, s);
-      MGRIT_CG(1, 1) MGRIT_CG(1, 2) MGRIT_CG(1, 3) MGRIT_CG(2, 3) MGRIT_CG(2, 4) MGRIT_CG(2, 5)
+      if (nwv == 4) { MGRIT_CG(1, 1) MGRIT_CG(1, 2) MGRIT_CG(1, 3) MGRIT_CG(2, 3) MGRIT_CG(2, 4) MGRIT_CG(2, 5) }
 #undef MGRIT_CG
+      // eight wavefronts (33 .. 64 channels: 10 .. 19 column blocks of 32, two or three per wavefront)
+      if (have_buf && nwv == 8 && tn == 2)
+        e = dtype == 0 ? launch_conv_grad<float, 2, 2, false, 8>(a, blocks, gm.smem, s) : launch_conv_grad<__bf16, 2, 2, false, 8>(a, blocks, gm.smem, s);
+      if (have_buf && nwv == 8 && tn == 3)
+        e = dtype == 0 ? launch_conv_grad<float, 2, 3, false, 8>(a, blocks, gm.smem, s) : launch_conv_grad<__bf16, 2, 3, false, 8>(a, blocks, gm.smem, s);
       }
       if (e != hipSuccess) { trace_after(s, TRACE_GRAD, groups, 0.0); return e; }
       if (gm.chunks > 1) {

@@ -164,6 +164,31 @@ def test_conv_bf16_64_channels_fixed_and_generic_kernel(monkeypatch):
     assert eU <= tol and eL <= tol and eW <= tol, (eU, eL, eW)
 
 
+# The all-taps parameter gradient of layers with more than 32 channels runs with eight wavefronts and taller slabs
+# (MGRIT_CGRAD_WAVES=4: four, as for narrower layers); image widths whose 4-pixel groups divide 64 build the shifted
+# patch copies by lane exchange (32 and 8 columns here), others element by element (12 columns).
+@pytest.mark.parametrize("waves", ["8", "4"])
+@pytest.mark.parametrize("shape", [(32, 32, 2), (5, 8, 3), (20, 12, 2)], ids=lambda s: "%dx%d" % (s[0], s[1]))
+def test_conv_gradient_64_channels_wavefront_forms(shape, waves, monkeypatch):
+    if waves == "4":
+        monkeypatch.setenv("MGRIT_CGRAD_WAVES", "4")
+    H, Wd, B = shape
+    wl = I.reduced(I.cfg4(1), name=f"cgrad_bf16_c64_{H}x{Wd}_B{B}_N8_w{waves}", B=B, Himg=H, Wimg=Wd, N=8, m=2, max_levels=2,
+                   act=I.TANH)
+    _announce(wl.name)
+    data = I.generate(wl)
+    Uo, _, _ = oracle_forward(wl, data, max_iter=2)
+    U = Uo.astype(np.float32)
+    lamN = np.random.default_rng(11).standard_normal(wl.state_shape).astype(np.float32)
+    gp = GpuProblem(wl, data)
+    Lam, dW, db, _, _ = gp.adjoint(U, lamN)
+    Lo, dWo, dbo, _, _ = oracle_adjoint(wl, data, U, lamN)
+    tol = TOL[wl.dtype]
+    eL, eW, eb = rel_l2_per_state(Lam, Lo), rel_l2_per_state(dW, dWo), rel_l2_per_state(db, dbo)
+    print(f"{wl.name}: Lam {eL:.3e} dW {eW:.3e} db {eb:.3e}", flush=True)
+    assert eL <= tol and eW <= tol and eb <= tol, (eL, eW, eb)
+
+
 # ------------------------------------------------------------------ options of the boundary
 def test_init_modes_and_user_guess():
     for q in (24, 128):
