@@ -182,6 +182,19 @@ __device__ __forceinline__ float act_prime(float z, int act) {
   if (act == ACT_RELU) return z > 0.0f ? 1.0f : 0.0f;
   return 1.0f;
 }
+// The same with the activation as a compile-time value: the epilogues of the tiled kernels branch on it once
+// per workgroup instead of once per element (a chain of scalar compares and branches around every one of a
+// lane's 64 output values took longer than their arithmetic).
+template <int ACT> __device__ __forceinline__ float act_fn_c(float z) {
+  if (ACT == ACT_TANH) return fast_tanh(z);
+  if (ACT == ACT_RELU) return fmaxf(z, 0.0f);
+  return z;
+}
+template <int ACT> __device__ __forceinline__ float act_prime_c(float z) {
+  if (ACT == ACT_TANH) { float t = fast_tanh(z); return 1.0f - t * t; }
+  if (ACT == ACT_RELU) return z > 0.0f ? 1.0f : 0.0f;
+  return 1.0f;
+}
 
 __device__ __forceinline__ float block_sum(float v, float* red) {
 #pragma unroll
@@ -237,8 +250,8 @@ __device__ __forceinline__ EpiPtrs epi_ptrs(const StepArgs& a, int gi, long long
 // loads its input tile in exactly this arrangement).
 // `stage_block(tm, stage)` writes the wavefront's accumulators of block row tm (32 rows x CW columns) to
 // `stage` with row stride CW + 4; it is the only part that depends on the MFMA shape.
-template <int TM, int CW, bool XREG, int NX, typename StageFn>
-__device__ __forceinline__ void epilogue_rows(const StepArgs& a, int gi, long long layer, StageFn stage_block,
+template <int ACT, int TM, int CW, bool XREG, int NX, typename StageFn>
+__device__ __forceinline__ void epilogue_rows_act(const StepArgs& a, int gi, long long layer, StageFn stage_block,
                                               const long long (&row0)[TM], long long row_end, int colbase, int L,
                                               float* red, float* stage_all, const float4 (&xreg)[NX]) {
   constexpr int SW = CW + 4;                 // staging row stride in floats
@@ -298,13 +311,13 @@ __device__ __forceinline__ void epilogue_rows(const StepArgs& a, int gi, long lo
       for (int i = 0; i < HB; ++i) {
         float4 o;
         if (dact) {
-          o.x = act_prime(z[i].x + bv.x, a.act); o.y = act_prime(z[i].y + bv.y, a.act);
-          o.z = act_prime(z[i].z + bv.z, a.act); o.w = act_prime(z[i].w + bv.w, a.act);
+          o.x = act_prime_c<ACT>(z[i].x + bv.x); o.y = act_prime_c<ACT>(z[i].y + bv.y);
+          o.z = act_prime_c<ACT>(z[i].z + bv.z); o.w = act_prime_c<ACT>(z[i].w + bv.w);
         } else {
-          o.x = a.sp * (xv[i].x + a.hs * act_fn(z[i].x + bv.x, a.act)) + a.c1 * e1[i].x + a.c2 * e2[i].x;
-          o.y = a.sp * (xv[i].y + a.hs * act_fn(z[i].y + bv.y, a.act)) + a.c1 * e1[i].y + a.c2 * e2[i].y;
-          o.z = a.sp * (xv[i].z + a.hs * act_fn(z[i].z + bv.z, a.act)) + a.c1 * e1[i].z + a.c2 * e2[i].z;
-          o.w = a.sp * (xv[i].w + a.hs * act_fn(z[i].w + bv.w, a.act)) + a.c1 * e1[i].w + a.c2 * e2[i].w;
+          o.x = a.sp * (xv[i].x + a.hs * act_fn_c<ACT>(z[i].x + bv.x)) + a.c1 * e1[i].x + a.c2 * e2[i].x;
+          o.y = a.sp * (xv[i].y + a.hs * act_fn_c<ACT>(z[i].y + bv.y)) + a.c1 * e1[i].y + a.c2 * e2[i].y;
+          o.z = a.sp * (xv[i].z + a.hs * act_fn_c<ACT>(z[i].z + bv.z)) + a.c1 * e1[i].z + a.c2 * e2[i].z;
+          o.w = a.sp * (xv[i].w + a.hs * act_fn_c<ACT>(z[i].w + bv.w)) + a.c1 * e1[i].w + a.c2 * e2[i].w;
         }
         xv[i] = o;
       }
@@ -328,6 +341,15 @@ __device__ __forceinline__ void epilogue_rows(const StepArgs& a, int gi, long lo
     const float s = block_sum(sq, red);
     if (threadIdx.x == 0) a.norm_partial[L] = s;
   }
+}
+
+template <int TM, int CW, bool XREG, int NX, typename StageFn>
+__device__ __forceinline__ void epilogue_rows(const StepArgs& a, int gi, long long layer, StageFn stage_block,
+                                              const long long (&row0)[TM], long long row_end, int colbase, int L,
+                                              float* red, float* stage_all, const float4 (&xreg)[NX]) {
+  if (a.act == ACT_TANH)      epilogue_rows_act<ACT_TANH, TM, CW, XREG, NX>(a, gi, layer, stage_block, row0, row_end, colbase, L, red, stage_all, xreg);
+  else if (a.act == ACT_RELU) epilogue_rows_act<ACT_RELU, TM, CW, XREG, NX>(a, gi, layer, stage_block, row0, row_end, colbase, L, red, stage_all, xreg);
+  else                        epilogue_rows_act<ACT_IDENT, TM, CW, XREG, NX>(a, gi, layer, stage_block, row0, row_end, colbase, L, red, stage_all, xreg);
 }
 
 // 32x32 MFMA blocks: register r of a lane holds row 8 (r / 4) + 4 g + r % 4, column c of the block
@@ -536,6 +558,8 @@ __global__ __launch_bounds__(64 * WR * WC, WR * WC == 8 ? 4 : 1) void dense_step
     const int rq = tid / (BK / 4), cq = (tid % (BK / 4)) * 4;
     const bool dact = a.mode == MODE_DACT;
     float sq = 0.0f;
+    auto tile_rows = [&](auto actc) {
+    constexpr int ACT = decltype(actc)::value;
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
       const int col = n0 + half * BK + cq;
@@ -573,13 +597,13 @@ __global__ __launch_bounds__(64 * WR * WC, WR * WC == 8 ? 4 : 1) void dense_step
           const float4 xv = xown[half][XR ? h0 + u : 0];
           float4 o;
           if (dact) {
-            o.x = act_prime(z[u].x + bv.x, a.act); o.y = act_prime(z[u].y + bv.y, a.act);
-            o.z = act_prime(z[u].z + bv.z, a.act); o.w = act_prime(z[u].w + bv.w, a.act);
+            o.x = act_prime_c<ACT>(z[u].x + bv.x); o.y = act_prime_c<ACT>(z[u].y + bv.y);
+            o.z = act_prime_c<ACT>(z[u].z + bv.z); o.w = act_prime_c<ACT>(z[u].w + bv.w);
           } else {
-            o.x = a.sp * (xv.x + a.hs * act_fn(z[u].x + bv.x, a.act)) + a.c1 * e1[u].x + a.c2 * e2[u].x;
-            o.y = a.sp * (xv.y + a.hs * act_fn(z[u].y + bv.y, a.act)) + a.c1 * e1[u].y + a.c2 * e2[u].y;
-            o.z = a.sp * (xv.z + a.hs * act_fn(z[u].z + bv.z, a.act)) + a.c1 * e1[u].z + a.c2 * e2[u].z;
-            o.w = a.sp * (xv.w + a.hs * act_fn(z[u].w + bv.w, a.act)) + a.c1 * e1[u].w + a.c2 * e2[u].w;
+            o.x = a.sp * (xv.x + a.hs * act_fn_c<ACT>(z[u].x + bv.x)) + a.c1 * e1[u].x + a.c2 * e2[u].x;
+            o.y = a.sp * (xv.y + a.hs * act_fn_c<ACT>(z[u].y + bv.y)) + a.c1 * e1[u].y + a.c2 * e2[u].y;
+            o.z = a.sp * (xv.z + a.hs * act_fn_c<ACT>(z[u].z + bv.z)) + a.c1 * e1[u].z + a.c2 * e2[u].z;
+            o.w = a.sp * (xv.w + a.hs * act_fn_c<ACT>(z[u].w + bv.w)) + a.c1 * e1[u].w + a.c2 * e2[u].w;
           }
           if (dact && a.dbf16) {
             __bf16* ob = reinterpret_cast<__bf16*>(a.Out) + (a.om.base + gi * a.om.stride) * a.E;
@@ -591,6 +615,10 @@ __global__ __launch_bounds__(64 * WR * WC, WR * WC == 8 ? 4 : 1) void dense_step
         }
       }
     }
+    };
+    if (a.act == ACT_TANH)      tile_rows(std::integral_constant<int, ACT_TANH>{});
+    else if (a.act == ACT_RELU) tile_rows(std::integral_constant<int, ACT_RELU>{});
+    else                        tile_rows(std::integral_constant<int, ACT_IDENT>{});
     if (a.norm_partial) {
       const float sum = block_sum(sq, red);
       if (threadIdx.x == 0) a.norm_partial[L] = sum;
@@ -806,7 +834,7 @@ __device__ __forceinline__ int div_small(int p, unsigned magic) { return (int)((
 // the weight pieces need neither masks nor divisions -- with bf16 matrix instructions a tap is 16 of them per
 // wavefront, and a rolled k loop that waits for every fragment read takes several times as long.
 template <typename WT, int TN, bool N16 = false, int CFIX = 0>
-__global__ __launch_bounds__(NT) void conv_step_kernel(StepArgs a) {
+__global__ __launch_bounds__(NT, 2) void conv_step_kernel(StepArgs a) {   // two workgroups per CU: at most 256 registers
   static_assert(!N16 || (sizeof(WT) == 4 && TN == 1), "the 16-wide variant is float only");
   static_assert(CFIX == 0 || (!N16 && CFIX == 32 * TN && CFIX % Op<WT>::KSTEP == 0), "fixed channel count = output columns");
   constexpr int VEC = Op<WT>::VEC, KSTEP = N16 ? 16 : Op<WT>::KSTEP, PAD = Op<WT>::PAD;
