@@ -2377,6 +2377,9 @@ __global__ __launch_bounds__(64 * NWV) void dense_sweep_kernel(SweepArgs a) {
       float* xo = a.X + (a.xb + ci * a.xs + (long long)k * a.xk) * a.E + slice_off;
       const bool build = k < a.nsteps;
       const WT* dp = (Dall && build) ? Dall + layer_of(k + 1) * a.E + slice_off : nullptr;
+      // (the activation as a compile-time value inside the pass: one branch per step, not four per float4)
+      auto update_pass = [&](auto actc) {
+      constexpr int ACT = decltype(actc)::value;
 #pragma unroll
       for (int i = 0; i < R * Q4 / NT; ++i) {
         const int row = (tid + NT * i) / Q4;
@@ -2384,8 +2387,8 @@ __global__ __launch_bounds__(64 * NWV) void dense_sweep_kernel(SweepArgs a) {
         const int off = ok ? row * Q + c4t : 0;
         const float4 z = *reinterpret_cast<const float4*>(Z + row * ZST + c4t);
         float4 u = *reinterpret_cast<const float4*>(S + row * Q + c4t);
-        u.x += a.hs * act_fn(z.x + bv.x, a.act); u.y += a.hs * act_fn(z.y + bv.y, a.act);
-        u.z += a.hs * act_fn(z.z + bv.z, a.act); u.w += a.hs * act_fn(z.w + bv.w, a.act);
+        u.x += a.hs * act_fn_c<ACT>(z.x + bv.x); u.y += a.hs * act_fn_c<ACT>(z.y + bv.y);
+        u.z += a.hs * act_fn_c<ACT>(z.z + bv.z); u.w += a.hs * act_fn_c<ACT>(z.w + bv.w);
         if (gp) {
           const float4 gv = *reinterpret_cast<const float4*>(gp + off);
           u.x += gv.x; u.y += gv.y; u.z += gv.z; u.w += gv.w;
@@ -2401,6 +2404,10 @@ __global__ __launch_bounds__(64 * NWV) void dense_sweep_kernel(SweepArgs a) {
           cvt_store4(&A[row * AST + c4t], u);
         }
       }
+      };
+      if (a.act == ACT_TANH)      update_pass(std::integral_constant<int, ACT_TANH>{});
+      else if (a.act == ACT_RELU) update_pass(std::integral_constant<int, ACT_RELU>{});
+      else                        update_pass(std::integral_constant<int, ACT_IDENT>{});
     }
     __syncthreads();                                       // next operand complete; the sums' buffer is free again
   }
@@ -2485,6 +2492,7 @@ bool conv_sweep_supported(int Himg, int Wimg, int C, int dtype) {
   return conv_sweep_smem(Himg, Wimg) <= (size_t)150 * 1024;
 }
 
+template <int ACT>          // the activation as a compile-time value (one branch per launch, not per state value)
 __global__ __launch_bounds__(CSW_NT) void conv_sweep_kernel(SweepArgs a, unsigned wmagic) {
   constexpr int NT = CSW_NT;                                 // shadows the file-wide 256
   constexpr int CS = CSW_CS;
@@ -2636,7 +2644,7 @@ __global__ __launch_bounds__(CSW_NT) void conv_sweep_kernel(SweepArgs a, unsigne
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
           const int pv = (blk0 + 8 * i) * 16 + 4 * kq + v;
-          if ((FULL || i < nv) && pv < HW && r16 < C) St[pv * CS + r16] = sv[i][v] + a.hs * act_fn(acc[i][v] + bo, a.act);
+          if ((FULL || i < nv) && pv < HW && r16 < C) St[pv * CS + r16] = sv[i][v] + a.hs * act_fn_c<ACT>(acc[i][v] + bo);
         }
     };
     for (int blk0 = wave; blk0 < nblk; blk0 += 32) {
@@ -2674,16 +2682,21 @@ hipError_t launch_conv_sweep(const SweepArgs& a, hipStream_t s) {
   if (a.nchains <= 0 || a.nsteps <= 0) return hipSuccess;
   if (!conv_sweep_supported(a.Himg, a.Wimg, a.C, 0) || a.M < 1) return hipErrorInvalidValue;
   const size_t smem = conv_sweep_smem(a.Himg, a.Wimg);
-  static LdsOptIn opt;
-  if (opt.need(smem)) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_sweep_kernel),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  const int actc = a.act == ACT_TANH ? 0 : a.act == ACT_RELU ? 1 : 2;
+  const void* kfn = actc == 0 ? reinterpret_cast<const void*>(conv_sweep_kernel<ACT_TANH>)
+                  : actc == 1 ? reinterpret_cast<const void*>(conv_sweep_kernel<ACT_RELU>)
+                              : reinterpret_cast<const void*>(conv_sweep_kernel<ACT_IDENT>);
+  static LdsOptIn opt[3];
+  if (opt[actc].need(smem)) {
+    const hipError_t e = hipFuncSetAttribute(kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
   }
   const unsigned blocks = (unsigned)a.M * (unsigned)a.nchains;
   const unsigned wmagic = ((1u << 20) + (unsigned)a.Wimg - 1u) / (unsigned)a.Wimg;
   trace_before(s);
-  hipLaunchKernelGGL(conv_sweep_kernel, dim3(blocks), dim3(CSW_NT), smem, s, a, wmagic);
+  if (actc == 0)      hipLaunchKernelGGL(conv_sweep_kernel<ACT_TANH>, dim3(blocks), dim3(CSW_NT), smem, s, a, wmagic);
+  else if (actc == 1) hipLaunchKernelGGL(conv_sweep_kernel<ACT_RELU>, dim3(blocks), dim3(CSW_NT), smem, s, a, wmagic);
+  else                hipLaunchKernelGGL(conv_sweep_kernel<ACT_IDENT>, dim3(blocks), dim3(CSW_NT), smem, s, a, wmagic);
   const hipError_t e = hipGetLastError();
   // algorithmic bytes per layer step: weights and bias, the act' factor, the right-hand side, the state out
   // (the state in is read once per chain)
