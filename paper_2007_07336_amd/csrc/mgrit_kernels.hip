@@ -2599,10 +2599,11 @@ __global__ __launch_bounds__(CSW_NT) void conv_sweep_kernel(SweepArgs a, unsigne
 #pragma unroll
     for (int tap = 0; tap < 9; ++tap) bf[tap] = *reinterpret_cast<const float4*>(Wt + (tap * 16 + r16) * CS + 4 * kq);
     // four blocks at a time: their accumulators are independent, so consecutive matrix instructions never
-    // wait for each other.  nv = blocks of the group inside the image (the same for all lanes of the wavefront).
-    auto group = [&](int blk0, auto full) {
-      constexpr bool FULL = decltype(full)::value;
-      const int nv = FULL ? 4 : (nblk - blk0 + 7) / 8;
+    // wait for each other.
+    // (NV, the number of blocks of the group inside the image, is a compile-time value: a run-time count put a
+    // compare and a branch around every matrix instruction of the image's last group)
+    auto group = [&](int blk0, auto nvc) {
+      constexpr int NV = decltype(nvc)::value;
       const float* ap[4];
       floatx4 acc[4];
 #pragma unroll
@@ -2618,15 +2619,15 @@ __global__ __launch_bounds__(CSW_NT) void conv_sweep_kernel(SweepArgs a, unsigne
         const int toff = ((tap / 3) * PW + (tap % 3)) * CS;
         float4 af[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) if (FULL || i < nv) af[i] = *reinterpret_cast<const float4*>(ap[i] + toff);
+        for (int i = 0; i < 4; ++i) if (i < NV) af[i] = *reinterpret_cast<const float4*>(ap[i] + toff);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) if (FULL || i < nv) acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[i].x, bf[tap].x, acc[i], 0, 0, 0);
+        for (int i = 0; i < 4; ++i) if (i < NV) acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[i].x, bf[tap].x, acc[i], 0, 0, 0);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) if (FULL || i < nv) acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[i].y, bf[tap].y, acc[i], 0, 0, 0);
+        for (int i = 0; i < 4; ++i) if (i < NV) acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[i].y, bf[tap].y, acc[i], 0, 0, 0);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) if (FULL || i < nv) acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[i].z, bf[tap].z, acc[i], 0, 0, 0);
+        for (int i = 0; i < 4; ++i) if (i < NV) acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[i].z, bf[tap].z, acc[i], 0, 0, 0);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) if (FULL || i < nv) acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[i].w, bf[tap].w, acc[i], 0, 0, 0);
+        for (int i = 0; i < 4; ++i) if (i < NV) acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[i].w, bf[tap].w, acc[i], 0, 0, 0);
       }
       // register v of a lane holds pixel 4 kq + v of the block, output channel r16.  All sixteen state values
       // are read before the first is written back (written as one read-modify-write each, every read would wait
@@ -2637,19 +2638,22 @@ __global__ __launch_bounds__(CSW_NT) void conv_sweep_kernel(SweepArgs a, unsigne
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
           const int pv = (blk0 + 8 * i) * 16 + 4 * kq + v;   // >= HW past the image
-          sv[i][v] = St[(pv < HW ? pv : 0) * CS + r16];
+          if (i < NV) sv[i][v] = St[(pv < HW ? pv : 0) * CS + r16];
         }
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
           const int pv = (blk0 + 8 * i) * 16 + 4 * kq + v;
-          if ((FULL || i < nv) && pv < HW && r16 < C) St[pv * CS + r16] = sv[i][v] + a.hs * act_fn_c<ACT>(acc[i][v] + bo);
+          if (i < NV && pv < HW && r16 < C) St[pv * CS + r16] = sv[i][v] + a.hs * act_fn_c<ACT>(acc[i][v] + bo);
         }
     };
     for (int blk0 = wave; blk0 < nblk; blk0 += 32) {
-      if (blk0 + 24 < nblk) group(blk0, std::true_type());
-      else group(blk0, std::false_type());
+      const int nv = (nblk - blk0 + 7) / 8;                  // the same for all lanes of the wavefront
+      if (nv >= 4)      group(blk0, std::integral_constant<int, 4>{});
+      else if (nv == 3) group(blk0, std::integral_constant<int, 3>{});
+      else if (nv == 2) group(blk0, std::integral_constant<int, 2>{});
+      else              group(blk0, std::integral_constant<int, 1>{});
     }
     __syncthreads();                                         // every block is done with P and has updated St
     {
