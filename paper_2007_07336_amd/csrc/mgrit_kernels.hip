@@ -1048,21 +1048,32 @@ __global__ __launch_bounds__(NT, 2) void conv_step_kernel(StepArgs a) {   // two
     if (wave_active) {
       const float* pf = reinterpret_cast<const float*>(patch);
       const float* wf = reinterpret_cast<const float*>(wts);
+      // NB of this wavefront's four 16-pixel blocks hold pixels of the tile (a compile-time value inside the tap
+      // loop: a tile of 7 x 28 pixels leaves the last wavefront one block of four, and its three empty ones would
+      // take matrix-core time from the other workgroups on the SIMD)
+      auto taps = [&](auto nbc) {
+        constexpr int NB = decltype(nbc)::value;
 #pragma unroll
-      for (int tap = 0; tap < 9; ++tap) {
-        const int toff = ((tap / 3) * PW + (tap % 3)) * CS;
-        // lane (r16, kq) feeds k = 4 kq .. + 3, one value per instruction (any fixed pairing of the lanes'
-        // k values is a valid order of the sum)
-        const float4 bf = *reinterpret_cast<const float4*>(wf + (tap * 16 + r16) * CS + 4 * kq);
+        for (int tap = 0; tap < 9; ++tap) {
+          const int toff = ((tap / 3) * PW + (tap % 3)) * CS;
+          // lane (r16, kq) feeds k = 4 kq .. + 3, one value per instruction (any fixed pairing of the lanes'
+          // k values is a valid order of the sum)
+          const float4 bf = *reinterpret_cast<const float4*>(wf + (tap * 16 + r16) * CS + 4 * kq);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const float4 af = *reinterpret_cast<const float4*>(pf + aoff[i] + toff + 4 * kq);
-          acc16[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.x, bf.x, acc16[i], 0, 0, 0);
-          acc16[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.y, bf.y, acc16[i], 0, 0, 0);
-          acc16[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.z, bf.z, acc16[i], 0, 0, 0);
-          acc16[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.w, bf.w, acc16[i], 0, 0, 0);
+          for (int i = 0; i < NB; ++i) {
+            const float4 af = *reinterpret_cast<const float4*>(pf + aoff[i] + toff + 4 * kq);
+            acc16[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.x, bf.x, acc16[i], 0, 0, 0);
+            acc16[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.y, bf.y, acc16[i], 0, 0, 0);
+            acc16[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.z, bf.z, acc16[i], 0, 0, 0);
+            acc16[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.w, bf.w, acc16[i], 0, 0, 0);
+          }
         }
-      }
+      };
+      const int nb = (npx - wave * 64 + 15) >> 4;            // >= 1 here; uniform
+      if (nb >= 4)      taps(std::integral_constant<int, 4>{});
+      else if (nb == 3) taps(std::integral_constant<int, 3>{});
+      else if (nb == 2) taps(std::integral_constant<int, 2>{});
+      else              taps(std::integral_constant<int, 1>{});
     }
   } else {
     WT* wbuf[2] = {wts, wts + CW * CS};
