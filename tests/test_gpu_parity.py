@@ -521,6 +521,8 @@ WHOLE_TILE_CASES = [
     I.reduced(I.cfg5(1), name="whole_bf16_q512_B256_N16_m4", q=512, B=256, N=16, m=4, max_levels=2),
     I.reduced(I.cfg5(1), name="whole_fp32_q512_B128_N16_m4", q=512, B=128, N=16, m=4, max_levels=2, dtype=I.FP32),
     I.reduced(I.cfg5(1), name="whole_bf16_q192_B64_N64_m4", q=192, B=64, N=64, m=4, max_levels=2),
+    # a single 128x128 tile per group (both kept state slabs are the only two of the contraction), 256 groups
+    I.reduced(I.cfg5(1), name="whole_bf16_q128_B128_N512_m2", q=128, B=128, N=512, m=2, max_levels=2),
 ]
 
 
