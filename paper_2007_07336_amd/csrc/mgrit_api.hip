@@ -155,6 +155,7 @@ struct Solver {
   float* R[MGRIT_MAX_LEVELS];
   bool plain_rhs = false;              // nested start: every level carries the right-hand side (first, 0, .., 0)
   const void* W;
+  const void* Wu = nullptr;            // adjoint of dense layers: the caller's weights as stored (W above is the transposed copy)
   const float* bias;
   const float* Dm;
   const void* Wfc = nullptr;           // fully connected layers of a mixed stack (their transposes in the adjoint)
@@ -178,7 +179,7 @@ struct Solver {
   StepArgs base_args(int l, long long js0, long long jstride) const {
     StepArgs a;
     memset(&a, 0, sizeof(a));
-    a.W = W; a.bias = bias; a.wm = layer_map(l, js0, jstride);
+    a.W = W; a.Wu = Wu; a.bias = bias; a.wm = layer_map(l, js0, jstride);
     a.Dm = Dm; a.dm = a.wm;
     a.sp = 1.0f; a.hs = pl.hl[l]; a.mode = MODE_PHI; a.act = act;
     a.M = pl.M; a.Nf = pl.Nf; a.K = pl.K; a.Himg = p->Himg; a.Wimg = p->Wimg; a.TH = pl.TH;
@@ -212,7 +213,7 @@ struct Solver {
     StepArgs d = a;
     d.xm = sub(a.xm); d.dm = sub(a.dm); d.om = sub(a.om); d.e1m = sub(a.e1m); d.e2m = sub(a.e2m);
     d.wm = PtMap{(a.wm.base + g0 * a.wm.stride) / pl.fcP, a.wm.stride * per / pl.fcP};
-    d.W = Wfc; d.bias = a.bias ? bfc : nullptr;
+    d.W = Wfc; d.Wu = nullptr; d.bias = a.bias ? bfc : nullptr;
     d.M = pl.B; d.Nf = (int)pl.dfc; d.K = (int)pl.dfc; d.Himg = 0; d.Wimg = 0; d.TH = 0;
     d.wsize = pl.wsize_fc;
     d.wstream = (double)pl.nfc * (double)pl.wsize_fc * (double)pl.esize > 128.0 * 1024.0 * 1024.0 ? 1 : 0;
@@ -493,6 +494,7 @@ int adjoint_impl(const mgrit_problem_t* p, const mgrit_fc_layers_t* fc, const vo
     sv.launch(a, p->N);
   }
   sv.W = Wt; sv.bias = nullptr; sv.Dm = D; sv.act = ACT_IDENT;
+  sv.Wu = p->layer == MGRIT_LAYER_DENSE ? W : nullptr;
   if (fc) { sv.Wfc = Wfct; sv.bfc = nullptr; }
   rc = run_solver(sv, lamN, resnorm_hist, iters_done);
   if (rc != MGRIT_OK && rc != MGRIT_ERR_NONFINITE) return rc;

@@ -28,6 +28,8 @@ struct StepArgs {
   const float* Dm;  PtMap dm;      // optional elementwise multiplier of the matrix operand (the act' cache);
                                    // its storage type is the weights' type: float, or bf16 when dbf16 is set
   const void*  W;   PtMap wm;      // weights of layer wm(gi); element type = template parameter
+  const void*  Wu;                 // adjoint steps of dense layers: the caller's weights as stored, W[k][n], which the
+                                   // kernels that can read them k-major use instead of the transposed copy in W
   const float* bias;               // [layers][Nf] or null (same layer index as W)
   float* Out;       PtMap om;      // may be null when only the norm is wanted
   const float* E1;  PtMap e1m;  float c1;

@@ -159,6 +159,59 @@ __device__ __forceinline__ void mma_step(const __bf16* const (&ap)[TM], const __
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
 }
 
+// The same with the weight slab k-major in LDS (row = k, pitch BNP, column = output feature), as the adjoint reads
+// W[k][n] untransposed: bk points at row ks of the slab, bcol[j] is this lane's column of block j.
+//   float : one value per lane and matrix instruction, k = ks + 4 g + t for instruction t (the A fragment's pairing)
+//   bf16  : two LDS transpose reads per fragment.  Within each group of 16 lanes, ds_read_b64_tr_b16 hands lane i
+//           element i % 4 of the 8-byte pieces addressed by lanes i / 4, 4 + i / 4, 8 + i / 4, 12 + i / 4; with lane
+//           l of a group pointing at row l / 4, columns 4 (l % 4) .. + 3, lane i receives rows 0..3 of column i.
+typedef short short4v __attribute__((ext_vector_type(4)));
+template <int TM, int TN>
+__device__ __forceinline__ void mma_step_wn(const float* const (&ap)[TM], const float* bk, int BNP, const int (&bcol)[TN],
+                                            floatx16 (&acc)[TM][TN], int g) {
+  float4 a[TM];
+  float b[TN][4];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const float4*>(ap[i] + 4 * g);
+#pragma unroll
+  for (int j = 0; j < TN; ++j)
+#pragma unroll
+    for (int t = 0; t < 4; ++t) b[j][t] = bk[(4 * g + t) * BNP + bcol[j]];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].x, b[j][0], acc[i][j], 0, 0, 0);
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].y, b[j][1], acc[i][j], 0, 0, 0);
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].z, b[j][2], acc[i][j], 0, 0, 0);
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].w, b[j][3], acc[i][j], 0, 0, 0);
+    }
+}
+template <int TM, int TN>
+__device__ __forceinline__ void mma_step_wn(const __bf16* const (&ap)[TM], const __bf16* bk, int BNP, const int (&bcol)[TN],
+                                            floatx16 (&acc)[TM][TN], int g) {
+  bf16x8 a[TM], b[TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const bf16x8*>(ap[i] + 8 * g);
+  const int l16 = threadIdx.x & 15;
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    // bcol[j] = first column of the block + lane % 32; this lane's piece: row 8 g + l16 / 4 (+ 4), columns
+    // (bcol - l16) + 4 (l16 % 4) .. + 3, i.e. the 16-column half its group covers
+    const __bf16* q = bk + (8 * g + (l16 >> 2)) * BNP + (bcol[j] - l16) + 4 * (l16 & 3);
+    typedef __attribute__((address_space(3))) short4v* lds_s4;
+    const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(q));
+    const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(q + 4 * BNP));
+    const bf16x4 l4 = __builtin_bit_cast(bf16x4, lo), h4 = __builtin_bit_cast(bf16x4, hi);
+    b[j] = __builtin_shufflevector(l4, h4, 0, 1, 2, 3, 4, 5, 6, 7);
+  }
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+}
+
 __device__ __forceinline__ floatx16 zero16() {
   floatx16 z;
 #pragma unroll
@@ -383,8 +436,10 @@ __device__ __forceinline__ void epilogue(const StepArgs& a, int gi, long long la
 // output columns are kept in registers when they pass through, as the skip-connection operand of the epilogue, and
 // the epilogue works on the whole 128 x 128 tile in the arrangement of those loads (thread -> 8 rows x 4 columns of
 // each 64-column half), so the state is read from memory once per step instead of twice.
-template <typename WT, int BM, int BN, int WR, int WC, int BK, int PF, bool WS, bool HD = true, bool FULL = false, bool XR = false>
-__global__ __launch_bounds__(64 * WR * WC, WR * WC == 8 ? 4 : 1) void dense_step_kernel(StepArgs a) {
+// WN: the weights are read as stored, W[k][n] (the adjoint's product, Out = G W): the slab sits k-major in LDS
+// and the fragments come from mma_step_wn; otherwise W[n][k] with k fastest (the forward product, Out = X W^T).
+template <typename WT, int BM, int BN, int WR, int WC, int BK, int PF, bool WS, bool HD = true, bool FULL = false, bool XR = false, bool WN = false>
+__global__ __launch_bounds__(64 * WR * WC, WR * WC == 8 ? 4 : (XR && WN) ? 2 : 1) void dense_step_kernel(StepArgs a) {
   constexpr int NTH = 64 * WR * WC;
   constexpr int ST = BK + Op<WT>::PAD, VEC = Op<WT>::VEC, KSTEP = Op<WT>::KSTEP;
   constexpr int TM = BM / WR / 32, TN = BN / WC / 32;
@@ -393,7 +448,9 @@ __global__ __launch_bounds__(64 * WR * WC, WR * WC == 8 ? 4 : 1) void dense_step
   static_assert(AP >= 1 && BP >= 1 && (WR * WC == 4 || WR * WC == 8) && BK % KSTEP == 0, "tile does not fit the workgroup");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   WT* As = reinterpret_cast<WT*>(smem_raw);          // [BM][ST]
-  WT* Bs = As + BM * ST;                             // [BN][ST]
+  constexpr int BNP = BN + (sizeof(WT) == 2 ? 16 : 4);   // WN: pitch of a k row (bf16: 32 bytes modulo 128, conflict-free transpose reads)
+  constexpr int BPR = WN ? BN / VEC : BK / VEC;      // 16-byte pieces per slab row of the weights
+  WT* Bs = As + BM * ST;                             // [BN][ST], or [BK][BNP] with WN
   __shared__ float red[WR * WC];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), g = lane >> 5, c = lane & 31;
@@ -404,7 +461,7 @@ __global__ __launch_bounds__(64 * WR * WC, WR * WC == 8 ? 4 : 1) void dense_step
   const long long layer = a.wm.base + gi * a.wm.stride;
   const float* Xp = a.X + (a.xm.base + gi * a.xm.stride) * a.E;
   const WT* Dp = HD && a.Dm ? reinterpret_cast<const WT*>(a.Dm) + (a.dm.base + gi * a.dm.stride) * a.E : nullptr;
-  const WT* Wp = reinterpret_cast<const WT*>(a.W) + layer * a.wsize;
+  const WT* Wp = reinterpret_cast<const WT*>(WN ? a.Wu : a.W) + layer * a.wsize;
   const int K = a.K;
   typedef typename DRaw<WT>::type DR;
 
@@ -422,8 +479,10 @@ __global__ __launch_bounds__(64 * WR * WC, WR * WC == 8 ? 4 : 1) void dense_step
   // bf16 matrix instructions the masks, selects and 64-bit address arithmetic of the general path take several
   // times as many issue cycles as the multiplications of a slab.
   const unsigned aoff0 = FULL ? (unsigned)((m0 + tid / (BK / 4)) * K + (tid % (BK / 4)) * 4) : 0u;
-  const unsigned boff0 = FULL ? (unsigned)((n0 + tid / (BK / VEC)) * K + (tid % (BK / VEC)) * VEC) : 0u;
-  const unsigned astep = (unsigned)(NTH / (BK / 4)) * (unsigned)K, bstep = (unsigned)(NTH / (BK / VEC)) * (unsigned)K;
+  const unsigned boff0 = !FULL ? 0u : WN ? (unsigned)((tid / BPR) * a.Nf + n0 + (tid % BPR) * VEC)
+                                         : (unsigned)((n0 + tid / BPR) * K + (tid % BPR) * VEC);
+  const unsigned astep = (unsigned)(NTH / (BK / 4)) * (unsigned)K;
+  const unsigned bstep = (unsigned)(NTH / BPR) * (unsigned)(WN ? a.Nf : K);
   const char* Xc = reinterpret_cast<const char*>(Xp);
   const char* Dc = reinterpret_cast<const char*>(Dp);
   const char* Wc = reinterpret_cast<const char*>(Wp);
@@ -437,7 +496,7 @@ __global__ __launch_bounds__(64 * WR * WC, WR * WC == 8 ? 4 : 1) void dense_step
       }
 #pragma unroll
       for (int i = 0; i < BP; ++i) {
-        const unsigned off = boff0 + (unsigned)i * bstep + (unsigned)k0;
+        const unsigned off = boff0 + (unsigned)i * bstep + (WN ? (unsigned)k0 * (unsigned)a.Nf : (unsigned)k0);
         br[i] = ld_weights<WS>(reinterpret_cast<const WT*>(Wc + (unsigned)sizeof(WT) * off));
       }
       return;
@@ -454,9 +513,9 @@ __global__ __launch_bounds__(64 * WR * WC, WR * WC == 8 ? 4 : 1) void dense_step
     }
 #pragma unroll
     for (int i = 0; i < BP; ++i) {
-      const int p = tid + NTH * i, row = p / (BK / VEC), kc = (p % (BK / VEC)) * VEC;
-      const bool ok = n0 + row < a.Nf && k0 + kc < K;
-      const unsigned off = ok ? (unsigned)((n0 + row) * K + k0 + kc) : 0u;
+      const int p = tid + NTH * i, row = p / BPR, kc = (p % BPR) * VEC;     // WN: row = k, kc = column
+      const bool ok = WN ? (k0 + row < K && n0 + kc < a.Nf) : (n0 + row < a.Nf && k0 + kc < K);
+      const unsigned off = !ok ? 0u : WN ? (unsigned)((k0 + row) * a.Nf + n0 + kc) : (unsigned)((n0 + row) * K + k0 + kc);
       bm |= ok ? (1u << i) : 0u;
       br[i] = ld_weights<WS>(Wp + off);
     }
@@ -473,10 +532,10 @@ __global__ __launch_bounds__(64 * WR * WC, WR * WC == 8 ? 4 : 1) void dense_step
     }
 #pragma unroll
     for (int i = 0; i < BP; ++i) {
-      const int p = tid + NTH * i, row = p / (BK / VEC), kc = (p % (BK / VEC)) * VEC;
+      const int p = tid + NTH * i, row = p / BPR, kc = (p % BPR) * VEC;
       uint4 v = br[i];
       if (!FULL && !((bm >> i) & 1u)) v = make_uint4(0, 0, 0, 0);
-      *reinterpret_cast<uint4*>(&Bs[row * ST + kc]) = v;
+      *reinterpret_cast<uint4*>(&Bs[row * (WN ? BNP : ST) + kc]) = v;
     }
   };
 
@@ -529,12 +588,19 @@ __global__ __launch_bounds__(64 * WR * WC, WR * WC == 8 ? 4 : 1) void dense_step
 #pragma unroll
         for (int ks = 0; ks < BK; ks += KSTEP) {
           const WT* ap[TM];
-          const WT* bp[TN];
 #pragma unroll
           for (int i = 0; i < TM; ++i) ap[i] = &As[(wm0 + i * 32 + c) * ST + ks];
+          if constexpr (WN) {
+            int bcol[TN];
 #pragma unroll
-          for (int j = 0; j < TN; ++j) bp[j] = &Bs[(wn0 + j * 32 + c) * ST + ks];
-          mma_step<TM, TN>(ap, bp, acc, g);
+            for (int j = 0; j < TN; ++j) bcol[j] = wn0 + j * 32 + c;
+            mma_step_wn<TM, TN>(ap, Bs + ks * BNP, BNP, bcol, acc, g);
+          } else {
+            const WT* bp[TN];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) bp[j] = &Bs[(wn0 + j * 32 + c) * ST + ks];
+            mma_step<TM, TN>(ap, bp, acc, g);
+          }
         }
       }
     }
@@ -1209,15 +1275,16 @@ static bool step_opt_in(LdsOptIn& opt, const void* kernel, size_t smem) {
   if (e != hipSuccess) { g_step_attr_err = e; opt = LdsOptIn(); return false; }
   return true;
 }
-template <typename WT, int BM, int BN, int BK, int PF, bool WS, int WR, int WC, bool HD, bool FULL, bool XR = false>
+template <typename WT, int BM, int BN, int BK, int PF, bool WS, int WR, int WC, bool HD, bool FULL, bool XR = false, bool WN = false>
 static void launch_dense_k(dim3 grid, hipStream_t s, const StepArgs& a) {
-  constexpr size_t tiles_b = (size_t)(BM + BN) * (BK + Op<WT>::PAD) * sizeof(WT);
+  constexpr size_t bn_rows = (size_t)BN * (BK + Op<WT>::PAD), bk_rows = (size_t)BK * (BN + (sizeof(WT) == 2 ? 16 : 4));
+  constexpr size_t tiles_b = ((size_t)BM * (BK + Op<WT>::PAD) + (WN ? bk_rows : bn_rows)) * sizeof(WT);
   constexpr size_t stage_b = XR ? (size_t)BM * (BN + 4) * sizeof(float)                   // whole-tile epilogue staging
                                 : (size_t)(WR * WC) * 32 * (BN / WC + 4) * sizeof(float);  // per-wavefront staging
   constexpr size_t smem = tiles_b > stage_b ? tiles_b : stage_b;
   static LdsOptIn opt;
-  if (!step_opt_in(opt, reinterpret_cast<const void*>(dense_step_kernel<WT, BM, BN, WR, WC, BK, PF, WS, HD, FULL, XR>), smem)) return;
-  hipLaunchKernelGGL((dense_step_kernel<WT, BM, BN, WR, WC, BK, PF, WS, HD, FULL, XR>), grid, dim3(64 * WR * WC), smem, s, a);
+  if (!step_opt_in(opt, reinterpret_cast<const void*>(dense_step_kernel<WT, BM, BN, WR, WC, BK, PF, WS, HD, FULL, XR, WN>), smem)) return;
+  hipLaunchKernelGGL((dense_step_kernel<WT, BM, BN, WR, WC, BK, PF, WS, HD, FULL, XR, WN>), grid, dim3(64 * WR * WC), smem, s, a);
 }
 // Whole tiles and 32-bit byte offsets within one group's operands: the kernel's unmasked path.
 template <typename WT, int BM, int BN, int BK>
@@ -1236,20 +1303,30 @@ static bool dense_xr(const StepArgs& a) {
   if (e && e[0] == '1') return false;
   return a.K == a.Nf && a.mode != MODE_DACT;
 }
+// MGRIT_ADJ_TRANSPOSED=1: adjoint steps read the transposed weight copy although the caller's weights are at hand
+static bool use_untransposed(const StepArgs& a) {
+  if (!a.Wu) return false;
+  const char* e = getenv("MGRIT_ADJ_TRANSPOSED");
+  return !(e && e[0] == '1');
+}
 template <typename WT, int BM, int BN, int BK, int PF, bool WS, int WR = 2, int WC = 2>
 static void launch_dense_ws(dim3 grid, hipStream_t s, const StepArgs& a) {
+  const bool wn = use_untransposed(a);              // adjoint steps: they all carry the act' operand (HD)
   if (dense_full<WT, BM, BN, BK>(a)) {
     if constexpr (sizeof(WT) == 2 && BM == 128 && BN == 128 && BK == 64 && PF == 1 && WR == 2 && WC == 2) {
       if (dense_xr<WT, BM, BN, BK, PF>(a)) {
-        if (a.Dm) launch_dense_k<WT, BM, BN, BK, PF, WS, WR, WC, true, true, true>(grid, s, a);
-        else      launch_dense_k<WT, BM, BN, BK, PF, WS, WR, WC, false, true, true>(grid, s, a);
+        if (a.Dm && wn) launch_dense_k<WT, BM, BN, BK, PF, WS, WR, WC, true, true, true, true>(grid, s, a);
+        else if (a.Dm)  launch_dense_k<WT, BM, BN, BK, PF, WS, WR, WC, true, true, true>(grid, s, a);
+        else            launch_dense_k<WT, BM, BN, BK, PF, WS, WR, WC, false, true, true>(grid, s, a);
         return;
       }
     }
-    if (a.Dm) launch_dense_k<WT, BM, BN, BK, PF, WS, WR, WC, true, true>(grid, s, a);
-    else      launch_dense_k<WT, BM, BN, BK, PF, WS, WR, WC, false, true>(grid, s, a);
+    if (a.Dm && wn) launch_dense_k<WT, BM, BN, BK, PF, WS, WR, WC, true, true, false, true>(grid, s, a);
+    else if (a.Dm)  launch_dense_k<WT, BM, BN, BK, PF, WS, WR, WC, true, true>(grid, s, a);
+    else            launch_dense_k<WT, BM, BN, BK, PF, WS, WR, WC, false, true>(grid, s, a);
   } else {
-    launch_dense_k<WT, BM, BN, BK, PF, WS, WR, WC, true, false>(grid, s, a);
+    if (wn) launch_dense_k<WT, BM, BN, BK, PF, WS, WR, WC, true, false, false, true>(grid, s, a);
+    else    launch_dense_k<WT, BM, BN, BK, PF, WS, WR, WC, true, false>(grid, s, a);
   }
 }
 template <typename WT, int BM, int BN, int BK, int PF, int WR = 2, int WC = 2>
