@@ -40,10 +40,10 @@ PROFILE_ROW = {
     "conv_step_kernel<bf16>": r"conv_step_kernel<__bf16,",
     "dense_sweep_kernel<float>": r"dense_sweep_kernel<float,",
     "dense_sweep_kernel<bf16>": r"dense_sweep_kernel<__bf16,",
-    "dense_ksplit_kernel<float,8>": r"dense_ksplit_kernel<float, (?:false|true), 8>",
-    "dense_ksplit_kernel<float,4>": r"dense_ksplit_kernel<float, (?:false|true), 4>",
-    "dense_ksplit_kernel<bf16,4>": r"dense_ksplit_kernel<__bf16, (?:false|true), 4>",
-    "dense_ksplit_kernel<bf16,8>": r"dense_ksplit_kernel<__bf16, (?:false|true), 8>",
+    "dense_ksplit_kernel<float,8>": r"dense_ksplit_kernel<float, (?:false|true), 8[,>]",
+    "dense_ksplit_kernel<float,4>": r"dense_ksplit_kernel<float, (?:false|true), 4[,>]",
+    "dense_ksplit_kernel<bf16,4>": r"dense_ksplit_kernel<__bf16, (?:false|true), 4[,>]",
+    "dense_ksplit_kernel<bf16,8>": r"dense_ksplit_kernel<__bf16, (?:false|true), 8[,>]",
     "conv_sweep_kernel": r"conv_sweep_kernel",
 }
 

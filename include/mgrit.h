@@ -37,6 +37,9 @@
  * wavefronts per workgroup, as for narrower layers, instead of eight.
  * MGRIT_CONV_GENERIC=1 keeps bf16 convolution layers of 64 channels on the kernel that takes the channel count at
  * run time instead of the one compiled for 64.
+ * MGRIT_ADJ_TRANSPOSED=1 runs the adjoint of dense and fully connected layers on transposed copies of their
+ * weights, made in the workspace at every call, instead of reading the caller's arrays along their slow index;
+ * the workspace queries then include those copies, so set it before the query as well as before the call.
  *
  * Layouts (all row-major, last index fastest):
  *   dense: state [B][q] float;  W [N][q_out][q_in];  b [N][q] float

@@ -15,6 +15,12 @@ namespace {
 
 constexpr size_t ALIGN = 256;
 inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+// MGRIT_ADJ_TRANSPOSED=1 in the environment: the adjoint of dense and fully connected layers runs on a transposed
+// copy of the weights in the workspace (diagnostic; by default the kernels read the caller's array k-major)
+inline bool adjoint_transposed_copy() {
+  const char* e = getenv("MGRIT_ADJ_TRANSPOSED");
+  return e && e[0] == '1';
+}
 inline bool aligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) % ALIGN) == 0; }
 
 // The fused F-relaxation sweep (one launch per sweep instead of one per step) can be switched off with
@@ -129,13 +135,17 @@ int make_plan(const mgrit_problem_t* p, Plan* pl, int fcP = 0) {
   pl->off_partial = off; off = align_up(off + np * 4);
   pl->off_hist = off; off = align_up(off + (size_t)(p->max_iter + 1) * 8);
   pl->bytes_fwd = off;
-  pl->off_Wt = off; off = align_up(off + (size_t)p->N * pl->wsize * pl->esize);
+  // transposed weights of the adjoint: convolution layers always; dense layers only on request (their kernels
+  // read the caller's array k-major)
+  const bool wcopy = p->layer != MGRIT_LAYER_DENSE || adjoint_transposed_copy();
+  pl->off_Wt = off;
+  if (wcopy) off = align_up(off + (size_t)p->N * pl->wsize * pl->esize);
   pl->off_D = off; off = align_up(off + (size_t)p->N * pl->E * pl->esize);   // act' cache, in the weights' type
   pl->off_gpart = off;                 // partial sums of the conv parameter gradient when layers are split
   if (p->layer == MGRIT_LAYER_CONV3X3)
     off = align_up(off + conv_grad_partial_bytes(p->B, p->Himg, p->Wimg, p->C, p->dtype, p->N));
   pl->off_Wfct = off;
-  if (fcP) off = align_up(off + (size_t)pl->nfc * pl->wsize_fc * pl->esize);
+  if (fcP && adjoint_transposed_copy()) off = align_up(off + (size_t)pl->nfc * pl->wsize_fc * pl->esize);
   pl->bytes_adj = off;
   return MGRIT_OK;
 }
@@ -155,7 +165,7 @@ struct Solver {
   float* R[MGRIT_MAX_LEVELS];
   bool plain_rhs = false;              // nested start: every level carries the right-hand side (first, 0, .., 0)
   const void* W;
-  const void* Wu = nullptr;            // adjoint of dense layers: the caller's weights as stored (W above is the transposed copy)
+  int wn = 0, wn_fc = 0;               // adjoint on the caller's dense / fully connected weights as stored: W[k][n]
   const float* bias;
   const float* Dm;
   const void* Wfc = nullptr;           // fully connected layers of a mixed stack (their transposes in the adjoint)
@@ -179,7 +189,7 @@ struct Solver {
   StepArgs base_args(int l, long long js0, long long jstride) const {
     StepArgs a;
     memset(&a, 0, sizeof(a));
-    a.W = W; a.Wu = Wu; a.bias = bias; a.wm = layer_map(l, js0, jstride);
+    a.W = W; a.wn = wn; a.bias = bias; a.wm = layer_map(l, js0, jstride);
     a.Dm = Dm; a.dm = a.wm;
     a.sp = 1.0f; a.hs = pl.hl[l]; a.mode = MODE_PHI; a.act = act;
     a.M = pl.M; a.Nf = pl.Nf; a.K = pl.K; a.Himg = p->Himg; a.Wimg = p->Wimg; a.TH = pl.TH;
@@ -213,7 +223,7 @@ struct Solver {
     StepArgs d = a;
     d.xm = sub(a.xm); d.dm = sub(a.dm); d.om = sub(a.om); d.e1m = sub(a.e1m); d.e2m = sub(a.e2m);
     d.wm = PtMap{(a.wm.base + g0 * a.wm.stride) / pl.fcP, a.wm.stride * per / pl.fcP};
-    d.W = Wfc; d.Wu = nullptr; d.bias = a.bias ? bfc : nullptr;
+    d.W = Wfc; d.wn = wn_fc; d.bias = a.bias ? bfc : nullptr;
     d.M = pl.B; d.Nf = (int)pl.dfc; d.K = (int)pl.dfc; d.Himg = 0; d.Wimg = 0; d.TH = 0;
     d.wsize = pl.wsize_fc;
     d.wstream = (double)pl.nfc * (double)pl.wsize_fc * (double)pl.esize > 128.0 * 1024.0 * 1024.0 ? 1 : 0;
@@ -275,7 +285,7 @@ struct Solver {
       a.S = X[l]; a.sm = pm(l, 0, p->m);
       a.X = X[l]; a.xb = unit.base; a.xs = unit.stride * p->m; a.xk = unit.stride;
       if (g[l] && !plain_rhs) { a.G = g[l]; a.gb = 0; a.gs = p->m; }
-      a.W = W; a.bias = bias; a.Dm = Dm;
+      a.W = W; a.wn = wn; a.bias = bias; a.Dm = Dm;
       if (adjoint) { a.lb = p->N - mp;           a.ls = -(long long)p->m * mp; a.lk = -mp; }
       else         { a.lb = 0;                   a.ls = (long long)p->m * mp;  a.lk = mp; }
       a.hs = pl.hl[l]; a.act = act; a.nsteps = p->m - 1; a.nchains = Nc;
@@ -480,9 +490,12 @@ int adjoint_impl(const mgrit_problem_t* p, const mgrit_fc_layers_t* fc, const vo
   void* Wt = ws + pl.off_Wt;
   void* Wfct = ws + pl.off_Wfct;
   float* D = reinterpret_cast<float*>(ws + pl.off_D);
-  // transposed parameters, and act'(A_n U^n + b_n) for every layer in one grouped launch
-  sv.chk(launch_transpose_weights(W, Wt, p->layer, p->dtype, p->N, pl.Nf, sv.s));
-  if (fc) sv.chk(launch_transpose_weights(fc->Wfc, Wfct, MGRIT_LAYER_DENSE, p->dtype, pl.nfc, (int)pl.dfc, sv.s));
+  // transposed parameters (convolution layers, whose taps are mirrored as well; dense and fully connected
+  // matrices only on request), and act'(A_n U^n + b_n) for every layer in one grouped launch
+  const bool copy_dense = adjoint_transposed_copy();
+  const bool copy_main = p->layer != MGRIT_LAYER_DENSE || copy_dense;
+  if (copy_main) sv.chk(launch_transpose_weights(W, Wt, p->layer, p->dtype, p->N, pl.Nf, sv.s));
+  if (fc && copy_dense) sv.chk(launch_transpose_weights(fc->Wfc, Wfct, MGRIT_LAYER_DENSE, p->dtype, pl.nfc, (int)pl.dfc, sv.s));
   {
     sv.W = W; sv.bias = b; sv.Dm = nullptr; sv.act = p->act;
     if (fc) { sv.Wfc = fc->Wfc; sv.bfc = fc->bfc; }
@@ -493,9 +506,12 @@ int adjoint_impl(const mgrit_problem_t* p, const mgrit_fc_layers_t* fc, const vo
     a.Out = D; a.om = PtMap{0, 1};
     sv.launch(a, p->N);
   }
-  sv.W = Wt; sv.bias = nullptr; sv.Dm = D; sv.act = ACT_IDENT;
-  sv.Wu = p->layer == MGRIT_LAYER_DENSE ? W : nullptr;
-  if (fc) { sv.Wfc = Wfct; sv.bfc = nullptr; }
+  sv.bias = nullptr; sv.Dm = D; sv.act = ACT_IDENT;
+  if (copy_main) sv.W = Wt; else { sv.W = W; sv.wn = 1; }
+  if (fc) {
+    sv.bfc = nullptr;
+    if (copy_dense) sv.Wfc = Wfct; else { sv.Wfc = fc->Wfc; sv.wn_fc = 1; }
+  }
   rc = run_solver(sv, lamN, resnorm_hist, iters_done);
   if (rc != MGRIT_OK && rc != MGRIT_ERR_NONFINITE) return rc;
   if (dW || db) {

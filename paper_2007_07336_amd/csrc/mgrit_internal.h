@@ -28,8 +28,8 @@ struct StepArgs {
   const float* Dm;  PtMap dm;      // optional elementwise multiplier of the matrix operand (the act' cache);
                                    // its storage type is the weights' type: float, or bf16 when dbf16 is set
   const void*  W;   PtMap wm;      // weights of layer wm(gi); element type = template parameter
-  const void*  Wu;                 // adjoint steps of dense layers: the caller's weights as stored, W[k][n], which the
-                                   // kernels that can read them k-major use instead of the transposed copy in W
+  int wn;                          // dense only, 1: W holds W[k][n] (contraction index slowest), as the adjoint reads the
+                                   // caller's weights without a transposed copy; 0: W[n][k].  Needs K == Nf and Dm.
   const float* bias;               // [layers][Nf] or null (same layer index as W)
   float* Out;       PtMap om;      // may be null when only the norm is wanted
   const float* E1;  PtMap e1m;  float c1;
@@ -123,6 +123,7 @@ struct SweepArgs {
   float* X;  long long xb, xs, xk;
   const float* G;  long long gb, gs;     // optional right-hand side (null: none)
   const void* W;  const float* bias;     // weights in the problem's type; bias may be null
+  int wn;                                // dense sweep, 1: W holds W[k][n] (the adjoint on the caller's weights)
   const void* Dm;                        // optional act' factors in the weights' type, [layers][E]
   long long lb, ls, lk;
   float hs;

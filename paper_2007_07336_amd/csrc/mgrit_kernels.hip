@@ -461,7 +461,7 @@ __global__ __launch_bounds__(64 * WR * WC, WR * WC == 8 ? 4 : (XR && WN) ? 2 : 1
   const long long layer = a.wm.base + gi * a.wm.stride;
   const float* Xp = a.X + (a.xm.base + gi * a.xm.stride) * a.E;
   const WT* Dp = HD && a.Dm ? reinterpret_cast<const WT*>(a.Dm) + (a.dm.base + gi * a.dm.stride) * a.E : nullptr;
-  const WT* Wp = reinterpret_cast<const WT*>(WN ? a.Wu : a.W) + layer * a.wsize;
+  const WT* Wp = reinterpret_cast<const WT*>(a.W) + layer * a.wsize;
   const int K = a.K;
   typedef typename DRaw<WT>::type DR;
 
@@ -711,6 +711,8 @@ __global__ __launch_bounds__(64 * WR * WC, WR * WC == 8 ? 4 : (XR && WN) ? 2 : 1
 // the k loop starts; the NW partial tiles are summed through LDS in a fixed order.  NW = 4, or 8 when the
 // launch has fewer workgroups than the chip has CUs: the time of such a launch is the number of pieces a
 // wavefront walks through times the memory latency.
+// WN: the weights are W[k][n] (the adjoint on the caller's array).  A piece is then KC / 2 rows of 32 columns
+// (128 or 64 bytes each), staged k-major with a row pitch of 36 elements and read with mma_step_wn's accesses.
 // ------------------------------------------------------------------------------------------
 template <typename WT> struct KsOp;
 template <> struct KsOp<float>  { static constexpr int KC = 64;  };   // a piece is KC / 2 values of k: 4 fragments x (4 k per lane group) x 2 groups
@@ -732,7 +734,7 @@ template <typename WT> constexpr size_t ksplit_smem(int nw) {
   return (size_t)nw * 2 * 32 * (KsOp<WT>::KC / 2 + Op<WT>::PAD) * sizeof(WT);
 }
 
-template <typename WT, bool WS, int NW>
+template <typename WT, bool WS, int NW, bool WN = false>
 __global__ __launch_bounds__(NW * 64) void dense_ksplit_kernel(StepArgs a) {
   static_assert(NW == 4 || NW == 8, "four or eight wavefronts");
   constexpr int KC = KsOp<WT>::KC;
@@ -770,7 +772,9 @@ __global__ __launch_bounds__(NW * 64) void dense_ksplit_kernel(StepArgs a) {
 
   // ---- k loop.  MFMA lane (c, g) feeds row m0+c of the state and row n0+c of the weights, KL consecutive k
   // at offset 2*KL*j + KL*g of the piece in fragment j
-  floatx16 acc = zero16();
+  floatx16 acc1[1][1];
+  floatx16& acc = acc1[0][0];
+  acc = zero16();
   {
     // pieces of KH = KC / 2 values of k (128 bytes of a weight row): two of them are in flight in two register
     // sets, so the loads of the next piece never wait for the current one to be consumed
@@ -784,6 +788,10 @@ __global__ __launch_bounds__(NW * 64) void dense_ksplit_kernel(StepArgs a) {
     WT* Wl = reinterpret_cast<WT*>(smem_raw) + wave * (2 * 32 * LST);
     WT* Al = Wl + 32 * LST;
     const int wrl = lane >> 3, wkc = (lane & 7) * VEC;          // weights: row 8 i + wrl
+    // WN: 32 / VEC lanes cover the 32 columns of a k row, 64 / (32 / VEC) rows per load instruction
+    constexpr int NLR = 32 / VEC, NRI = 64 / NLR, NPITCH = 36;
+    static_assert(!WN || (NRI * WI == KH && KH * NPITCH <= 32 * LST), "a k-major piece fills the same staging area");
+    const int nrl = lane / NLR, nnc = (lane % NLR) * VEC;       // k row NRI i + nrl, columns nnc .. + VEC - 1
     const int arl = lane / APR, akc = (lane % APR) * 4;         // state: row ARI i + arl
     uint4 wr[2][WI];
     float4 ar[2][AI];
@@ -793,10 +801,19 @@ __global__ __launch_bounds__(NW * 64) void dense_ksplit_kernel(StepArgs a) {
       wm = 0; am = 0;
 #pragma unroll
       for (int i = 0; i < WI; ++i) {
-        const int row = n0 + 8 * i + wrl, k = k0 + wkc;
-        const bool ok = row < a.Nf && k < K;         // K % 8 == 0: a 16-byte part is in or out as a whole
+        bool ok;
+        unsigned off;
+        if constexpr (WN) {
+          const int k = k0 + NRI * i + nrl, col = n0 + nnc;
+          ok = k < K && col < a.Nf;                  // Nf % 8 == 0: a 16-byte part is in or out as a whole
+          off = (unsigned)(k * a.Nf + col);
+        } else {
+          const int row = n0 + 8 * i + wrl, k = k0 + wkc;
+          ok = row < a.Nf && k < K;                  // K % 8 == 0: a 16-byte part is in or out as a whole
+          off = (unsigned)(row * K + k);
+        }
         wm |= ok ? (1u << i) : 0u;
-        w[i] = ld_weights<WS>(Wp + (ok ? (unsigned)(row * K + k) : 0u));
+        w[i] = ld_weights<WS>(Wp + (ok ? off : 0u));
       }
 #pragma unroll
       for (int i = 0; i < AI; ++i) {
@@ -816,7 +833,14 @@ __global__ __launch_bounds__(NW * 64) void dense_ksplit_kernel(StepArgs a) {
       for (int i = 0; i < WI; ++i) {
         uint4 v = w[i];
         if (!((wm >> i) & 1u)) v = make_uint4(0, 0, 0, 0);
-        *reinterpret_cast<uint4*>(&Wl[(8 * i + wrl) * LST + wkc]) = v;
+        if constexpr (!WN) {
+          *reinterpret_cast<uint4*>(&Wl[(8 * i + wrl) * LST + wkc]) = v;
+        } else if constexpr (BF) {                   // 72-byte rows: two 8-byte stores
+          uint2* q = reinterpret_cast<uint2*>(&Wl[(NRI * i + nrl) * NPITCH + nnc]);
+          q[0] = make_uint2(v.x, v.y); q[1] = make_uint2(v.z, v.w);
+        } else {
+          *reinterpret_cast<uint4*>(&Wl[(NRI * i + nrl) * NPITCH + nnc]) = v;
+        }
       }
 #pragma unroll
       for (int i = 0; i < AI; ++i) {
@@ -829,7 +853,15 @@ __global__ __launch_bounds__(NW * 64) void dense_ksplit_kernel(StepArgs a) {
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
-      for (int j = 0; j < 4; ++j) ks_piece(&Al[c * LST + 2 * KL * j + KL * g], &Wl[c * LST + 2 * KL * j + KL * g], acc);
+      for (int j = 0; j < 4; ++j) {
+        if constexpr (WN) {
+          const WT* ap[1] = {&Al[c * LST + 2 * KL * j]};
+          const int bcol[1] = {c};
+          mma_step_wn<1, 1>(ap, Wl + 2 * KL * j * NPITCH, NPITCH, bcol, acc1, g);
+        } else {
+          ks_piece(&Al[c * LST + 2 * KL * j + KL * g], &Wl[c * LST + 2 * KL * j + KL * g], acc);
+        }
+      }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -1303,15 +1335,9 @@ static bool dense_xr(const StepArgs& a) {
   if (e && e[0] == '1') return false;
   return a.K == a.Nf && a.mode != MODE_DACT;
 }
-// MGRIT_ADJ_TRANSPOSED=1: adjoint steps read the transposed weight copy although the caller's weights are at hand
-static bool use_untransposed(const StepArgs& a) {
-  if (!a.Wu) return false;
-  const char* e = getenv("MGRIT_ADJ_TRANSPOSED");
-  return !(e && e[0] == '1');
-}
 template <typename WT, int BM, int BN, int BK, int PF, bool WS, int WR = 2, int WC = 2>
 static void launch_dense_ws(dim3 grid, hipStream_t s, const StepArgs& a) {
-  const bool wn = use_untransposed(a);              // adjoint steps: they all carry the act' operand (HD)
+  const bool wn = a.wn != 0;                        // adjoint steps: they all carry the act' operand (HD)
   if (dense_full<WT, BM, BN, BK>(a)) {
     if constexpr (sizeof(WT) == 2 && BM == 128 && BN == 128 && BK == 64 && PF == 1 && WR == 2 && WC == 2) {
       if (dense_xr<WT, BM, BN, BK, PF>(a)) {
@@ -1337,7 +1363,12 @@ static void launch_dense(dim3 grid, hipStream_t s, const StepArgs& a) {
 template <typename WT, bool WS, int NW>
 static void launch_ksplit_nw(dim3 grid, hipStream_t s, const StepArgs& a) {
   constexpr size_t smem = ksplit_smem<WT>(NW);
-  static LdsOptIn opt;
+  static LdsOptIn opt, optn;
+  if (a.wn) {
+    if (!step_opt_in(optn, reinterpret_cast<const void*>(dense_ksplit_kernel<WT, WS, NW, true>), smem)) return;
+    hipLaunchKernelGGL((dense_ksplit_kernel<WT, WS, NW, true>), grid, dim3(NW * 64), smem, s, a);
+    return;
+  }
   if (!step_opt_in(opt, reinterpret_cast<const void*>(dense_ksplit_kernel<WT, WS, NW>), smem)) return;
   hipLaunchKernelGGL((dense_ksplit_kernel<WT, WS, NW>), grid, dim3(NW * 64), smem, s, a);
 }
@@ -1362,6 +1393,8 @@ static bool conv_fixed_channels(const StepArgs& a, int dtype) {
 
 hipError_t launch_step(const StepArgs& a_in, int layer_kind, int dtype, int groups, hipStream_t s) {
   if (groups <= 0) return hipSuccess;
+  // k-major weights: dense adjoint steps only (square matrix, act' operand present)
+  if (a_in.wn && (layer_kind != 0 || !a_in.Dm || a_in.K != a_in.Nf || a_in.mode != MODE_PHI)) return hipErrorInvalidValue;
   StepArgs a = a_in;
   a.tiles = step_grid_blocks(a, layer_kind, dtype, groups);
   const dim3 grid((unsigned)a.tiles * (unsigned)groups);
@@ -2317,13 +2350,16 @@ static hipError_t launch_conv_grad(const GradArgs& a, unsigned blocks, size_t sm
 // q = 32 * NBW * NWV.  Width 256 runs with eight wavefronts of one column block each: two per SIMD, so that one
 // wavefront's fragment reads and float4 passes hide behind the other's matrix instructions (four wavefronts of two
 // blocks left the matrix cores idle half of the time).
+// WN: the weights are W[k][n] (the adjoint sweep on the caller's array): a slab is BK rows of k, of which a wavefront
+// loads and stages its own columns, k-major with pitch Q + 4 (float) or Q + 16 (bf16) -- no larger than the n-major
+// slab -- and the fragments come from mma_step_wn.
 // ------------------------------------------------------------------------------------------
 constexpr int SWEEP_R = 32;
 template <typename WT> struct SweepOp;
 template <> struct SweepOp<float>  { static constexpr int BK = 32; };
 template <> struct SweepOp<__bf16> { static constexpr int BK = 64; };
 
-template <typename WT, int NBW, int PF, int NWV>
+template <typename WT, int NBW, int PF, int NWV, bool WN = false>
 __global__ __launch_bounds__(64 * NWV) void dense_sweep_kernel(SweepArgs a) {
   constexpr int NT = 64 * NWV;                  // shadows the file-wide 256: NWV wavefronts
   constexpr int R = SWEEP_R, BK = SweepOp<WT>::BK, VEC = Op<WT>::VEC, KSTEP = Op<WT>::KSTEP, PAD = Op<WT>::PAD;
@@ -2334,6 +2370,10 @@ __global__ __launch_bounds__(64 * NWV) void dense_sweep_kernel(SweepArgs a) {
   constexpr int BP = WROWS * PPR / 64;          // pieces per lane and slab
   constexpr int NSL = Q / BK;                   // slabs per layer
   static_assert(WROWS * PPR % 64 == 0 && R * Q4 % NT == 0, "slab and slice must divide over the lanes");
+  constexpr int QP = Q + (sizeof(WT) == 2 ? 16 : 4);    // k-major slab: row pitch
+  constexpr int PPN = WROWS / VEC;                      // ... and 16-byte pieces of a wavefront's columns per k row
+  constexpr int BUF = WN ? BK * QP : Q * ST;            // elements of one slab buffer
+  static_assert(BK * QP <= Q * ST, "the k-major slab fits the n-major one's buffer");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   float* S = reinterpret_cast<float*>(smem_raw);           // [R][Q] state slice
   WT* A = reinterpret_cast<WT*>(S + R * Q);                // [R][AST] operand of the current step
@@ -2355,18 +2395,28 @@ __global__ __launch_bounds__(64 * NWV) void dense_sweep_kernel(SweepArgs a) {
   const int total = a.nsteps * NSL;
   uint4 breg[PF][BP];
   auto load_slab = [&](uint4 (&br)[BP], int it) {
-    const WT* Wp = Wall + layer_of(it / NSL + 1) * a.wsize + (it % NSL) * BK;
+    const WT* Wp = Wall + layer_of(it / NSL + 1) * a.wsize + (it % NSL) * (WN ? BK * Q : BK);   // slab = k range
 #pragma unroll
     for (int i = 0; i < BP; ++i) {
-      const int p = lane + 64 * i, row = wave * WROWS + p / PPR, kc = (p % PPR) * VEC;
-      br[i] = ld_weights<false>(Wp + row * Q + kc);
+      if constexpr (WN) {
+        const int p = lane + 64 * i, kr = p / PPN, col = wave * WROWS + (p % PPN) * VEC;
+        br[i] = ld_weights<false>(Wp + kr * Q + col);
+      } else {
+        const int p = lane + 64 * i, row = wave * WROWS + p / PPR, kc = (p % PPR) * VEC;
+        br[i] = ld_weights<false>(Wp + row * Q + kc);
+      }
     }
   };
   auto store_slab = [&](const uint4 (&br)[BP], WT* dst) {
 #pragma unroll
     for (int i = 0; i < BP; ++i) {
-      const int p = lane + 64 * i, row = wave * WROWS + p / PPR, kc = (p % PPR) * VEC;
-      *reinterpret_cast<uint4*>(&dst[row * ST + kc]) = br[i];
+      if constexpr (WN) {
+        const int p = lane + 64 * i, kr = p / PPN, col = wave * WROWS + (p % PPN) * VEC;
+        *reinterpret_cast<uint4*>(&dst[kr * QP + col]) = br[i];
+      } else {
+        const int p = lane + 64 * i, row = wave * WROWS + p / PPR, kc = (p % PPR) * VEC;
+        *reinterpret_cast<uint4*>(&dst[row * ST + kc]) = br[i];
+      }
     }
   };
   // A wavefront loads, stages and multiplies only its own weight rows, so the slab pipeline needs no workgroup
@@ -2434,17 +2484,24 @@ __global__ __launch_bounds__(64 * NWV) void dense_sweep_kernel(SweepArgs a) {
         const int sl = sl0 + sidx, it = (k - 1) * NSL + sl;
         wave_sync();                                       // slab it of this wavefront is in LDS; slab it-1 consumed
         if (it + 1 < total) {                              // next slab (maybe the next layer's first) -> other buffer
-          store_slab(breg[(sidx + 1) % PF], Bs + ((sidx + 1) & 1) * (Q * ST));
+          store_slab(breg[(sidx + 1) % PF], Bs + ((sidx + 1) & 1) * BUF);
           if (it + 1 + PF < total) load_slab(breg[(sidx + 1) % PF], it + 1 + PF);
         }
-        const WT* Bcur = Bs + (sidx & 1) * (Q * ST);
+        const WT* Bcur = Bs + (sidx & 1) * BUF;
 #pragma unroll
         for (int ks = 0; ks < BK; ks += KSTEP) {
           const WT* ap[1] = {&A[c * AST + sl * BK + ks]};
-          const WT* bp[NBW];
+          if constexpr (WN) {
+            int bcol[NBW];
 #pragma unroll
-          for (int t = 0; t < NBW; ++t) bp[t] = &Bcur[((wave * NBW + t) * 32 + c) * ST + ks];
-          mma_step<1, NBW>(ap, bp, acc, g);
+            for (int t = 0; t < NBW; ++t) bcol[t] = (wave * NBW + t) * 32 + c;
+            mma_step_wn<1, NBW>(ap, Bcur + ks * QP, QP, bcol, acc, g);
+          } else {
+            const WT* bp[NBW];
+#pragma unroll
+            for (int t = 0; t < NBW; ++t) bp[t] = &Bcur[((wave * NBW + t) * 32 + c) * ST + ks];
+            mma_step<1, NBW>(ap, bp, acc, g);
+          }
         }
       }
     }
@@ -2453,7 +2510,8 @@ __global__ __launch_bounds__(64 * NWV) void dense_sweep_kernel(SweepArgs a) {
     // whole rows: new state to S and to global memory, and the next step's operand to A.
     __syncthreads();                                       // every wavefront is done with that buffer and with A
     constexpr int ZST = Q + 4;
-    float* Z = reinterpret_cast<float*>(Bs + ((NSL - 1) & 1) * (Q * ST));     // [R][ZST], fits: 144 Q >= 128 Q + 512 bytes
+    float* Z = reinterpret_cast<float*>(Bs + ((NSL - 1) & 1) * BUF);          // [R][ZST], fits: 128 Q + 512 bytes in either layout
+    static_assert((size_t)BUF * sizeof(WT) >= sizeof(float) * R * ZST, "the raw sums fit a slab buffer");
 #pragma unroll
     for (int t = 0; t < NBW; ++t)
 #pragma unroll
@@ -2511,19 +2569,22 @@ bool sweep_supported(int q, int dtype) {
 }
 int sweep_blocks(int M, int nchains) { return ((M + SWEEP_R - 1) / SWEEP_R) * nchains; }
 
-template <typename WT, int NBW, int NWV>
+template <typename WT, int NBW, int NWV, bool WN = false>
 static hipError_t launch_sweep_t(const SweepArgs& a, unsigned blocks, size_t smem, hipStream_t s) {
+  if constexpr (!WN) {
+    if (a.wn) return launch_sweep_t<WT, NBW, NWV, true>(a, blocks, smem, s);
+  }
   // weight slabs in flight in registers: as many as a layer has, at most 4 (eight measured no faster and
   // take 256 registers of a lane)
   constexpr int NSLABS = 32 * NBW * NWV / SweepOp<WT>::BK;
   constexpr int PF = NSLABS < 4 ? NSLABS : 4;
   static LdsOptIn opt;
   if (opt.need(smem)) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(dense_sweep_kernel<WT, NBW, PF, NWV>),
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(dense_sweep_kernel<WT, NBW, PF, NWV, WN>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL((dense_sweep_kernel<WT, NBW, PF, NWV>), dim3(blocks), dim3(64 * NWV), smem, s, a);
+  hipLaunchKernelGGL((dense_sweep_kernel<WT, NBW, PF, NWV, WN>), dim3(blocks), dim3(64 * NWV), smem, s, a);
   return hipGetLastError();
 }
 // MGRIT_SWEEP_WAVES=4 in the environment runs width 256 with four wavefronts of two column blocks (diagnostic)

@@ -173,6 +173,34 @@ def test_mixed_adjoint_and_gradient(wl):
         assert eW <= tol and eb <= tol, (n, eW, eb)
 
 
+AS_STORED_MIXED = [w for w in MIXED_CASES if w.name in (
+    "mixed_fp32_c16_6x5_N16_m2_L3_P4", "mixed_bf16_c64_4x4_N16_m4_L2_P8", "mixed_fp32_c32_8x8_N16_m2_L2_P2_d2048",
+    "mixed_fp32_c32_8x8_B20_N8_P2_d2048_deep_ksplit", "mixed_bf16_c64_8x8_B8_N4_P2_d4096_deep_ksplit")]
+
+
+@pytest.mark.parametrize("wl", AS_STORED_MIXED, ids=lambda w: w.name)
+def test_mixed_adjoint_fc_weights_as_stored_and_transposed_copy(wl, monkeypatch):
+    """The fully connected layers' adjoint reads the caller's matrices as stored; MGRIT_ADJ_TRANSPOSED=1 runs it on
+    transposed copies in the workspace instead.  Same arithmetic in the same order: equal bit for bit."""
+    _announce(wl.name)
+    data = I.generate(wl)
+    gp = GpuMixed(wl, data)
+    U, _, _ = gp.forward()
+    if wl.dtype == I.BF16 and wl.act == I.RELU:
+        U = I.round_to_bf16(U)
+    lamN = np.random.default_rng(9).standard_normal(wl.state_shape).astype(np.float32)
+    n_default = gp.M.mgrit_adjoint_workspace_bytes_mixed(gp.p, wl.fc_period)
+    res = gp.adjoint(U, lamN)
+    monkeypatch.setenv("MGRIT_ADJ_TRANSPOSED", "1")
+    n_copy = gp.M.mgrit_adjoint_workspace_bytes_mixed(gp.p, wl.fc_period)
+    ref = gp.adjoint(U, lamN)
+    monkeypatch.delenv("MGRIT_ADJ_TRANSPOSED")
+    assert n_copy - n_default >= data["Wfc"].size * (4 if wl.dtype == I.FP32 else 2)
+    for x, y in zip(res[:5], ref[:5]):
+        assert np.array_equal(x, y)
+    assert res[5] == ref[5] and res[6] == ref[6]
+
+
 # ------------------------------------------------------------------ the benchmark's mixed workload at full size
 def test_mixed_full_size_forward_elementwise():
     wl = I.mixed(2)

@@ -645,6 +645,47 @@ def test_dense_adjoint_fused_sweeps(wl, fused, monkeypatch):
     assert eL <= tol and eW <= tol and eb <= tol, (eL, eW, eb)
 
 
+# ------------------------------------------------------------------ the adjoint on the weights as stored
+# The adjoint of a dense layer contracts over the weights' slow index.  By default every dense kernel (tiled step in
+# its masked / whole-tile / kept-state forms, k-split step, fused sweep) reads the caller's W[k][n] as stored;
+# MGRIT_ADJ_TRANSPOSED=1 makes a transposed copy in the workspace and runs the forward kernels' reading on it.  The
+# arithmetic and its order are the same, so the two agree bit for bit (the default path is the one every other
+# adjoint test compares with the oracle), and the default workspace is smaller by the copy.
+AS_STORED_CASES = [w for w in ADJ_CASES if w.name in (
+    "adj_dense_fp32_q72_B37_N64_m4", "adj_dense_bf16_q136_B50_N64_m4", "adj_fp32_q512_B8_N16_m4",
+    "adj_dense_fp32_q2048_B20_N8_m2_deep_ksplit", "adj_dense_bf16_q4096_B32_N4_m2_deep_ksplit",
+    "adj_dense_bf16_q136_B50_N70_m4_trailing")] + WHOLE_TILE_CASES + [w for w in SWEEP_ADJ_CASES if w.name in (
+    "adj_sweep_fp32_q128_B37_N256_m4_L3", "adj_sweep_bf16_q256_B70_N192_m4_relu", "adj_sweep_fp32_q256_B100_N96_m3_F",
+    "adj_sweep_bf16_q128_B40_N1024_m4_L3_rhs")]
+
+
+@pytest.mark.parametrize("wl", AS_STORED_CASES, ids=lambda w: w.name)
+def test_dense_adjoint_weights_as_stored_and_transposed_copy(wl, monkeypatch):
+    import paper_2007_07336_amd as M
+    _announce(wl.name)
+    data = I.generate(wl)
+    gp = GpuProblem(wl, data)
+    rc, U, _, _ = gp.forward()
+    assert rc == 0
+    if wl.dtype == I.BF16 and wl.act == I.RELU:
+        U = I.round_to_bf16(U)
+    lamN = I.terminal_adjoint(wl, data, U[-1])
+    n_default = M.mgrit_adjoint_workspace_bytes(gp.p)
+    M.mgrit_trace_begin()
+    res = gp.adjoint(U, lamN)
+    tr = M.mgrit_trace_end()
+    monkeypatch.setenv("MGRIT_ADJ_TRANSPOSED", "1")
+    n_copy = M.mgrit_adjoint_workspace_bytes(gp.p)
+    ref = gp.adjoint(U, lamN)
+    monkeypatch.delenv("MGRIT_ADJ_TRANSPOSED")
+    wbytes = wl.N * wl.q * wl.q * (4 if wl.dtype == I.FP32 else 2)
+    assert 0 <= n_copy - n_default - wbytes < 4096, (n_copy, n_default, wbytes)
+    print(f"{wl.name}: workspace {n_default} / {n_copy} bytes; kernels {sorted(tr)}", flush=True)
+    for x, y in zip(res[:3], ref[:3]):
+        assert np.array_equal(x, y)
+    assert res[3] == ref[3] and res[4] == ref[4]
+
+
 # ------------------------------------------------------------------ fused sweeps of convolution layers
 CONV_SWEEP_CASES = [
     I.reduced(I.cfg3(2), name="csweep_fp32_c16_7x5_B8_N64_m4_L2_FCF", B=8, Himg=7, Wimg=5, N=64),
