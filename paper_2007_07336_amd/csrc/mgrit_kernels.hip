@@ -1643,7 +1643,9 @@ hipError_t launch_transpose_weights(const void* W, void* Wt, int layer_kind, int
 // stored batch-row-major in memory, i.e. with the contraction index slowest, so each thread
 // loads a 4 (rows) x 4 (columns) block with row-contiguous float4 loads, transposes it in
 // registers and writes 4 consecutive k per column to LDS, where the usual k-fastest fragments
-// are read.
+// are read.  The bias gradient db[n] = hs * (column sums of G) rides along: the tiles of the first tile
+// column add up the unrounded G values that pass through their threads (fixed order: a thread's rows in
+// sequence, then the eight threads of a column group by a butterfly).
 // ------------------------------------------------------------------------------------------
 template <typename OT>
 __global__ __launch_bounds__(NT) void dense_grad_kernel(GradArgs a) {
@@ -1664,7 +1666,7 @@ __global__ __launch_bounds__(NT) void dense_grad_kernel(GradArgs a) {
   const float* Up = a.U + (a.um.base + gi * a.um.stride) * a.E;
   const float* Lp = a.Lam + (a.lm.base + gi * a.lm.stride) * a.E;
   const OT* Dp = reinterpret_cast<const OT*>(a.Dm) + (a.dm.base + gi * a.dm.stride) * a.E;
-  float* dWp = a.dW + (long long)gi * a.wsize;
+  float* dWp = a.dW ? a.dW + (long long)gi * a.wsize : nullptr;
   typedef typename DRaw<OT>::type DR;
 
   const int rb = tid & 7, cb = tid >> 3;             // 4 batch rows x 4 columns per thread
@@ -1672,6 +1674,9 @@ __global__ __launch_bounds__(NT) void dense_grad_kernel(GradArgs a) {
   float4 lv[4], uv[4];
   DR dv[4];
   unsigned rmask = 0;
+  const bool bias = a.db != nullptr && n0 == 0;       // workgroup-uniform
+  if (!a.dW && !bias) return;                         // bias gradient alone: the first tile column does it, the same way
+  float gs[4] = {0.f, 0.f, 0.f, 0.f};                 // running column sums of G (columns m0 + 4 cb .. + 3)
   auto load_slab = [&](int r0) {
     rmask = 0;
 #pragma unroll
@@ -1696,6 +1701,10 @@ __global__ __launch_bounds__(NT) void dense_grad_kernel(GradArgs a) {
       gk[0][rr] = ga * dd.x * lv[rr].x; gk[1][rr] = ga * dd.y * lv[rr].y;
       gk[2][rr] = ga * dd.z * lv[rr].z; gk[3][rr] = ga * dd.w * lv[rr].w;
       uk[0][rr] = ub * uv[rr].x; uk[1][rr] = ub * uv[rr].y; uk[2][rr] = ub * uv[rr].z; uk[3][rr] = ub * uv[rr].w;
+    }
+    if (bias) {
+#pragma unroll
+      for (int cc = 0; cc < 4; ++cc) gs[cc] += (gk[cc][0] + gk[cc][1]) + (gk[cc][2] + gk[cc][3]);
     }
 #pragma unroll
     for (int cc = 0; cc < 4; ++cc) {
@@ -1727,6 +1736,17 @@ __global__ __launch_bounds__(NT) void dense_grad_kernel(GradArgs a) {
       mma_step<TM, TN>(ap, bp, acc, g);
     }
   }
+  if (bias) {                                         // the eight threads rb = 0..7 of a column group are neighbouring lanes
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc) {
+      gs[cc] += __shfl_xor(gs[cc], 1);
+      gs[cc] += __shfl_xor(gs[cc], 2);
+      gs[cc] += __shfl_xor(gs[cc], 4);
+    }
+    if (rb == 0 && aok)
+      *reinterpret_cast<float4*>(a.db + (long long)gi * q + m0 + 4 * cb) =
+          make_float4(a.hs * gs[0], a.hs * gs[1], a.hs * gs[2], a.hs * gs[3]);
+  }
   // output through LDS so that a lane stores a float4 and 16 lanes a whole 256-byte row segment
   __syncthreads();
   float* stage = reinterpret_cast<float*>(lds_raw) + wave * 32 * SW;
@@ -1744,7 +1764,7 @@ __global__ __launch_bounds__(NT) void dense_grad_kernel(GradArgs a) {
       const int row = m0 + wm0 + i * 32 + rl;
       float4 z = *reinterpret_cast<const float4*>(&stage[rl * SW + colq]);
       z.x *= a.hs; z.y *= a.hs; z.z *= a.hs; z.w *= a.hs;
-      if (row < q && col < q) *reinterpret_cast<float4*>(dWp + (long long)row * q + col) = z;
+      if (a.dW && row < q && col < q) *reinterpret_cast<float4*>(dWp + (long long)row * q + col) = z;
     }
   }
 }
@@ -2881,10 +2901,11 @@ hipError_t launch_grad(const GradArgs& a_in, int layer_kind, int dtype, int grou
     db_done = true;
   } else if (layer_kind == 0) {
     a.tiles = ((a.Nf + 127) / 128) * ((a.Nf + 127) / 128);
-    if (a.dW) {
+    if (a.dW || a.db) {                                    // the bias gradient, if wanted, in the same launch
       dim3 grid((unsigned)a.tiles * (unsigned)groups);
       if (dtype == 0) hipLaunchKernelGGL((dense_grad_kernel<float>), grid, dim3(NT), 0, s, a);
       else            hipLaunchKernelGGL((dense_grad_kernel<__bf16>), grid, dim3(NT), 0, s, a);
+      db_done = true;
     }
   } else if (a.dW || a.db) {
     const ConvGradGeom gm = conv_grad_geom(a.B, a.Himg, a.Wimg, a.Nf, dtype, groups);
