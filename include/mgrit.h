@@ -28,7 +28,7 @@
  * F-relaxation sweep into one launch (dense layers of width 128 or 256, or float convolution layers of at
  * most 16 channels on images of at most 832 pixels, with many coarse intervals).  MGRIT_SWEEP_WAVES=4 runs
  * the fused sweep of width 256 with four instead of eight wavefronts.  MGRIT_GRAD_NARROW=1 keeps the
- * parameter gradient of dense layers of width 512 and more on 128x128 tiles with a separate bias pass.
+ * parameter gradient of dense layers of width 512 and more on the 128x128 tiles of narrower layers.
  * MGRIT_MASKED_STEP=1 sends dense layer steps whose batch, width and contraction length are whole multiples of
  * the tile through the bounds-masked loop that ragged shapes use.
  * MGRIT_STEP_REREAD=1 makes the epilogue of the bf16 128x128 dense tile read the state for the skip connection
